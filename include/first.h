@@ -1,0 +1,174 @@
+/*
+ * first.h -- C ABI of the MI355X (gfx950) implementation of FiRST's inference hot path:
+ * router-gated prefill and autoregressive decode of a Llama-style decoder.
+ *
+ * Method (paper sections in parentheses):
+ *   - every decoder layer i has a router R_i: a bias-free linear map D->1 applied to each
+ *     token of the stream entering the layer, a sigmoid per token and a mean over the
+ *     sequence, giving rho_i in [0,1] per sequence (Section 4.1);
+ *   - the layer is kept iff rho_i >= 0.5; a skipped layer passes the hidden state of its
+ *     nearest kept ancestor through unchanged (Section 3, Eq. 2 and its rounded form);
+ *   - prefill never skips, so the first generated token is the full model's, and the
+ *     decisions taken in prefill are cached and followed by every decode token, so a kept
+ *     layer always holds KV for all earlier positions and a skipped layer needs none
+ *     (Section 4.3, items 1 and 2).
+ *
+ * Conventions
+ *   - "DEV" pointers are device (HBM) addresses, "HOST" pointers are host addresses.
+ *   - All matrices are row-major [out_features, in_features]; bf16 is the raw upper half
+ *     of an IEEE fp32; the residual stream, router, logits and all accumulation are fp32.
+ *   - The caller owns weights, token buffers and every output buffer; weights are borrowed
+ *     for the life of the context.  The library owns the paged KV cache, page tables, the
+ *     mask / kept-index store, workspaces and cached hipGraphs.
+ *   - All device work is enqueued on the hipStream_t given at creation and is asynchronous
+ *     with respect to the host unless stated.  One context per stream; not re-entrant.
+ *   - Every entry point returns FIRST_OK (0) or a negative error code and never throws or
+ *     aborts; on an argument/state/capacity error nothing has been enqueued and no output
+ *     is written.  first_last_error() gives the text of the last failure.
+ */
+#ifndef FIRST_H_
+#define FIRST_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FIRST_OK            0
+#define FIRST_ERR_ARG      -1   /* null / out-of-range / misaligned argument               */
+#define FIRST_ERR_STATE    -2   /* call not legal in the current state of the sequence(s)  */
+#define FIRST_ERR_CAPACITY -3   /* batch, sequence length or KV pages exceed the context   */
+#define FIRST_ERR_HIP      -4   /* a HIP runtime call failed (text in first_last_error)    */
+
+#define FIRST_DTYPE_FP32 0
+#define FIRST_DTYPE_BF16 1
+
+/* options for first_set_option */
+#define FIRST_OPT_USE_GRAPH     1  /* 1 (default): replay a cached hipGraph per mask; 0: eager launches */
+#define FIRST_OPT_ATTN_SPLITS   2  /* KV splits per (sequence, KV head) in decode attention; 0 = auto   */
+#define FIRST_OPT_DECODE_PATH   3  /* 0: one kernel per fused op; 1: one persistent kernel per step     */
+
+typedef struct first_ctx first_ctx;
+
+/* Geometry of the decoder.  POD, filled by the caller. */
+typedef struct first_model_desc {
+  int32_t n_layers;       /* L (m in the paper)                                            */
+  int32_t d_model;        /* D, multiple of 8                                              */
+  int32_t n_q_heads;      /* Hq, multiple of n_kv_heads                                    */
+  int32_t n_kv_heads;     /* Hkv                                                           */
+  int32_t head_dim;       /* 64 or 128                                                     */
+  int32_t d_ffn;          /* F, multiple of 8                                              */
+  int32_t vocab;          /* V                                                             */
+  int32_t dtype;          /* FIRST_DTYPE_*: storage type of the weights and of the KV cache */
+  float   rope_base;      /* rotate-half RoPE, theta_d = base^(-2d/head_dim)               */
+  float   rms_eps;        /* RMSNorm epsilon                                               */
+  int32_t kv_page_tokens; /* tokens per KV page (16)                                       */
+  int32_t max_batch;      /* sequences the context can hold at once                        */
+  int32_t max_seq_len;    /* prompt + generated tokens per sequence                        */
+} first_model_desc;
+
+/* Weights.  The struct and the per-layer pointer arrays are HOST memory (copied at create);
+ * every pointer inside is DEV memory of the model's dtype except where marked fp32. */
+typedef struct first_weights {
+  const void *embed;               /* [V, D]                                               */
+  const void *lm_head;             /* [V, D], untied                                       */
+  const float *final_norm;         /* [D] fp32 gains                                       */
+  const float *const *attn_norm;   /* [L] -> [D] fp32                                      */
+  const void *const *wq;           /* [L] -> [Hq*hd, D]                                    */
+  const void *const *wk;           /* [L] -> [Hkv*hd, D]                                   */
+  const void *const *wv;           /* [L] -> [Hkv*hd, D]                                   */
+  const void *const *wo;           /* [L] -> [D, Hq*hd]                                    */
+  const float *const *mlp_norm;    /* [L] -> [D] fp32                                      */
+  const void *const *w_gate;       /* [L] -> [F, D]                                        */
+  const void *const *w_up;         /* [L] -> [F, D]                                        */
+  const void *const *w_down;       /* [L] -> [D, F]                                        */
+  const float *router;             /* [L, D] fp32, no bias (Section 4.1)                   */
+} first_weights;
+
+/* Creates a context: validates the geometry, allocates the KV page pool
+ * (max_batch * ceil(max_seq_len / kv_page_tokens) pages per layer), page tables and
+ * workspaces.  hip_stream is a hipStream_t; NULL makes the context create a private stream
+ * that keeps the null stream's implicit ordering (graphs cannot be captured on the null
+ * stream itself). */
+int first_create(const first_model_desc *desc, const first_weights *weights, void *hip_stream,
+                 first_ctx **out);
+int first_destroy(first_ctx *ctx);
+
+/* Prefill and route (Section 4.1, Section 4.3 item 1).  Drops any earlier sequences, then
+ * for each of the B prompts runs ALL layers (no skipping), fills the KV cache of every
+ * layer, evaluates router i on the stream entering layer i, fixes mask[b][i] =
+ * (rho >= 0.5), compacts the kept-layer indices, and produces the first token from the
+ * full model.  Synchronises the stream before returning (the masks are needed on the host).
+ *   ids        DEV  int32 [sum(lens)]  prompts packed back to back
+ *   lens       HOST int32 [B]          1 <= lens[b] < max_seq_len
+ *   rho_out    DEV  fp32  [B, L]       router probabilities           (may be NULL)
+ *   mask_out   DEV  uint8 [B, L]       1 = keep                       (may be NULL)
+ *   hidden_out DEV  fp32  [B, D]       H_L of the last prompt token   (may be NULL)
+ *   logits_out DEV  fp32  [B, V]       first-token logits             (may be NULL)
+ *   token_out  DEV  int32 [B]          greedy first token, lowest index on ties (may be NULL) */
+int first_prefill_route(first_ctx *ctx, int32_t B, const int32_t *ids, const int32_t *lens,
+                        float *rho_out, uint8_t *mask_out, float *hidden_out,
+                        float *logits_out, int32_t *token_out);
+
+/* Benchmark override of the cached decisions of one sequence (this is how random-skip and
+ * fixed-interval baselines of Section 5 are fed in).  Legal after prefill; once the
+ * sequence has decoded a token only bits may be cleared, since re-enabling a layer would
+ * leave holes in its KV (Section 4.3 item 2) -> FIRST_ERR_STATE.  mask: HOST uint8 [L]. */
+int first_set_mask(first_ctx *ctx, int32_t seq, const uint8_t *mask);
+
+/* Kept-layer indices of one sequence, ascending, as compacted on the device.
+ * kept_idx HOST int32 [L], n_kept HOST int32 [1].  Synchronises the stream. */
+int first_get_kept(first_ctx *ctx, int32_t seq, int32_t *kept_idx, int32_t *n_kept);
+
+/* One decode token for every live sequence (Section 4.3 item 2; Section 3 rounded form):
+ * h = E[token]; for each kept layer: RMSNorm, QKV, RoPE, KV append at position len[b],
+ * GQA attention over positions 0..len[b], O projection, SwiGLU MLP; skipped layers are not
+ * launched, leave h bit-identical and never touch their KV; then final norm, LM head and
+ * greedy argmax.  len[b] grows by one.
+ *   last_tokens DEV int32 [B]; logits_out DEV fp32 [B, V] (may be NULL); token_out DEV int32 [B].
+ * FIRST_ERR_STATE before prefill, FIRST_ERR_CAPACITY when a sequence is full. */
+int first_decode_step(first_ctx *ctx, const int32_t *last_tokens, float *logits_out,
+                      int32_t *token_out);
+
+int first_set_option(first_ctx *ctx, int32_t option, int32_t value);
+int first_sync(first_ctx *ctx);                          /* hipStreamSynchronize of the stream */
+const char *first_last_error(const first_ctx *ctx);      /* ctx may be NULL: last create error */
+
+/* ---- inspection taps used by the parity tests (synchronise the stream) ------------------ */
+
+/* Current length (prompt + decoded tokens) of a sequence and its number of live sequences. */
+int first_seq_len(first_ctx *ctx, int32_t seq, int32_t *len_out /*HOST*/);
+int first_batch(first_ctx *ctx, int32_t *batch_out /*HOST*/);
+
+/* Gathers / scatters positions [pos0, pos0+n) of one layer's KV of one sequence through the
+ * page table.  k, v: DEV fp32 [n, Hkv, hd] (values converted from / rounded to the KV type). */
+int first_kv_read(first_ctx *ctx, int32_t seq, int32_t layer, int32_t pos0, int32_t n,
+                  float *k_out, float *v_out);
+int first_kv_write(first_ctx *ctx, int32_t seq, int32_t layer, int32_t pos0, int32_t n,
+                   const float *k_in, const float *v_in);
+
+/* Residual stream after the last decode step (before the final norm).  DEV fp32 [B, D]. */
+int first_get_hidden(first_ctx *ctx, float *hidden_out);
+
+/* Order in which free KV pages are handed out: perm HOST int32 [n_pages] a permutation of
+ * 0..n_pages-1.  Legal only while no sequence is live.  n_pages via first_num_pages. */
+int first_set_page_order(first_ctx *ctx, const int32_t *perm);
+int first_num_pages(first_ctx *ctx, int32_t *n_pages_out /*HOST*/);
+
+/* ---- single fused ops, exposed for unit parity tests and kernel-level rooflines ---------- */
+
+/* y[r] = sum_k W[r,k] * x[k]  (+ y_in[r] if accumulate).  The decode projection kernel.
+ * W DEV [n, k] of dtype; x DEV fp32 [k]; y DEV fp32 [n]; k multiple of 8. */
+int first_op_gemv(void *hip_stream, int32_t dtype, const void *W, const float *x, float *y,
+                  int32_t n, int32_t k, int32_t accumulate);
+
+/* C[m,n] = sum_k A[m,k] * W[n,k]  (+ C if accumulate).  The prefill projection kernel
+ * (MFMA for bf16).  A DEV [m,k] and W DEV [n,k] of dtype, C DEV fp32 [m,n]; k multiple of 8. */
+int first_op_gemm_nt(void *hip_stream, int32_t dtype, const void *A, const void *W, float *C,
+                     int32_t m, int32_t n, int32_t k, int32_t accumulate);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIRST_H_ */

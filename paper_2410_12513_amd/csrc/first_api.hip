@@ -1,0 +1,631 @@
+// C ABI of the router-gated prefill/decode library (see include/first.h).
+// Host runtime: context, paged KV allocator, mask store, kept-index compaction, graph cache.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/first.h"
+#include "decode_kernels.h"
+#include "prefill_kernels.h"
+
+using namespace first;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct LayerPtrs {
+  const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+  const float *g_attn, *g_mlp;
+};
+
+}  // namespace
+
+struct first_ctx {
+  first_model_desc d{};
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  int num_cu = 256;
+  std::string err;
+  // weights (borrowed)
+  const void* embed = nullptr;
+  const void* lm_head = nullptr;
+  const float* g_final = nullptr;
+  const float* router = nullptr;
+  std::vector<LayerPtrs> layers;
+  // derived geometry
+  int nq = 0, nkv = 0, half = 0, G = 1, max_pages = 0, n_pages = 0;
+  size_t elem = 2, page_elems = 0;
+  // device state
+  std::vector<void*> allocs;
+  char* kv_pool = nullptr;
+  int *d_page_table = nullptr, *d_len = nullptr, *d_kept = nullptr, *d_nkept = nullptr;
+  uint8_t* d_mask = nullptr;
+  float* d_rho = nullptr;
+  double* d_theta = nullptr;
+  float *d_h = nullptr, *d_qkv = nullptr, *d_attn = nullptr, *d_z = nullptr, *d_part_o = nullptr, *d_part_ml = nullptr;
+  unsigned *d_attn_cnt = nullptr, *d_head_cnt = nullptr;
+  float2* d_rope_cs = nullptr;
+  Best* d_arg_part = nullptr;
+  // prefill workspace
+  float *p_H = nullptr, *p_q = nullptr, *p_k = nullptr, *p_v = nullptr, *p_g = nullptr, *p_u = nullptr, *p_sig = nullptr;
+  void *p_x = nullptr, *p_a = nullptr, *p_z = nullptr;
+  float2* p_cs = nullptr;
+  // host state
+  int B = 0;
+  std::vector<int> hlen;
+  std::vector<char> decoded;
+  std::vector<std::vector<uint8_t>> hmask;
+  std::vector<int> free_pages, page_order, h_page_table;
+  std::vector<int> seq_npages;
+  // options and graph cache
+  int use_graph = 1, attn_splits = 0, decode_path = 0;
+  std::map<std::string, hipGraphExec_t> graphs;
+};
+
+namespace {
+
+int fail(first_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                      \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail((c), FIRST_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));    \
+  } while (0)
+
+template <typename T>
+int dev_alloc(first_ctx* c, T** out, size_t count) {
+  void* p = nullptr;
+  HIPCHK(c, hipMalloc(&p, count * sizeof(T) + 256));
+  c->allocs.push_back(p);
+  *out = reinterpret_cast<T*>(p);
+  return FIRST_OK;
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
+// workgroups for a mat-vec over `rows` rows with R rows per wave iteration
+int gemv_grid(int rows, int R, int num_cu) {
+  const int need = (rows + WAVES * R - 1) / (WAVES * R);
+  return std::max(1, std::min(need, num_cu * 4));
+}
+
+void release_sequences(first_ctx* c) {
+  c->B = 0;
+  c->free_pages.assign(c->page_order.rbegin(), c->page_order.rend());   // pop_back hands out page_order[0] first
+  std::fill(c->seq_npages.begin(), c->seq_npages.end(), 0);
+  std::fill(c->decoded.begin(), c->decoded.end(), 0);
+}
+
+void drop_graphs(first_ctx* c) {
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  c->graphs.clear();
+}
+
+DecParams base_params(const first_ctx* c, int b, int S) {
+  DecParams p{};
+  const first_model_desc& d = c->d;
+  p.D = d.d_model; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.hd = d.head_dim; p.F = d.d_ffn; p.V = d.vocab;
+  p.G = c->G; p.P = d.kv_page_tokens; p.max_pages = c->max_pages; p.S = S;
+  p.eps = d.rms_eps; p.qscale = 1.0f / std::sqrt((float)d.head_dim);
+  p.b = b;
+  p.h = c->d_h; p.qkv = c->d_qkv; p.attn = c->d_attn; p.z = c->d_z;
+  p.part_o = c->d_part_o; p.part_ml = c->d_part_ml; p.attn_cnt = c->d_attn_cnt;
+  p.rope_cs = c->d_rope_cs; p.len = c->d_len; p.page_table = c->d_page_table; p.theta = c->d_theta;
+  p.embed = c->embed; p.lm_head = c->lm_head; p.g_final = c->g_final;
+  p.arg_part = c->d_arg_part; p.head_cnt = c->d_head_cnt;
+  p.page_elems = c->page_elems;
+  return p;
+}
+
+void set_layer(const first_ctx* c, DecParams& p, int i) {
+  const LayerPtrs& l = c->layers[i];
+  p.wq = l.wq; p.wk = l.wk; p.wv = l.wv; p.wo = l.wo; p.wg = l.wg; p.wu = l.wu; p.wd = l.wd;
+  p.g_attn = l.g_attn; p.g_mlp = l.g_mlp;
+  p.kv_layer = c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem;
+}
+
+template <typename WT>
+size_t attn_lds(const first_ctx* c) {
+  const size_t kpitch = (size_t)c->d.head_dim * sizeof(WT) + 4;
+  return ((size_t)c->G * c->d.head_dim + 2 * c->d.head_dim + 4) * sizeof(float) + 64 * kpitch +
+         64 * (size_t)c->d.head_dim * sizeof(WT);
+}
+
+// LM head of sequence p.b (also used for the first token after prefill); logits / token_out
+// are the [B, ...] base pointers.
+template <typename WT>
+void enqueue_head(first_ctx* c, DecParams p, float* logits, int* token_out, int advance) {
+  p.logits = logits; p.token_out = token_out; p.advance_len = advance;
+  const int grid = std::min(gemv_grid(c->d.vocab, 4, c->num_cu), ARG_MAX_WG);
+  const size_t lds = ((size_t)c->d.d_model + WAVES) * sizeof(float) + WAVES * sizeof(Best) + 16;
+  hipLaunchKernelGGL(k_head<WT>, dim3(grid), dim3(WG), lds, c->stream, p);
+}
+
+// One decode token for every live sequence, one kernel per fused op, kept layers only.
+template <typename WT>
+void enqueue_decode_ops(first_ctx* c, const int* tokens, float* logits, int* token_out, int S) {
+  const first_model_desc& d = c->d;
+  const size_t lds_d = ((size_t)d.d_model + WAVES) * sizeof(float);
+  const size_t lds_o = ((size_t)c->nq + WAVES) * sizeof(float);
+  const size_t lds_f = ((size_t)d.d_ffn + WAVES) * sizeof(float);
+  const int g_qkv = gemv_grid(c->nq + 2 * c->nkv, 4, c->num_cu);
+  const int g_o = gemv_grid(d.d_model, 4, c->num_cu);
+  const int g_gu = gemv_grid(2 * d.d_ffn, 4, c->num_cu);
+  for (int b = 0; b < c->B; ++b) {
+    DecParams p = base_params(c, b, S);
+    p.tokens = tokens;
+    hipLaunchKernelGGL(k_embed<WT>, dim3(1), dim3(WG), 0, c->stream, p);
+    for (int i = 0; i < d.n_layers; ++i) {
+      if (!c->hmask[b][i]) continue;            // skipped layer: no launch, no bytes
+      set_layer(c, p, i);
+      hipLaunchKernelGGL(k_qkv<WT>, dim3(g_qkv), dim3(WG), lds_d, c->stream, p);
+      hipLaunchKernelGGL(k_attn<WT>, dim3(S, d.n_kv_heads), dim3(WG), attn_lds<WT>(c), c->stream, p);
+      hipLaunchKernelGGL(k_oproj<WT>, dim3(g_o), dim3(WG), lds_o, c->stream, p);
+      hipLaunchKernelGGL(k_gateup<WT>, dim3(g_gu), dim3(WG), lds_d, c->stream, p);
+      hipLaunchKernelGGL(k_down<WT>, dim3(g_o), dim3(WG), lds_f, c->stream, p);
+    }
+    enqueue_head<WT>(c, p, logits, token_out, 1);
+  }
+}
+
+int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const void* W, float* C, int M, int N,
+                int K, int acc) {
+  if (dtype == FIRST_DTYPE_BF16) {
+    dim3 grid((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M);
+    hipLaunchKernelGGL(k_gemm_nt_bf16, grid, dim3(WG), 0, st, reinterpret_cast<const bf16*>(A),
+                       reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
+  } else {
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    hipLaunchKernelGGL(k_gemm_nt_f32, grid, dim3(WG), 0, st, reinterpret_cast<const float*>(A),
+                       reinterpret_cast<const float*>(W), C, M, N, K, acc);
+  }
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
+// Prefill of one sequence: T prompt tokens at ids, all layers, routers scored on the way.
+template <typename WT>
+int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, float* logits_out, int* token_out) {
+  const first_model_desc& d = c->d;
+  hipStream_t st = c->stream;
+  const int D = d.d_model, F = d.d_ffn, L = d.n_layers, hd = d.head_dim, P = d.kv_page_tokens;
+  const int* pt = c->d_page_table + (size_t)b * c->max_pages;
+  const int QB = std::max(1, 64 / c->G);
+  const float qscale = 1.0f / std::sqrt((float)hd);
+  const size_t kpitch = (size_t)hd * sizeof(WT) + 4;
+  const size_t lds_attn = (size_t)64 * hd * sizeof(float) + 64 * kpitch + (size_t)64 * hd * sizeof(WT);
+  WT* x = reinterpret_cast<WT*>(c->p_x);
+  WT* a = reinterpret_cast<WT*>(c->p_a);
+  WT* z = reinterpret_cast<WT*>(c->p_z);
+
+  hipLaunchKernelGGL(k_embed_rows<WT>, dim3(T), dim3(WG), 0, st, ids, reinterpret_cast<const WT*>(c->embed), c->p_H, D,
+                     d.vocab);
+  hipLaunchKernelGGL(k_rope_table, dim3((T * c->half + WG - 1) / WG), dim3(WG), 0, st, c->d_theta, c->p_cs, T, c->half);
+  for (int i = 0; i < L; ++i) {
+    const LayerPtrs& l = c->layers[i];
+    WT* pool = reinterpret_cast<WT*>(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem);
+    // router i reads the stream entering layer i, in the same pass as the attention norm
+    hipLaunchKernelGGL(k_rmsnorm_router<WT>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_attn,
+                       c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps);
+    hipLaunchKernelGGL(k_router_reduce, dim3(1), dim3(WG), 0, st, c->p_sig, T, c->d_rho + (size_t)b * L + i,
+                       c->d_mask + (size_t)b * L + i);
+    int rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wq, c->p_q, T, c->nq, D, 0))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wk, c->p_k, T, c->nkv, D, 0))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wv, c->p_v, T, c->nkv, D, 0))) return rc;
+    hipLaunchKernelGGL(k_rope_kvwrite<WT>, dim3(T), dim3(WG), 0, st, c->p_q, c->p_k, c->p_v, c->p_cs, pt, pool,
+                       c->page_elems, d.n_q_heads, d.n_kv_heads, hd, P, qscale);
+    hipLaunchKernelGGL((k_attn_prefill<WT, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
+                       pt, pool, c->page_elems, T, d.n_q_heads, d.n_kv_heads, hd, P, QB);
+    if ((rc = launch_gemm(c, st, d.dtype, a, l.wo, c->p_H, T, D, c->nq, 1))) return rc;
+    hipLaunchKernelGGL(k_rmsnorm_router<WT>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
+                       (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps);
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wg, c->p_g, T, F, D, 0))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wu, c->p_u, T, F, D, 0))) return rc;
+    hipLaunchKernelGGL(k_silu_mul<WT>, dim3(std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536)), dim3(WG), 0, st,
+                       c->p_g, c->p_u, z, (size_t)T * F);
+    if ((rc = launch_gemm(c, st, d.dtype, z, l.wd, c->p_H, T, D, F, 1))) return rc;
+  }
+  // last position -> decode residual slot of this sequence (+ optional copy out), first token
+  hipLaunchKernelGGL(k_copy_f32, dim3((D + WG - 1) / WG), dim3(WG), 0, st, c->p_H + (size_t)(T - 1) * D,
+                     c->d_h + (size_t)b * D, hidden_out ? hidden_out + (size_t)b * D : nullptr, D);
+  hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, st, c->d_len + b, T);
+  DecParams p = base_params(c, b, 1);
+  enqueue_head<WT>(c, p, logits_out, token_out, 0);
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
+int compact_masks(first_ctx* c) {
+  hipLaunchKernelGGL(k_compact, dim3(c->d.max_batch), dim3(64), 0, c->stream, c->d_mask, c->d.n_layers, c->d_kept,
+                     c->d_nkept);
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
+int alloc_page(first_ctx* c, int b) {
+  if (c->free_pages.empty() || c->seq_npages[b] >= c->max_pages) return -1;
+  const int pg = c->free_pages.back();
+  c->free_pages.pop_back();
+  c->h_page_table[(size_t)b * c->max_pages + c->seq_npages[b]] = pg;
+  return c->seq_npages[b]++;
+}
+
+}  // namespace
+
+extern "C" {
+
+int first_create(const first_model_desc* desc, const first_weights* w, void* hip_stream, first_ctx** out) {
+  if (!desc || !w || !out) return fail(nullptr, FIRST_ERR_ARG, "first_create: null argument");
+  const first_model_desc& d = *desc;
+  if (d.n_layers < 1 || d.d_model < 8 || d.d_model % 8 || d.n_q_heads < 1 || d.n_kv_heads < 1 ||
+      d.n_q_heads % d.n_kv_heads || d.n_q_heads / d.n_kv_heads > 8 || (d.head_dim != 64 && d.head_dim != 128) ||
+      d.d_ffn < 8 || d.d_ffn % 8 || d.vocab < 1 || (d.dtype != FIRST_DTYPE_FP32 && d.dtype != FIRST_DTYPE_BF16) ||
+      d.kv_page_tokens < 1 || d.max_batch < 1 || d.max_seq_len < 2 || !(d.rope_base > 0.f) || !(d.rms_eps >= 0.f))
+    return fail(nullptr, FIRST_ERR_ARG, "first_create: unsupported model geometry");
+  if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+      !w->mlp_norm || !w->w_gate || !w->w_up || !w->w_down || !w->router)
+    return fail(nullptr, FIRST_ERR_ARG, "first_create: null weight pointer");
+  first_ctx* c = new first_ctx();
+  c->d = d;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  if (!c->stream) {
+    // graphs cannot be captured on the null stream: use a private stream that keeps the
+    // null stream's implicit ordering (created without the non-blocking flag)
+    if (hipStreamCreateWithFlags(&c->stream, hipStreamDefault) != hipSuccess) {
+      delete c;
+      return fail(nullptr, FIRST_ERR_HIP, "first_create: hipStreamCreate failed");
+    }
+    c->own_stream = true;
+  }
+  c->num_cu = device_cus();
+  c->embed = w->embed; c->lm_head = w->lm_head; c->g_final = w->final_norm; c->router = w->router;
+  c->layers.resize(d.n_layers);
+  for (int i = 0; i < d.n_layers; ++i) {
+    LayerPtrs& l = c->layers[i];
+    l.wq = w->wq[i]; l.wk = w->wk[i]; l.wv = w->wv[i]; l.wo = w->wo[i];
+    l.wg = w->w_gate[i]; l.wu = w->w_up[i]; l.wd = w->w_down[i];
+    l.g_attn = w->attn_norm[i]; l.g_mlp = w->mlp_norm[i];
+    if (!l.wq || !l.wk || !l.wv || !l.wo || !l.wg || !l.wu || !l.wd || !l.g_attn || !l.g_mlp) {
+      if (c->own_stream) (void)hipStreamDestroy(c->stream);
+      delete c;
+      return fail(nullptr, FIRST_ERR_ARG, "first_create: null layer weight pointer");
+    }
+  }
+  c->nq = d.n_q_heads * d.head_dim; c->nkv = d.n_kv_heads * d.head_dim; c->half = d.head_dim / 2;
+  c->G = d.n_q_heads / d.n_kv_heads;
+  c->elem = d.dtype == FIRST_DTYPE_BF16 ? 2 : 4;
+  c->max_pages = (d.max_seq_len + d.kv_page_tokens - 1) / d.kv_page_tokens;
+  c->n_pages = c->max_pages * d.max_batch;
+  c->page_elems = (size_t)2 * d.n_kv_heads * d.kv_page_tokens * d.head_dim;
+
+  const int B = d.max_batch, L = d.n_layers, T = d.max_seq_len;
+  int rc = FIRST_OK;
+  auto A = [&](int r) { if (rc == FIRST_OK) rc = r; };
+  A(dev_alloc(c, &c->kv_pool, (size_t)L * c->n_pages * c->page_elems * c->elem));
+  A(dev_alloc(c, &c->d_page_table, (size_t)B * c->max_pages));
+  A(dev_alloc(c, &c->d_len, B)); A(dev_alloc(c, &c->d_kept, (size_t)B * L)); A(dev_alloc(c, &c->d_nkept, B));
+  A(dev_alloc(c, &c->d_mask, (size_t)B * L)); A(dev_alloc(c, &c->d_rho, (size_t)B * L));
+  A(dev_alloc(c, &c->d_theta, c->half));
+  A(dev_alloc(c, &c->d_h, (size_t)B * d.d_model)); A(dev_alloc(c, &c->d_qkv, (size_t)B * (c->nq + 2 * c->nkv)));
+  A(dev_alloc(c, &c->d_attn, (size_t)B * c->nq)); A(dev_alloc(c, &c->d_z, (size_t)B * d.d_ffn));
+  A(dev_alloc(c, &c->d_part_o, (size_t)B * d.n_q_heads * S_MAX * d.head_dim));
+  A(dev_alloc(c, &c->d_part_ml, (size_t)B * d.n_q_heads * S_MAX * 2));
+  A(dev_alloc(c, &c->d_attn_cnt, (size_t)B * d.n_kv_heads)); A(dev_alloc(c, &c->d_head_cnt, B));
+  A(dev_alloc(c, &c->d_rope_cs, (size_t)B * c->half)); A(dev_alloc(c, &c->d_arg_part, (size_t)B * ARG_MAX_WG));
+  A(dev_alloc(c, &c->p_H, (size_t)T * d.d_model)); A(dev_alloc(c, &c->p_q, (size_t)T * c->nq));
+  A(dev_alloc(c, &c->p_k, (size_t)T * c->nkv)); A(dev_alloc(c, &c->p_v, (size_t)T * c->nkv));
+  A(dev_alloc(c, &c->p_g, (size_t)T * d.d_ffn)); A(dev_alloc(c, &c->p_u, (size_t)T * d.d_ffn));
+  A(dev_alloc(c, &c->p_sig, T)); A(dev_alloc(c, &c->p_cs, (size_t)T * c->half));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * c->elem));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * c->elem));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * c->elem));
+  if (rc == FIRST_OK) {
+    std::vector<double> theta(c->half);
+    for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
+    hipError_t e = hipMemcpy(c->d_theta, theta.data(), c->half * sizeof(double), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(c->d_attn_cnt, 0, (size_t)B * d.n_kv_heads * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
+    if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
+    // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<bf16, bf16>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, float>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    if (e != hipSuccess) rc = fail(nullptr, FIRST_ERR_HIP, std::string("first_create: ") + hipGetErrorString(e));
+  } else {
+    g_create_error = c->err;
+  }
+  if (rc != FIRST_OK) {
+    for (void* p : c->allocs) (void)hipFree(p);
+    if (c->own_stream) (void)hipStreamDestroy(c->stream);
+    delete c;
+    return rc;
+  }
+  c->hlen.assign(B, 0); c->decoded.assign(B, 0); c->seq_npages.assign(B, 0);
+  c->hmask.assign(B, std::vector<uint8_t>(L, 0));
+  c->h_page_table.assign((size_t)B * c->max_pages, 0);
+  c->page_order.resize(c->n_pages);
+  for (int i = 0; i < c->n_pages; ++i) c->page_order[i] = i;
+  release_sequences(c);
+  *out = c;
+  return FIRST_OK;
+}
+
+int first_destroy(first_ctx* c) {
+  if (!c) return FIRST_ERR_ARG;
+  (void)hipStreamSynchronize(c->stream);
+  drop_graphs(c);
+  for (void* p : c->allocs) (void)hipFree(p);
+  if (c->own_stream) (void)hipStreamDestroy(c->stream);
+  delete c;
+  return FIRST_OK;
+}
+
+int first_prefill_route(first_ctx* c, int32_t B, const int32_t* ids, const int32_t* lens, float* rho_out,
+                        uint8_t* mask_out, float* hidden_out, float* logits_out, int32_t* token_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!ids || !lens) return fail(c, FIRST_ERR_ARG, "first_prefill_route: null ids/lens");
+  if (B < 1 || B > c->d.max_batch) return fail(c, FIRST_ERR_CAPACITY, "first_prefill_route: batch exceeds max_batch");
+  for (int b = 0; b < B; ++b) {
+    if (lens[b] < 1) return fail(c, FIRST_ERR_ARG, "first_prefill_route: empty prompt");
+    if (lens[b] >= c->d.max_seq_len)
+      return fail(c, FIRST_ERR_CAPACITY, "first_prefill_route: prompt does not leave room for a generated token");
+  }
+  const int L = c->d.n_layers, P = c->d.kv_page_tokens;
+  release_sequences(c);
+  drop_graphs(c);
+  // pages for every prompt, then one upload of the page tables
+  for (int b = 0; b < B; ++b)
+    for (int need = (lens[b] + P - 1) / P; c->seq_npages[b] < need;)
+      if (alloc_page(c, b) < 0) return fail(c, FIRST_ERR_CAPACITY, "first_prefill_route: out of KV pages");
+  HIPCHK(c, hipMemcpyAsync(c->d_page_table, c->h_page_table.data(), c->h_page_table.size() * sizeof(int),
+                           hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));     // the host table may now be edited again
+  size_t off = 0;
+  for (int b = 0; b < B; ++b) {
+    const int rc = c->d.dtype == FIRST_DTYPE_BF16
+                       ? prefill_one<bf16>(c, b, ids + off, lens[b], hidden_out, logits_out, token_out)
+                       : prefill_one<float>(c, b, ids + off, lens[b], hidden_out, logits_out, token_out);
+    if (rc) return rc;
+    off += lens[b];
+    c->hlen[b] = lens[b];
+  }
+  c->B = B;
+  int rc = compact_masks(c);
+  if (rc) return rc;
+  std::vector<uint8_t> hm((size_t)B * L);
+  HIPCHK(c, hipMemcpyAsync(hm.data(), c->d_mask, hm.size(), hipMemcpyDeviceToHost, c->stream));
+  if (rho_out) HIPCHK(c, hipMemcpyAsync(rho_out, c->d_rho, (size_t)B * L * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+  if (mask_out) HIPCHK(c, hipMemcpyAsync(mask_out, c->d_mask, (size_t)B * L, hipMemcpyDeviceToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int b = 0; b < B; ++b) c->hmask[b].assign(hm.begin() + (size_t)b * L, hm.begin() + (size_t)(b + 1) * L);
+  return FIRST_OK;
+}
+
+int first_set_mask(first_ctx* c, int32_t seq, const uint8_t* mask) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!mask) return fail(c, FIRST_ERR_ARG, "first_set_mask: null mask");
+  if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_set_mask: no such live sequence");
+  const int L = c->d.n_layers;
+  std::vector<uint8_t> m(L);
+  for (int i = 0; i < L; ++i) {
+    m[i] = mask[i] ? 1 : 0;
+    if (c->decoded[seq] && m[i] && !c->hmask[seq][i])
+      return fail(c, FIRST_ERR_STATE, "first_set_mask: layer was skipped by earlier decode tokens; its KV has holes");
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(c->d_mask + (size_t)seq * L, m.data(), L, hipMemcpyHostToDevice));
+  c->hmask[seq] = m;
+  return compact_masks(c);
+}
+
+int first_get_kept(first_ctx* c, int32_t seq, int32_t* kept_idx, int32_t* n_kept) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!kept_idx || !n_kept) return fail(c, FIRST_ERR_ARG, "first_get_kept: null output");
+  if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_get_kept: no such live sequence");
+  const int L = c->d.n_layers;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(kept_idx, c->d_kept + (size_t)seq * L, L * sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(n_kept, c->d_nkept + seq, sizeof(int), hipMemcpyDeviceToHost));
+  return FIRST_OK;
+}
+
+int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_out, int32_t* token_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!last_tokens) return fail(c, FIRST_ERR_ARG, "first_decode_step: null tokens");
+  if (c->B < 1) return fail(c, FIRST_ERR_STATE, "first_decode_step: no prefilled sequence");
+  const int P = c->d.kv_page_tokens;
+  int max_len = 0;
+  for (int b = 0; b < c->B; ++b) {
+    if (c->hlen[b] + 1 > c->d.max_seq_len) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: sequence is full");
+    max_len = std::max(max_len, c->hlen[b]);
+  }
+  // make sure the page that will receive position len[b] exists
+  for (int b = 0; b < c->B; ++b) {
+    if (c->hlen[b] / P >= c->seq_npages[b]) {
+      const int slot = alloc_page(c, b);
+      if (slot < 0) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: out of KV pages");
+      hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, c->stream, c->d_page_table + (size_t)b * c->max_pages + slot,
+                         c->h_page_table[(size_t)b * c->max_pages + slot]);
+    }
+  }
+  int S = c->attn_splits;
+  if (S <= 0) S = (max_len + 128 + 127) / 128;
+  S = std::max(1, std::min(S, 32));
+  const bool bf = c->d.dtype == FIRST_DTYPE_BF16;
+  if (!c->use_graph) {
+    if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
+    else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
+    HIPCHK(c, hipGetLastError());
+  } else {
+    std::string key(reinterpret_cast<const char*>(&S), sizeof(S));
+    key.append(reinterpret_cast<const char*>(&last_tokens), sizeof(void*));
+    key.append(reinterpret_cast<const char*>(&logits_out), sizeof(void*));
+    key.append(reinterpret_cast<const char*>(&token_out), sizeof(void*));
+    for (int b = 0; b < c->B; ++b) key.append(reinterpret_cast<const char*>(c->hmask[b].data()), c->hmask[b].size());
+    auto it = c->graphs.find(key);
+    if (it == c->graphs.end()) {
+      if (c->graphs.size() >= 32) drop_graphs(c);
+      hipGraph_t graph = nullptr;
+      hipGraphExec_t exec = nullptr;
+      HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+      if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
+      else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
+      HIPCHK(c, hipStreamEndCapture(c->stream, &graph));
+      HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+      (void)hipGraphDestroy(graph);
+      it = c->graphs.emplace(key, exec).first;
+    }
+    HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+  }
+  for (int b = 0; b < c->B; ++b) { c->hlen[b] += 1; c->decoded[b] = 1; }
+  return FIRST_OK;
+}
+
+int first_set_option(first_ctx* c, int32_t option, int32_t value) {
+  if (!c) return FIRST_ERR_ARG;
+  switch (option) {
+    case FIRST_OPT_USE_GRAPH: c->use_graph = value ? 1 : 0; return FIRST_OK;
+    case FIRST_OPT_ATTN_SPLITS:
+      if (value < 0 || value > S_MAX) return fail(c, FIRST_ERR_ARG, "first_set_option: splits out of range");
+      c->attn_splits = value; return FIRST_OK;
+    case FIRST_OPT_DECODE_PATH:
+      if (value != 0) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown decode path");
+      c->decode_path = value; return FIRST_OK;
+    default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
+  }
+}
+
+int first_sync(first_ctx* c) {
+  if (!c) return FIRST_ERR_ARG;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return FIRST_OK;
+}
+
+const char* first_last_error(const first_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int first_seq_len(first_ctx* c, int32_t seq, int32_t* len_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!len_out) return fail(c, FIRST_ERR_ARG, "first_seq_len: null output");
+  if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_seq_len: no such live sequence");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(len_out, c->d_len + seq, sizeof(int), hipMemcpyDeviceToHost));
+  return FIRST_OK;
+}
+
+int first_batch(first_ctx* c, int32_t* batch_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!batch_out) return fail(c, FIRST_ERR_ARG, "first_batch: null output");
+  *batch_out = c->B;
+  return FIRST_OK;
+}
+
+static int kv_tap(first_ctx* c, int seq, int layer, int pos0, int n, float* k, float* v, bool write) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!k || !v) return fail(c, FIRST_ERR_ARG, "first_kv: null buffer");
+  if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_kv: no such live sequence");
+  if (layer < 0 || layer >= c->d.n_layers || pos0 < 0 || n < 0 || pos0 + n > c->seq_npages[seq] * c->d.kv_page_tokens)
+    return fail(c, FIRST_ERR_ARG, "first_kv: range outside the sequence's pages");
+  if (n == 0) return FIRST_OK;
+  char* pool = c->kv_pool + (size_t)layer * c->n_pages * c->page_elems * c->elem;
+  const int* pt = c->d_page_table + (size_t)seq * c->max_pages;
+  const first_model_desc& d = c->d;
+  if (d.dtype == FIRST_DTYPE_BF16) {
+    if (write) hipLaunchKernelGGL((k_kv_tap<bf16, true>), dim3(n), dim3(WG), 0, c->stream, (bf16*)pool, c->page_elems, pt, pos0, d.n_kv_heads, d.head_dim, d.kv_page_tokens, k, v);
+    else hipLaunchKernelGGL((k_kv_tap<bf16, false>), dim3(n), dim3(WG), 0, c->stream, (bf16*)pool, c->page_elems, pt, pos0, d.n_kv_heads, d.head_dim, d.kv_page_tokens, k, v);
+  } else {
+    if (write) hipLaunchKernelGGL((k_kv_tap<float, true>), dim3(n), dim3(WG), 0, c->stream, (float*)pool, c->page_elems, pt, pos0, d.n_kv_heads, d.head_dim, d.kv_page_tokens, k, v);
+    else hipLaunchKernelGGL((k_kv_tap<float, false>), dim3(n), dim3(WG), 0, c->stream, (float*)pool, c->page_elems, pt, pos0, d.n_kv_heads, d.head_dim, d.kv_page_tokens, k, v);
+  }
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return FIRST_OK;
+}
+
+int first_kv_read(first_ctx* c, int32_t seq, int32_t layer, int32_t pos0, int32_t n, float* k_out, float* v_out) {
+  return kv_tap(c, seq, layer, pos0, n, k_out, v_out, false);
+}
+int first_kv_write(first_ctx* c, int32_t seq, int32_t layer, int32_t pos0, int32_t n, const float* k_in,
+                   const float* v_in) {
+  return kv_tap(c, seq, layer, pos0, n, const_cast<float*>(k_in), const_cast<float*>(v_in), true);
+}
+
+int first_get_hidden(first_ctx* c, float* hidden_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!hidden_out) return fail(c, FIRST_ERR_ARG, "first_get_hidden: null output");
+  if (c->B < 1) return fail(c, FIRST_ERR_STATE, "first_get_hidden: no live sequence");
+  HIPCHK(c, hipMemcpyAsync(hidden_out, c->d_h, (size_t)c->B * c->d.d_model * sizeof(float), hipMemcpyDeviceToDevice,
+                           c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return FIRST_OK;
+}
+
+int first_set_page_order(first_ctx* c, const int32_t* perm) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!perm) return fail(c, FIRST_ERR_ARG, "first_set_page_order: null permutation");
+  if (c->B != 0) return fail(c, FIRST_ERR_STATE, "first_set_page_order: sequences are live");
+  std::vector<char> seen(c->n_pages, 0);
+  for (int i = 0; i < c->n_pages; ++i) {
+    if (perm[i] < 0 || perm[i] >= c->n_pages || seen[perm[i]])
+      return fail(c, FIRST_ERR_ARG, "first_set_page_order: not a permutation");
+    seen[perm[i]] = 1;
+  }
+  c->page_order.assign(perm, perm + c->n_pages);
+  release_sequences(c);
+  return FIRST_OK;
+}
+
+int first_num_pages(first_ctx* c, int32_t* n_pages_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!n_pages_out) return fail(c, FIRST_ERR_ARG, "first_num_pages: null output");
+  *n_pages_out = c->n_pages;
+  return FIRST_OK;
+}
+
+int first_op_gemv(void* hip_stream, int32_t dtype, const void* W, const float* x, float* y, int32_t n, int32_t k,
+                  int32_t accumulate) {
+  if (!W || !x || !y || n < 1 || k < 8 || k % 8 || (size_t)k * sizeof(float) > 60 * 1024 ||
+      (dtype != FIRST_DTYPE_FP32 && dtype != FIRST_DTYPE_BF16))
+    return fail(nullptr, FIRST_ERR_ARG, "first_op_gemv: bad argument");
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int grid = gemv_grid(n, 4, device_cus());
+  const size_t lds = ((size_t)k + WAVES) * sizeof(float);
+  if (dtype == FIRST_DTYPE_BF16)
+    hipLaunchKernelGGL(k_gemv<bf16>, dim3(grid), dim3(WG), lds, st, reinterpret_cast<const bf16*>(W), x, y, n, k, accumulate);
+  else
+    hipLaunchKernelGGL(k_gemv<float>, dim3(grid), dim3(WG), lds, st, reinterpret_cast<const float*>(W), x, y, n, k, accumulate);
+  HIPCHK(nullptr, hipGetLastError());
+  return FIRST_OK;
+}
+
+int first_op_gemm_nt(void* hip_stream, int32_t dtype, const void* A, const void* W, float* C, int32_t m, int32_t n,
+                     int32_t k, int32_t accumulate) {
+  if (!A || !W || !C || m < 1 || n < 1 || k < 8 || k % 8 || (dtype != FIRST_DTYPE_FP32 && dtype != FIRST_DTYPE_BF16))
+    return fail(nullptr, FIRST_ERR_ARG, "first_op_gemm_nt: bad argument");
+  return launch_gemm(nullptr, reinterpret_cast<hipStream_t>(hip_stream), dtype, A, W, C, m, n, k, accumulate);
+}
+
+}  // extern "C"

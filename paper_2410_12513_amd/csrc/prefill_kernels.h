@@ -1,0 +1,391 @@
+// Prefill kernels: every layer runs on the whole prompt (Section 4.3 item 1), the routers
+// are scored on the stream entering each layer (Section 4.1), KV of all layers is written.
+#pragma once
+#include "common.h"
+
+namespace first {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+
+// H[t] = E[ids[t]] widened to fp32.  grid = T.
+template <typename WT>
+__global__ void __launch_bounds__(WG) k_embed_rows(const int* __restrict__ ids, const WT* __restrict__ E,
+                                                   float* __restrict__ H, int D, int V) {
+  const int t = blockIdx.x;
+  int tok = ids[t];
+  tok = min(max(tok, 0), V - 1);
+  const WT* row = E + (size_t)tok * D;
+  for (int k = threadIdx.x; k < D; k += WG) H[(size_t)t * D + k] = to_f32(row[k]);
+}
+
+// cs[t][i] = (cos, sin)(t * theta_i), angle formed in fp64.  grid covers T*half threads.
+__global__ void __launch_bounds__(WG) k_rope_table(const double* __restrict__ theta, float2* __restrict__ cs,
+                                                   int T, int half) {
+  const int i = blockIdx.x * WG + threadIdx.x;
+  if (i >= T * half) return;
+  const int t = i / half, d = i - t * half;
+  const double a = (double)t * theta[d];
+  cs[i] = make_float2((float)cos(a), (float)sin(a));
+}
+
+// One wave per token: x = RMSNorm(H[t]; gain) in the GEMM input type, and, if rw is given,
+// sig[t] = sigmoid(rw . H[t]) on the raw stream (router, Section 4.1).  grid = ceil(T/4).
+template <typename XT>
+__global__ void __launch_bounds__(WG) k_rmsnorm_router(const float* __restrict__ H, const float* __restrict__ gain,
+                                                       const float* __restrict__ rw, XT* __restrict__ x,
+                                                       float* __restrict__ sig, int T, int D, float eps) {
+  const int t = blockIdx.x * WAVES + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (t >= T) return;
+  const float* row = H + (size_t)t * D;
+  float ss = 0.f, dot = 0.f;
+  for (int k = lane * 4; k < D; k += 256) {
+    const float4 v = *reinterpret_cast<const float4*>(row + k);
+    ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+    if (rw) {
+      const float4 w = *reinterpret_cast<const float4*>(rw + k);
+      dot = fmaf(v.x, w.x, dot); dot = fmaf(v.y, w.y, dot); dot = fmaf(v.z, w.z, dot); dot = fmaf(v.w, w.w, dot);
+    }
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)D + eps);
+  for (int k = lane * 4; k < D; k += 256) {
+    const float4 v = *reinterpret_cast<const float4*>(row + k);
+    const float4 g = *reinterpret_cast<const float4*>(gain + k);
+    XT* o = x + (size_t)t * D + k;
+    o[0] = from_f32<XT>(v.x * g.x * r); o[1] = from_f32<XT>(v.y * g.y * r);
+    o[2] = from_f32<XT>(v.z * g.z * r); o[3] = from_f32<XT>(v.w * g.w * r);
+  }
+  if (rw) {
+    dot = wave_sum(dot);
+    if (lane == 0) sig[t] = sigmoidf(dot);
+  }
+}
+
+// rho = mean_t sig[t] (fixed summation order); mask = (rho >= 0.5).  One workgroup.
+__global__ void __launch_bounds__(WG) k_router_reduce(const float* __restrict__ sig, int T,
+                                                      float* __restrict__ rho, uint8_t* __restrict__ mask) {
+  __shared__ float red[WAVES];
+  float s = 0.f;
+  for (int t = threadIdx.x; t < T; t += WG) s += sig[t];
+  const float tot = block_sum(s, red);
+  if (threadIdx.x == 0) {
+    const float r = __fdiv_rn(tot, (float)T);
+    *rho = r;
+    *mask = (r >= 0.5f) ? 1 : 0;
+  }
+}
+
+// kept = ascending indices of set mask bytes; one wave per sequence (ballot + popcount).
+__global__ void __launch_bounds__(64) k_compact(const uint8_t* __restrict__ mask, int L, int* __restrict__ kept,
+                                                int* __restrict__ n_kept) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  int base = 0;
+  for (int i0 = 0; i0 < L; i0 += 64) {
+    const int i = i0 + lane;
+    const bool on = (i < L) && mask[(size_t)b * L + i] != 0;
+    const unsigned long long bal = __ballot(on);
+    if (on) kept[(size_t)b * L + base + __popcll(bal & ((1ull << lane) - 1ull))] = i;
+    base += __popcll(bal);
+  }
+  for (int i = base + lane; i < L; i += 64) kept[(size_t)b * L + i] = -1;
+  if (lane == 0) n_kept[b] = base;
+}
+
+// ---------------------------------------------------------------------------------------
+// C[M,N] (+)= A[M,K] . W[N,K]^T, bf16 inputs, fp32 accumulate on the matrix cores.
+// 128x128 tile per workgroup, 4 waves of 64x64 (2x2 MFMA 32x32x16), K step 64, operands
+// staged through LDS with the next tile prefetched into registers.
+constexpr int GB_M = 128, GB_N = 128, GB_K = 64, GB_PITCH = GB_K + 8;
+
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16(const bf16* __restrict__ A, const bf16* __restrict__ W,
+                                                     float* __restrict__ C, int M, int N, int K, int accumulate) {
+  __shared__ __align__(16) uint16_t sA[GB_M * GB_PITCH];
+  __shared__ __align__(16) uint16_t sB[GB_N * GB_PITCH];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  floatx16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint4 ra[4], rb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      const int k = k0 + kc;
+      ra[i] = make_uint4(0, 0, 0, 0);
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (k < K) {
+        if (m0 + row < M) ra[i] = *reinterpret_cast<const uint4*>(A + (size_t)(m0 + row) * K + k);
+        if (n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
+      }
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      *reinterpret_cast<uint4*>(sA + row * GB_PITCH + kc) = ra[i];
+      *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
+    }
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += GB_K) {
+    __syncthreads();
+    stash();
+    __syncthreads();
+    if (k0 + GB_K < K) fetch(k0 + GB_K);
+#pragma unroll
+    for (int kk = 0; kk < GB_K; kk += 16) {
+      bf16x8_t a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8_t*>(sA + (wm + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
+        b[i] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  // D layout of the 32x32 MFMA: lane -> column (lane & 31); register r -> row
+  // 8*(r/4) + 4*(lane/32) + r%4.
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < M && col < N) {
+          float* c = C + (size_t)row * N + col;
+          *c = accumulate ? *c + acc[i][j][r] : acc[i][j][r];
+        }
+      }
+    }
+}
+
+// fp32 variant (the small full-precision configuration): 64x64 tile, 4x4 per thread.
+__global__ void __launch_bounds__(WG) k_gemm_nt_f32(const float* __restrict__ A, const float* __restrict__ W,
+                                                    float* __restrict__ C, int M, int N, int K, int accumulate) {
+  __shared__ __align__(16) float sA[16][68];
+  __shared__ __align__(16) float sB[16][68];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int lr = tid >> 2, lk = (tid & 3) << 2;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    float4 va = make_float4(0, 0, 0, 0), vb = make_float4(0, 0, 0, 0);
+    if (k0 + lk < K) {
+      if (m0 + lr < M) va = *reinterpret_cast<const float4*>(A + (size_t)(m0 + lr) * K + k0 + lk);
+      if (n0 + lr < N) vb = *reinterpret_cast<const float4*>(W + (size_t)(n0 + lr) * K + k0 + lk);
+    }
+    __syncthreads();
+    sA[lk][lr] = va.x; sA[lk + 1][lr] = va.y; sA[lk + 2][lr] = va.z; sA[lk + 3][lr] = va.w;
+    sB[lk][lr] = vb.x; sB[lk + 1][lr] = vb.y; sB[lk + 2][lr] = vb.z; sB[lk + 3][lr] = vb.w;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float4 a = *reinterpret_cast<const float4*>(&sA[k][ty * 4]);
+      const float4 b = *reinterpret_cast<const float4*>(&sB[k][tx * 4]);
+      const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = m0 + ty * 4 + i, col = n0 + tx * 4 + j;
+      if (row < M && col < N) {
+        float* c = C + (size_t)row * N + col;
+        *c = accumulate ? *c + acc[i][j] : acc[i][j];
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Per token: rotate q (in place, pre-scaled by 1/sqrt(hd)), rotate k, round k and v to the
+// cache type and write them to the token's page slot.  grid = T.
+template <typename KVT>
+__global__ void __launch_bounds__(WG) k_rope_kvwrite(float* __restrict__ q, const float* __restrict__ kraw,
+                                                     const float* __restrict__ vraw, const float2* __restrict__ cs,
+                                                     const int* __restrict__ pt, KVT* __restrict__ pool,
+                                                     size_t page_elems, int Hq, int Hkv, int hd, int P, float qscale) {
+  const int t = blockIdx.x, half = hd >> 1;
+  const float2* c = cs + (size_t)t * half;
+  float* qrow = q + (size_t)t * Hq * hd;
+  for (int i = threadIdx.x; i < Hq * half; i += WG) {
+    const int h = i / half, d = i - h * half;
+    const float x1 = qrow[h * hd + d], x2 = qrow[h * hd + d + half];
+    qrow[h * hd + d] = (x1 * c[d].x - x2 * c[d].y) * qscale;
+    qrow[h * hd + d + half] = (x2 * c[d].x + x1 * c[d].y) * qscale;
+  }
+  const size_t base = (size_t)pt[t / P] * page_elems + (size_t)(t % P) * hd;
+  const size_t v_off = (size_t)Hkv * P * hd;
+  const float* krow = kraw + (size_t)t * Hkv * hd;
+  const float* vrow = vraw + (size_t)t * Hkv * hd;
+  for (int i = threadIdx.x; i < Hkv * half; i += WG) {
+    const int g = i / half, d = i - g * half;
+    const float x1 = krow[g * hd + d], x2 = krow[g * hd + d + half];
+    KVT* dst = pool + base + (size_t)g * P * hd;
+    dst[d] = from_f32<KVT>(x1 * c[d].x - x2 * c[d].y);
+    dst[d + half] = from_f32<KVT>(x2 * c[d].x + x1 * c[d].y);
+  }
+  for (int i = threadIdx.x; i < Hkv * hd; i += WG) {
+    const int g = i / hd, d = i - g * hd;
+    pool[base + v_off + (size_t)g * P * hd + d] = from_f32<KVT>(vrow[i]);
+  }
+}
+
+// Causal GQA attention over the prompt, reading K and V back from the cache pages.
+// grid = (ceil(T/QB), Hkv); the workgroup owns QB query positions x G heads (<= 64 rows),
+// one wave per row in turn; 64-key tiles of K (padded rows) and V are shared through LDS.
+constexpr int PA_RPW = 16;      // rows per wave
+template <typename XT, typename KVT>
+__global__ void __launch_bounds__(WG) k_attn_prefill(const float* __restrict__ q, XT* __restrict__ out,
+                                                     const int* __restrict__ pt, const KVT* __restrict__ pool,
+                                                     size_t page_elems, int T, int Hq, int Hkv, int hd, int P, int QB) {
+  extern __shared__ __align__(16) float smem_f[];
+  constexpr int VEC = Vec<KVT>::N;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int G = Hq / Hkv, g = blockIdx.y, t0 = blockIdx.x * QB;
+  const int NR = QB * G;
+  float* qs = smem_f;                                              // [NR][hd]
+  char* kt = reinterpret_cast<char*>(qs + 64 * hd);
+  const int kpitch = hd * (int)sizeof(KVT) + 4;
+  const KVT* vt = reinterpret_cast<const KVT*>(kt + 64 * kpitch);
+  KVT* vtw = reinterpret_cast<KVT*>(kt + 64 * kpitch);
+  const size_t head_off = (size_t)g * P * hd, v_off = (size_t)Hkv * P * hd;
+
+  for (int i = tid; i < NR * hd; i += WG) {
+    const int rr = i / hd, d = i - rr * hd;
+    const int t = t0 + rr / G, H = g * G + rr % G;
+    qs[i] = (t < T) ? q[((size_t)t * Hq + H) * hd + d] : 0.f;
+  }
+  float m[PA_RPW], l[PA_RPW], o0[PA_RPW], o1[PA_RPW];
+#pragma unroll
+  for (int i = 0; i < PA_RPW; ++i) { m[i] = -INFINITY; l[i] = 0.f; o0[i] = 0.f; o1[i] = 0.f; }
+
+  const int k_end = min(T, t0 + QB);
+  const int vec_per_key = hd / VEC;
+  for (int kt0 = 0; kt0 < k_end; kt0 += 64) {
+    __syncthreads();
+    for (int i = tid; i < 64 * vec_per_key; i += WG) {
+      const int j = i / vec_per_key, c = (i - j * vec_per_key) * VEC;
+      const int key = kt0 + j;
+      uint4 kv4 = make_uint4(0, 0, 0, 0), vv4 = make_uint4(0, 0, 0, 0);
+      if (key < k_end) {
+        const size_t base = (size_t)pt[key / P] * page_elems + head_off + (size_t)(key % P) * hd + c;
+        kv4 = *reinterpret_cast<const uint4*>(pool + base);
+        vv4 = *reinterpret_cast<const uint4*>(pool + base + v_off);
+      }
+      uint32_t* kd = reinterpret_cast<uint32_t*>(kt + j * kpitch + c * sizeof(KVT));
+      kd[0] = kv4.x; kd[1] = kv4.y; kd[2] = kv4.z; kd[3] = kv4.w;
+      *reinterpret_cast<uint4*>(vtw + j * hd + c) = vv4;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ri = 0; ri < PA_RPW; ++ri) {
+      const int rr = wave + ri * WAVES;
+      const int t = t0 + rr / G;
+      if (rr < NR && t < T && kt0 <= t) {
+        const int jn = min(64, t - kt0 + 1);
+        float sc = 0.f;
+        const char* krow = kt + lane * kpitch;
+        const float* qv = qs + rr * hd;
+        if (sizeof(KVT) == 2) {
+          for (int d = 0; d < hd; d += 2) {
+            const uint32_t w2 = *reinterpret_cast<const uint32_t*>(krow + d * 2);
+            sc = fmaf(qv[d], __uint_as_float(w2 << 16), sc);
+            sc = fmaf(qv[d + 1], __uint_as_float(w2 & 0xffff0000u), sc);
+          }
+        } else {
+          for (int d = 0; d < hd; ++d) sc = fmaf(qv[d], *reinterpret_cast<const float*>(krow + d * 4), sc);
+        }
+        if (lane >= jn) sc = -INFINITY;
+        const float mn = fmaxf(m[ri], wave_max(sc));
+        const float corr = expf(m[ri] - mn);
+        const float pj = (lane < jn) ? expf(sc - mn) : 0.f;
+        l[ri] = l[ri] * corr + wave_sum(pj);
+        o0[ri] *= corr; o1[ri] *= corr;
+        m[ri] = mn;
+        for (int j = 0; j < jn; ++j) {
+          const float pb = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pj), j));
+          if (lane < hd) o0[ri] = fmaf(pb, to_f32(vt[j * hd + lane]), o0[ri]);
+          if (lane + 64 < hd) o1[ri] = fmaf(pb, to_f32(vt[j * hd + lane + 64]), o1[ri]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int ri = 0; ri < PA_RPW; ++ri) {
+    const int rr = wave + ri * WAVES;
+    const int t = t0 + rr / G, H = g * G + rr % G;
+    if (rr < NR && t < T) {
+      XT* o = out + ((size_t)t * Hq + H) * hd;
+      if (lane < hd) o[lane] = from_f32<XT>(o0[ri] / l[ri]);
+      if (lane + 64 < hd) o[lane + 64] = from_f32<XT>(o1[ri] / l[ri]);
+    }
+  }
+}
+
+// z = silu(g) * u in the GEMM input type.
+template <typename XT>
+__global__ void __launch_bounds__(WG) k_silu_mul(const float* __restrict__ g, const float* __restrict__ u,
+                                                 XT* __restrict__ z, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n; i += (size_t)gridDim.x * WG)
+    z[i] = from_f32<XT>(siluf(g[i]) * u[i]);
+}
+
+__global__ void __launch_bounds__(WG) k_copy_f32(const float* __restrict__ src, float* __restrict__ dst,
+                                                 float* __restrict__ dst2, int n) {
+  for (int i = blockIdx.x * WG + threadIdx.x; i < n; i += gridDim.x * WG) {
+    const float v = src[i];
+    dst[i] = v;
+    if (dst2) dst2[i] = v;
+  }
+}
+
+__global__ void k_set_int(int* p, int v) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = v; }
+
+__global__ void __launch_bounds__(WG) k_fill_u32(unsigned* p, unsigned v, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n; i += (size_t)gridDim.x * WG) p[i] = v;
+}
+
+// KV taps: positions [pos0, pos0+n) of one layer <-> dense fp32 [n][Hkv][hd].
+template <typename KVT, bool WRITE>
+__global__ void __launch_bounds__(WG) k_kv_tap(KVT* __restrict__ pool, size_t page_elems, const int* __restrict__ pt,
+                                               int pos0, int Hkv, int hd, int P, float* __restrict__ kbuf,
+                                               float* __restrict__ vbuf) {
+  const int j = blockIdx.x, pos = pos0 + j;
+  const size_t base = (size_t)pt[pos / P] * page_elems + (size_t)(pos % P) * hd;
+  const size_t v_off = (size_t)Hkv * P * hd;
+  for (int i = threadIdx.x; i < Hkv * hd; i += WG) {
+    const int g = i / hd, d = i - g * hd;
+    const size_t a = base + (size_t)g * P * hd + d;
+    if (WRITE) {
+      pool[a] = from_f32<KVT>(kbuf[(size_t)j * Hkv * hd + i]);
+      pool[a + v_off] = from_f32<KVT>(vbuf[(size_t)j * Hkv * hd + i]);
+    } else {
+      kbuf[(size_t)j * Hkv * hd + i] = to_f32(pool[a]);
+      vbuf[(size_t)j * Hkv * hd + i] = to_f32(pool[a + v_off]);
+    }
+  }
+}
+
+}  // namespace first
