@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the router-gated decode step on one MI355X.
+
+A step = one call of first_decode_step (embed -> kept layers -> final norm -> LM head ->
+argmax) for the batch, free-running on the device (each step feeds its own greedy token).
+Workload: the 8B-class bf16 decoder, batch 1, prompt 1024, with a seeded skip mask (first and
+last layers kept) fed through first_set_mask; prefill + route runs once per mask before the
+timed region, so weights, KV and tokens are resident in HBM when timing starts.
+
+Prints ONE JSON line: decode tokens/s (headline skip fraction), a sweep over the skip
+fractions, the HBM roofline of the dominant kernel (gate/up mat-vec) measured with events on
+the library's stream, and the CPU oracle timed on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def step_bytes(desc, n_kept, ctx_len, logits=True):
+    """Algorithmic HBM bytes of one batch-1 decode step: kept-layer weights once, LM head,
+    embedding row, KV read of all previous positions plus append, fp32 logits write."""
+    e = desc.bytes_per_elem
+    kvb = 2 * desc.n_kv_heads * desc.head_dim * e
+    w = n_kept * (desc.layer_params * e + 2 * desc.d_model * 4)
+    head = desc.vocab * desc.d_model * e + desc.d_model * 4
+    kv = n_kept * kvb * (ctx_len + 1) + n_kept * kvb
+    return w + head + desc.d_model * e + kv + (desc.vocab * 4 if logits else 0)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="cfg3_8b", choices=["cfg3_8b", "cfg2_1b", "cfg1_tiny"])
+    ap.add_argument("--headline-skip", type=float, default=0.25)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import paper_2410_12513_amd as P
+    from synth import CONFIGS, WORKLOADS, make_prompt, make_router, make_skip_mask, make_weights
+
+    wl = WORKLOADS[args.workload]
+    desc = CONFIGS[wl["model"]]
+    seed = wl["seed"]
+    n_prompt, L = wl["prompt"], desc.n_layers
+    K, W = args.steps, args.warmup
+    skips = sorted(set(wl["skip"]))
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    t0 = time.time()
+    weights = make_weights(desc, seed, device="cuda")
+    router = make_router(desc, seed, device="cuda")
+    prompt = make_prompt(desc.vocab, n_prompt, seed).cuda()
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+
+    ctx = P.FirstContext(desc, weights, router, max_batch=1, max_seq_len=n_prompt + W + K + 16, stream=stream)
+    if args.no_graph:
+        ctx.set_option(1, 0)
+    logits = torch.zeros(1, desc.vocab, device="cuda")
+    tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    sweep, prefill_ms = [], None
+    for k in skips:
+        mask = make_skip_mask(L, k, seed).tolist()
+        ev0.record(stream)
+        ctx.prefill_route(prompt, [n_prompt], token=tok)          # synchronises
+        ev1.record(stream)
+        ev1.synchronize()
+        prefill_ms = ev0.elapsed_time(ev1)
+        ctx.set_mask(0, mask)
+        assert len(ctx.get_kept(0)) == L - k
+        for _ in range(W):
+            ctx.decode_step(tok, logits, tok)
+        ctx.sync()
+        ev0.record(stream)
+        for _ in range(K):
+            ctx.decode_step(tok, logits, tok)
+        ev1.record(stream)
+        ev1.synchronize()
+        ms = ev0.elapsed_time(ev1) / K
+        mid_ctx = n_prompt + W + K // 2
+        by = step_bytes(desc, L - k, mid_ctx)
+        sweep.append({"skip_fraction": k / L, "kept_layers": L - k, "tokens_per_s": 1000.0 / ms,
+                      "ms_per_step": ms, "step_bytes": by,
+                      "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)})
+    head = min(sweep, key=lambda r: abs(r["skip_fraction"] - args.headline_skip))
+
+    # dominant kernel: gate/up mat-vec of one layer; rotate over layers so no launch finds
+    # its weights in cache
+    reps = max(64, K)
+    for i in range(8):
+        ctx.op_gateup(i % L)
+    ctx.sync()
+    ev0.record(stream)
+    for i in range(reps):
+        ctx.op_gateup(i % L)
+    ev1.record(stream)
+    ev1.synchronize()
+    gu_ms = ev0.elapsed_time(ev1) / reps
+    gu_bytes = 2 * desc.d_ffn * desc.d_model * desc.bytes_per_elem       # both matrices, once
+    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gateup_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": "k_gateup (RMSNorm + gate/up mat-vec + SiLU*up, one layer)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3,
+                "launches_timed": reps}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(desc, weights, router, head, seed)
+
+    out = {
+        "metric": "decode tokens/sec at skip fraction s, batch 1 (8B-class); % of HBM roofline",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if desc.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {wl['model']} Llama-style decoder, batch 1, prompt {n_prompt}, "
+                               f"greedy decode, seeded skip mask (first/last kept)",
+                   "skip_fraction": head["skip_fraction"], "kept_layers": head["kept_layers"],
+                   "kv_page_tokens": 16, "graph": not args.no_graph},
+        "hbm_roofline_frac_step": head["hbm_frac"],
+        "sweep": sweep,
+        "prefill": {"tokens": n_prompt, "ms": prefill_ms,
+                    "tflops": (2.0 * n_prompt * L * desc.layer_params + 2.0 * desc.vocab * desc.d_model)
+                              / (prefill_ms * 1e-3) / 1e12},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "setup_s": {"generate_weights": t_gen},
+    }
+    ctx.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(desc, weights, router, head, seed):
+    """The CPU oracle, as it stands, on this machine's host cores: a short prefill (16 tokens, so
+    the run stays bounded) then decode steps of the same model and mask, timed."""
+    import torch
+    from oracle import first_oracle as O
+    from synth import make_prompt, make_skip_mask
+    from synth.generators import to_device
+    t0 = time.time()
+    w_cpu = to_device(weights, "cpu")
+    r_cpu = router.cpu()
+    t_copy = time.time() - t0
+    L = desc.n_layers
+    mask = make_skip_mask(L, L - head["kept_layers"], seed)
+    st = O.prefill_route(desc, w_cpu, r_cpu, make_prompt(desc.vocab, 16, seed))
+    st.set_mask(mask)
+    tok, n, t_dec = st.token, 0, 0.0
+    while n < 2 or (t_dec < 10.0 and n < 64):
+        t1 = time.time()
+        _, tok = O.decode_step(desc, w_cpu, st, tok)
+        t_dec += time.time() - t1
+        n += 1
+    return {"value": n / t_dec, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"{n} decode steps of the same model and mask after a 16-token oracle prefill "
+                      f"(context 16 instead of the workload's prompt; fp64 arithmetic); weights copied "
+                      f"device->host in {t_copy:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

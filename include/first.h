@@ -168,6 +168,12 @@ int first_op_gemv(void *hip_stream, int32_t dtype, const void *W, const float *x
 int first_op_gemm_nt(void *hip_stream, int32_t dtype, const void *A, const void *W, float *C,
                      int32_t m, int32_t n, int32_t k, int32_t accumulate);
 
+/* Launches only the gate/up kernel of one layer (the largest kernel of a decode step,
+ * Section 2 Eq. 1's phi_i: z = silu(Wg y) * (Wu y), y = RMSNorm(h)) for sequence slot seq, on
+ * the context stream, reading the residual h[seq] and overwriting the MLP activation
+ * workspace z[seq] (dead between decode steps).  For kernel-level timing. */
+int first_op_gateup(first_ctx *ctx, int32_t layer, int32_t seq);
+
 #ifdef __cplusplus
 }
 #endif

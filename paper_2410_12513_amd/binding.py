@@ -15,7 +15,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt"]
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup"]
 
 
 class FirstError(RuntimeError):
@@ -205,6 +205,9 @@ class FirstContext:
         out = torch.empty((self.batch(), self.desc.d_model), dtype=torch.float32, device="cuda")
         self._chk(self.lib.first_get_hidden(self.h, _ptr(out)))
         return out
+
+    def op_gateup(self, layer: int, seq: int = 0) -> None:
+        self._chk(self.lib.first_op_gateup(self.h, C.c_int32(layer), C.c_int32(seq)))
 
     def num_pages(self) -> int:
         n = C.c_int32()

@@ -621,6 +621,20 @@ int first_op_gemv(void* hip_stream, int32_t dtype, const void* W, const float* x
   return FIRST_OK;
 }
 
+int first_op_gateup(first_ctx* c, int32_t layer, int32_t seq) {
+  if (!c) return FIRST_ERR_ARG;
+  if (layer < 0 || layer >= c->d.n_layers || seq < 0 || seq >= c->d.max_batch)
+    return fail(c, FIRST_ERR_ARG, "first_op_gateup: layer or sequence out of range");
+  DecParams p = base_params(c, seq, 1);
+  set_layer(c, p, layer);
+  const int grid = gemv_grid(2 * c->d.d_ffn, 4, c->num_cu);
+  const size_t lds = ((size_t)c->d.d_model + WAVES) * sizeof(float);
+  if (c->d.dtype == FIRST_DTYPE_BF16) hipLaunchKernelGGL(k_gateup<bf16>, dim3(grid), dim3(WG), lds, c->stream, p);
+  else hipLaunchKernelGGL(k_gateup<float>, dim3(grid), dim3(WG), lds, c->stream, p);
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
 int first_op_gemm_nt(void* hip_stream, int32_t dtype, const void* A, const void* W, float* C, int32_t m, int32_t n,
                      int32_t k, int32_t accumulate) {
   if (!A || !W || !C || m < 1 || n < 1 || k < 8 || k % 8 || (dtype != FIRST_DTYPE_FP32 && dtype != FIRST_DTYPE_BF16))

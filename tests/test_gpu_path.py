@@ -56,7 +56,7 @@ def test_prefill_route_matches_oracle(model):
     st = O.prefill_route(desc, w, router, prompt)
     got = _prefill(ctx, desc, [prompt])
     # router probabilities and the cached decisions
-    assert float((got["rho"][0] - st.rho).abs().max()) <= (2e-4 if desc.dtype == "bf16" else 2e-6)
+    assert float((got["rho"][0] - st.rho).abs().max()) <= (1e-3 if desc.dtype == "bf16" else 2e-6)   # margin of the routers is 2e-3
     assert got["mask"][0].tolist() == st.mask.tolist()
     assert ctx.get_kept(0) == O.compact_kept(st.mask)
     assert ctx.seq_len(0) == prompt.numel()
@@ -65,7 +65,7 @@ def test_prefill_route_matches_oracle(model):
     assert ok, (ma, rel)
     h_rel = float((got["hidden"][0].double() - st.hidden).norm() / st.hidden.norm())
     assert h_rel <= TOL[desc.dtype]["rel"]
-    if top2_gap(st.logits) > 4 * TOL[desc.dtype]["max_abs"]:
+    if top2_gap(st.logits) > 2 * ma:              # decided beyond twice the measured logit error
         assert int(got["token"][0]) == st.token
     assert int(got["token"][0]) == int(torch.argmax(got["logits"][0]))
     # KV of every layer, every prompt position
@@ -103,10 +103,10 @@ def test_decode_matches_oracle_teacher_forced(model, mask_kind):
         ok, ma, rel = logits_close(lg[s, 0], ref_lg[s], desc.dtype)
         assert ok, (s, ma, rel)
         assert int(tk[s, 0]) == int(torch.argmax(lg[s, 0]))
-        if top2_gap(ref_lg[s]) > 4 * TOL[desc.dtype]["max_abs"]:
+        if top2_gap(ref_lg[s]) > 2 * ma:           # decided beyond twice the measured logit error
             assert int(tk[s, 0]) == ref_tk[s]
             checked += 1
-    assert checked >= n_steps // 2
+    assert checked >= (3 * n_steps) // 4
     assert ctx.seq_len(0) == prompt.numel() + n_steps
     # kept layers hold KV for the new positions, equal to the oracle's
     for i in O.compact_kept(st.mask):
@@ -146,6 +146,9 @@ def test_all_skip_is_embedding_norm_head_and_hidden_is_bit_identical():
     _prefill(ctx, desc, [prompt])
     ctx.set_mask(0, [0] * desc.n_layers)
     assert ctx.get_kept(0) == []
+    sent = torch.full((8, desc.n_kv_heads, desc.head_dim), -3.0, device="cuda")
+    for i in range(desc.n_layers):                               # define the unused tail of the last page
+        ctx.kv_write(0, i, 40, sent, sent)
     before = [tuple(t.clone() for t in ctx.kv_read(0, i, 0, 48)) for i in range(desc.n_layers)]
     tok = 123
     lg, tk = _decode(ctx, desc, [[tok]])
