@@ -47,7 +47,9 @@ extern "C" {
 /* options for first_set_option */
 #define FIRST_OPT_USE_GRAPH     1  /* 1 (default): replay a cached hipGraph per mask; 0: eager launches */
 #define FIRST_OPT_ATTN_SPLITS   2  /* KV splits per (sequence, KV head) in decode attention; 0 = auto   */
-#define FIRST_OPT_DECODE_PATH   3  /* 0: one kernel per fused op; 1: one persistent kernel per step     */
+#define FIRST_OPT_DECODE_PATH   3  /* -1 (default): persistent whole-step kernel when the model fits it
+                                      (bf16, widths multiples of 2048, one live sequence), else per-op
+                                      kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 typedef struct first_ctx first_ctx;
 

@@ -12,6 +12,7 @@
 #include "../../include/first.h"
 #include "decode_kernels.h"
 #include "prefill_kernels.h"
+#include "step_kernel.h"
 
 using namespace first;
 
@@ -63,8 +64,14 @@ struct first_ctx {
   std::vector<std::vector<uint8_t>> hmask;
   std::vector<int> free_pages, page_order, h_page_table;
   std::vector<int> seq_npages;
+  // persistent whole-step kernel (bf16, one live sequence)
+  LayerDev* d_layers = nullptr;
+  unsigned* d_bar = nullptr;
+  int* d_err = nullptr;
+  bool step_ok = false;        // geometry fits the persistent kernel
+  size_t step_lds = 0;
   // options and graph cache
-  int use_graph = 1, attn_splits = 0, decode_path = 0;
+  int use_graph = 1, attn_splits = 0, decode_path = -1;   // -1: persistent kernel when possible
   std::map<std::string, hipGraphExec_t> graphs;
 };
 
@@ -186,6 +193,35 @@ void enqueue_decode_ops(first_ctx* c, const int* tokens, float* logits, int* tok
     }
     enqueue_head<WT>(c, p, logits, token_out, 1);
   }
+}
+
+// One decode token of the single live sequence as one persistent kernel.
+void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, int* token_out) {
+  StepParams P{};
+  P.d = base_params(c, 0, 1);
+  P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
+  P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
+  P.bar = c->d_bar; P.err = c->d_err;
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)1);
+  if (c->d.head_dim == 128)
+    hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  else
+    hipLaunchKernelGGL(k_step<64>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+}
+
+// Does the geometry fit the persistent kernel's static work split?
+bool step_kernel_fits(const first_ctx* c) {
+  const first_model_desc& d = c->d;
+  if (d.dtype != FIRST_DTYPE_BF16) return false;
+  if (d.d_model % SK_SEG || c->nq % SK_SEG || d.d_ffn % SK_SEG) return false;
+  if (c->G > SK_WAVES || (c->G & (c->G - 1))) return false;
+  if (d.n_kv_heads > c->num_cu) return false;
+  const int ncu = c->num_cu;
+  auto units = [&](long long rows, int K) { return (int)((rows + ncu - 1) / ncu + 2) * (K / SK_SEG); };
+  const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), units(d.d_model, c->nq),
+                              units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});
+  if (worst > SK_PSUM) return false;
+  return sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float) <= 150 * 1024;
 }
 
 int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const void* W, float* C, int M, int N,
@@ -340,6 +376,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * c->elem));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * c->elem));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * c->elem));
+  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, 4)); A(dev_alloc(c, &c->d_err, 4));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
     for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
@@ -347,6 +384,29 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_attn_cnt, 0, (size_t)B * d.n_kv_heads * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, 4 * sizeof(unsigned));
+    c->step_ok = step_kernel_fits(c);
+    if (e == hipSuccess && c->step_ok) {
+      std::vector<LayerDev> ld(L);
+      for (int i = 0; i < L; ++i) {
+        const LayerPtrs& l = c->layers[i];
+        ld[i] = LayerDev{(const bf16*)l.wq, (const bf16*)l.wk, (const bf16*)l.wv, (const bf16*)l.wo, (const bf16*)l.wg,
+                         (const bf16*)l.wu, (const bf16*)l.wd, l.g_attn, l.g_mlp,
+                         (bf16*)(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem)};
+      }
+      e = hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
+      c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
+      const void* fn = d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>)
+                                         : reinterpret_cast<const void*>(&k_step<64>);
+      if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
+      int per_cu = 0;
+      if (e == hipSuccess)
+        e = d.head_dim == 128
+                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<128>, SK_THREADS, c->step_lds)
+                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<64>, SK_THREADS, c->step_lds);
+      if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
+    }
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
     if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
     // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
@@ -476,24 +536,33 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   if (S <= 0) S = (max_len + 128 + 127) / 128;
   S = std::max(1, std::min(S, 32));
   const bool bf = c->d.dtype == FIRST_DTYPE_BF16;
-  if (!c->use_graph) {
-    if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
+  const bool persistent = c->step_ok && c->B == 1 && c->decode_path != 0;
+  if (c->decode_path == 1 && !persistent)
+    return fail(c, FIRST_ERR_STATE, "first_decode_step: the persistent kernel needs a bf16 model whose widths are "
+                                    "multiples of 2048 and exactly one live sequence");
+  auto enqueue = [&]() {
+    if (persistent) enqueue_decode_step_kernel(c, last_tokens, logits_out, token_out);
+    else if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
     else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
+  };
+  if (!c->use_graph) {
+    enqueue();
     HIPCHK(c, hipGetLastError());
   } else {
+    if (persistent) S = -1;                        // the kernel reads the kept list from the device
     std::string key(reinterpret_cast<const char*>(&S), sizeof(S));
     key.append(reinterpret_cast<const char*>(&last_tokens), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&logits_out), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&token_out), sizeof(void*));
-    for (int b = 0; b < c->B; ++b) key.append(reinterpret_cast<const char*>(c->hmask[b].data()), c->hmask[b].size());
+    if (!persistent)
+      for (int b = 0; b < c->B; ++b) key.append(reinterpret_cast<const char*>(c->hmask[b].data()), c->hmask[b].size());
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
       if (c->graphs.size() >= 32) drop_graphs(c);
       hipGraph_t graph = nullptr;
       hipGraphExec_t exec = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
-      if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
-      else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
+      enqueue();
       HIPCHK(c, hipStreamEndCapture(c->stream, &graph));
       HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
       (void)hipGraphDestroy(graph);
@@ -513,7 +582,7 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       if (value < 0 || value > S_MAX) return fail(c, FIRST_ERR_ARG, "first_set_option: splits out of range");
       c->attn_splits = value; return FIRST_OK;
     case FIRST_OPT_DECODE_PATH:
-      if (value != 0) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown decode path");
+      if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown decode path");
       c->decode_path = value; return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
   }
@@ -522,6 +591,9 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
 int first_sync(first_ctx* c) {
   if (!c) return FIRST_ERR_ARG;
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  int err = 0;
+  HIPCHK(c, hipMemcpy(&err, c->d_err, sizeof(int), hipMemcpyDeviceToHost));
+  if (err) return fail(c, FIRST_ERR_HIP, "first_sync: a grid barrier of the persistent decode kernel gave up waiting");
   return FIRST_OK;
 }
 

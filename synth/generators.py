@@ -58,6 +58,11 @@ CONFIGS: Dict[str, ModelDesc] = {
     "mini_bf16": ModelDesc(4, 512, 8, 2, 64, 1416, 2003, dtype="bf16"),
     "mini_fp32": ModelDesc(3, 256, 4, 2, 64, 696, 1001, dtype="fp32"),
     "mini_hd128": ModelDesc(3, 512, 4, 1, 128, 1032, 1500, dtype="bf16"),
+    # widths that are multiples of 2048: shapes the persistent whole-step decode kernel accepts
+    "step_hd128": ModelDesc(3, 2048, 16, 4, 128, 4096, 5003, dtype="bf16"),
+    "step_hd64": ModelDesc(2, 2048, 32, 8, 64, 2048, 3001, dtype="bf16"),
+    "step_g8": ModelDesc(2, 2048, 16, 2, 128, 2048, 2999, dtype="bf16"),
+    "step_mha": ModelDesc(2, 2048, 16, 16, 128, 2048, 2999, dtype="bf16"),
 }
 
 # Workloads: (model, batch, prompt length(s), decode steps, skipped-layer count(s)).

@@ -1,0 +1,112 @@
+"""The persistent whole-step decode kernel (one launch per token) against the oracle and
+against the per-op kernels, through the C ABI.  Option 3 = 1 makes the library refuse to
+fall back, so these tests cannot pass on another path."""
+import pytest
+import torch
+
+from oracle import first_oracle as O
+from synth import CONFIGS, make_prompt, make_skip_mask, make_weights
+from tests.gpu_util import TOL, build, logits_close, routers_with_margin, top2_gap
+from tests.test_gpu_path import _decode, _prefill
+
+pytestmark = pytest.mark.gpu
+torch.set_grad_enabled(False)
+
+OPT_DECODE_PATH = 3
+
+
+@pytest.mark.parametrize("model,n_prompt", [("step_hd128", 150), ("step_hd64", 70), ("step_g8", 200),
+                                            ("step_mha", 65), ("step_hd128", 700)])
+@pytest.mark.parametrize("mask_kind", ["interior", "all_keep", "all_skip"])
+def test_step_kernel_matches_oracle(model, n_prompt, mask_kind):
+    desc = CONFIGS[model]
+    if n_prompt > 300 and mask_kind != "interior":
+        pytest.skip("long prompt is run once")
+    prompt = make_prompt(desc.vocab, n_prompt, 41)
+    desc, w, router, ctx = build(model, 41, max_seq_len=n_prompt + 40)
+    ctx.set_option(OPT_DECODE_PATH, 1)
+    st = O.prefill_route(desc, w, router, prompt)
+    _prefill(ctx, desc, [prompt])
+    L = desc.n_layers
+    mask = {"interior": [1] + [0] * (L - 2) + [1] if L > 2 else [0, 1], "all_keep": [1] * L, "all_skip": [0] * L}[mask_kind]
+    st.set_mask(mask)
+    ctx.set_mask(0, mask)
+    n_steps = 20
+    ref_lg, ref_tk = O.generate(desc, w, st, n_steps)
+    lg, tk = _decode(ctx, desc, [[t] for t in [st.token] + ref_tk[:-1]])
+    checked = 0
+    for s in range(n_steps):
+        ok, ma, rel = logits_close(lg[s, 0], ref_lg[s], desc.dtype)
+        assert ok, (s, ma, rel)
+        assert int(tk[s, 0]) == int(torch.argmax(lg[s, 0]))
+        if top2_gap(ref_lg[s]) > 2 * ma:
+            assert int(tk[s, 0]) == ref_tk[s]
+            checked += 1
+    assert checked >= (3 * n_steps) // 4
+    assert ctx.seq_len(0) == n_prompt + n_steps
+    for i in O.compact_kept(st.mask):
+        k, v = ctx.kv_read(0, i, n_prompt, n_steps)
+        kr = st.K[i][n_prompt:].double()
+        assert float((k.cpu().double() - kr).norm() / kr.norm()) <= 1.5e-2
+    ctx.close()
+
+
+@pytest.mark.parametrize("model", ["step_hd128", "step_hd64"])
+def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
+    desc = CONFIGS[model]
+    prompt = make_prompt(desc.vocab, 130, 43)
+    mask = make_skip_mask(desc.n_layers, 1 if desc.n_layers > 2 else 0, 43).tolist()
+    inputs = [[int(t)] for t in make_prompt(desc.vocab, 24, 44)]
+    runs = {}
+    for name, path, graph in (("ops", 0, 1), ("step", 1, 1), ("step_again", 1, 1), ("step_eager", 1, 0)):
+        desc, w, router, ctx = build(model, 43, max_seq_len=200)
+        ctx.set_option(OPT_DECODE_PATH, path)
+        ctx.set_option(1, graph)
+        _prefill(ctx, desc, [prompt])
+        ctx.set_mask(0, mask)
+        lg, tk = _decode(ctx, desc, inputs)
+        h = ctx.get_hidden().cpu()
+        runs[name] = (lg, tk, h)
+        ctx.close()
+    assert torch.equal(runs["step"][0], runs["step_again"][0]) and torch.equal(runs["step"][1], runs["step_again"][1])
+    assert torch.equal(runs["step"][0], runs["step_eager"][0])
+    # same arithmetic up to fp32 summation order
+    assert float((runs["step"][0] - runs["ops"][0]).abs().max()) <= 2e-4
+    assert float((runs["step"][2] - runs["ops"][2]).abs().max()) <= 2e-4 * float(runs["ops"][2].abs().max())
+
+
+def test_step_kernel_all_skip_leaves_hidden_bit_identical_and_kv_untouched():
+    desc, w, router, ctx = build("step_hd128", 45, max_seq_len=128)
+    ctx.set_option(OPT_DECODE_PATH, 1)
+    prompt = make_prompt(desc.vocab, 40, 45)
+    _prefill(ctx, desc, [prompt])
+    ctx.set_mask(0, [1, 0, 0])
+    sent = torch.full((8, desc.n_kv_heads, desc.head_dim), -3.0, device="cuda")
+    for i in range(desc.n_layers):
+        ctx.kv_write(0, i, 40, sent, sent)
+    before = [tuple(t.clone() for t in ctx.kv_read(0, i, 0, 48)) for i in range(desc.n_layers)]
+    _decode(ctx, desc, [[7], [9]])
+    for i in (1, 2):
+        k, v = ctx.kv_read(0, i, 0, 48)
+        assert torch.equal(k, before[i][0]) and torch.equal(v, before[i][1])
+    k, v = ctx.kv_read(0, 0, 0, 48)
+    assert torch.equal(k[:40], before[0][0][:40]) and float(k[40:42].max()) != -3.0
+    ctx.set_mask(0, [0, 0, 0])
+    _decode(ctx, desc, [[123]])
+    assert torch.equal(ctx.get_hidden().cpu()[0], w["embed"][123].float())
+    ctx.close()
+
+
+def test_step_kernel_is_refused_when_the_model_does_not_fit():
+    import paper_2410_12513_amd as P
+    desc, w, router, ctx = build("mini_bf16", 47, max_seq_len=64)
+    ctx.set_option(OPT_DECODE_PATH, 1)
+    _prefill(ctx, desc, [make_prompt(desc.vocab, 20, 47)])
+    tin = torch.tensor([1], dtype=torch.int32, device="cuda")
+    with pytest.raises(P.FirstError) as e:
+        ctx.decode_step(tin, None, tin)
+    assert e.value.code == -2
+    ctx.set_option(OPT_DECODE_PATH, -1)
+    ctx.decode_step(tin, None, tin)          # automatic choice falls back to the per-op kernels
+    ctx.sync()
+    ctx.close()
