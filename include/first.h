@@ -51,6 +51,8 @@ extern "C" {
                                       (bf16, widths multiples of 2048, one live sequence), else per-op
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
+#define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
+
 typedef struct first_ctx first_ctx;
 
 /* Geometry of the decoder.  POD, filled by the caller. */
@@ -169,6 +171,20 @@ int first_op_gemv(void *hip_stream, int32_t dtype, const void *W, const float *x
  * (MFMA for bf16).  A DEV [m,k] and W DEV [n,k] of dtype, C DEV fp32 [m,n]; k multiple of 8. */
 int first_op_gemm_nt(void *hip_stream, int32_t dtype, const void *A, const void *W, float *C,
                      int32_t m, int32_t n, int32_t k, int32_t accumulate);
+
+/* The same contraction with fp32 activations and bf16 weights, as the prefill path runs it:
+ * each activation is split into a high and a low bf16 part and both go through the matrix
+ * cores, so about 16 bits of the activation's mantissa take part.
+ * A DEV fp32 [m,k], W DEV bf16 [n,k], C DEV fp32 [m,n]; k multiple of 8. */
+int first_op_gemm_nt_f32a(void *hip_stream, const float *A, const void *W, float *C, int32_t m,
+                          int32_t n, int32_t k, int32_t accumulate);
+
+/* Per-phase timestamps of the last persistent-kernel decode step (FIRST_OPT_STEP_TIMING = 1),
+ * taken by workgroup 0 on the 100 MHz device clock: for each phase (QKV, O, gate/up, down of
+ * every kept layer in order, then the LM head) twelve values: arrival at the phase's barrier,
+ * barrier passed, attention done (O phase only), input staged, weights streamed, results
+ * stored, then six marks inside the attention of workgroup 0 (O phase only).  stamps HOST uint64 [capacity]; n_out HOST receives the count.  Synchronises. */
+int first_step_timing(first_ctx *ctx, uint64_t *stamps, int32_t capacity, int32_t *n_out);
 
 /* Launches only the gate/up kernel of one layer (the largest kernel of a decode step,
  * Section 2 Eq. 1's phi_i: z = silu(Wg y) * (Wu y), y = RMSNorm(h)) for sequence slot seq, on

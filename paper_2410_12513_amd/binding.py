@@ -15,7 +15,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup"]
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a"]
 
 
 class FirstError(RuntimeError):
@@ -209,6 +209,14 @@ class FirstContext:
     def op_gateup(self, layer: int, seq: int = 0) -> None:
         self._chk(self.lib.first_op_gateup(self.h, C.c_int32(layer), C.c_int32(seq)))
 
+    def step_timing(self):
+        """Timestamps [phases, 6] (100 MHz ticks) of the last persistent-kernel step."""
+        cap = (4 * self.desc.n_layers + 1) * 12
+        arr = (C.c_uint64 * cap)()
+        n = C.c_int32()
+        self._chk(self.lib.first_step_timing(self.h, arr, C.c_int32(cap), C.byref(n)))
+        return [list(arr[i:i + 12]) for i in range(0, n.value, 12)]
+
     def num_pages(self) -> int:
         n = C.c_int32()
         self._chk(self.lib.first_num_pages(self.h, C.byref(n)))
@@ -244,5 +252,17 @@ def op_gemm_nt(A: torch.Tensor, W: torch.Tensor, Cm: torch.Tensor, accumulate: b
     _check_dev(A, W.dtype, "A"); _check_dev(W, W.dtype, "W"); _check_dev(Cm, torch.float32, "C", m * n)
     rc = lib.first_op_gemm_nt(_stream_ptr(stream), C.c_int32(code), _ptr(A), _ptr(W), _ptr(Cm), C.c_int32(m),
                               C.c_int32(n), C.c_int32(k), C.c_int32(int(accumulate)))
+    if rc != 0:
+        raise FirstError(rc, lib.first_last_error(None).decode())
+
+
+def op_gemm_nt_f32a(A: torch.Tensor, W: torch.Tensor, Cm: torch.Tensor, accumulate: bool = False, stream=None) -> None:
+    """fp32 activations x bf16 weights (split-precision matrix-core kernel of the prefill path)."""
+    lib = load_library()
+    m, k = A.shape
+    n = W.shape[0]
+    _check_dev(A, torch.float32, "A"); _check_dev(W, torch.bfloat16, "W"); _check_dev(Cm, torch.float32, "C", m * n)
+    rc = lib.first_op_gemm_nt_f32a(_stream_ptr(stream), _ptr(A), _ptr(W), _ptr(Cm), C.c_int32(m), C.c_int32(n),
+                                   C.c_int32(k), C.c_int32(int(accumulate)))
     if rc != 0:
         raise FirstError(rc, lib.first_last_error(None).decode())

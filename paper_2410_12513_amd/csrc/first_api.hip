@@ -68,6 +68,8 @@ struct first_ctx {
   LayerDev* d_layers = nullptr;
   unsigned* d_bar = nullptr;
   int* d_err = nullptr;
+  unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
+  int step_timing = 0;
   bool step_ok = false;        // geometry fits the persistent kernel
   size_t step_lds = 0;
   // options and graph cache
@@ -202,7 +204,8 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
   P.bar = c->d_bar; P.err = c->d_err;
-  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)1);
+  P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)c->num_cu);
   if (c->d.head_dim == 128)
     hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
   else
@@ -214,9 +217,10 @@ bool step_kernel_fits(const first_ctx* c) {
   const first_model_desc& d = c->d;
   if (d.dtype != FIRST_DTYPE_BF16) return false;
   if (d.d_model % SK_SEG || c->nq % SK_SEG || d.d_ffn % SK_SEG) return false;
-  if (c->G > SK_WAVES || (c->G & (c->G - 1))) return false;
-  if (d.n_kv_heads > c->num_cu) return false;
+  if (c->G > SK_SWAVES || d.kv_page_tokens != 16) return false;               // one streaming wave per query head of a KV group
+  if (d.n_kv_heads > c->num_cu || d.d_ffn > 16384 || d.d_model > 16384 || c->nq > 16384) return false;
   const int ncu = c->num_cu;
+  if ((long long)std::max({d.vocab, 2 * d.d_ffn, c->nq + 2 * c->nkv}) * (ncu + 1) >= (1LL << 31)) return false;
   auto units = [&](long long rows, int K) { return (int)((rows + ncu - 1) / ncu + 2) * (K / SK_SEG); };
   const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), units(d.d_model, c->nq),
                               units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});
@@ -224,9 +228,15 @@ bool step_kernel_fits(const first_ctx* c) {
   return sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float) <= 150 * 1024;
 }
 
+// a_fp32: the activations are fp32 (prefill path); bf16 weights then use the split-precision
+// matrix-core kernel.
 int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const void* W, float* C, int M, int N,
-                int K, int acc) {
-  if (dtype == FIRST_DTYPE_BF16) {
+                int K, int acc, bool a_fp32 = false) {
+  if (dtype == FIRST_DTYPE_BF16 && a_fp32) {
+    dim3 grid((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M);
+    hipLaunchKernelGGL(k_gemm_nt_bf16_split, grid, dim3(WG), 0, st, reinterpret_cast<const float*>(A),
+                       reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
+  } else if (dtype == FIRST_DTYPE_BF16) {
     dim3 grid((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M);
     hipLaunchKernelGGL(k_gemm_nt_bf16, grid, dim3(WG), 0, st, reinterpret_cast<const bf16*>(A),
                        reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
@@ -250,9 +260,10 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
   const float qscale = 1.0f / std::sqrt((float)hd);
   const size_t kpitch = (size_t)hd * sizeof(WT) + 4;
   const size_t lds_attn = (size_t)64 * hd * sizeof(float) + 64 * kpitch + (size_t)64 * hd * sizeof(WT);
-  WT* x = reinterpret_cast<WT*>(c->p_x);
-  WT* a = reinterpret_cast<WT*>(c->p_a);
-  WT* z = reinterpret_cast<WT*>(c->p_z);
+  // activations stay fp32 between the kernels; the bf16 GEMM splits them into two bf16 parts
+  float* x = reinterpret_cast<float*>(c->p_x);
+  float* a = reinterpret_cast<float*>(c->p_a);
+  float* z = reinterpret_cast<float*>(c->p_z);
 
   hipLaunchKernelGGL(k_embed_rows<WT>, dim3(T), dim3(WG), 0, st, ids, reinterpret_cast<const WT*>(c->embed), c->p_H, D,
                      d.vocab);
@@ -261,26 +272,26 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     const LayerPtrs& l = c->layers[i];
     WT* pool = reinterpret_cast<WT*>(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem);
     // router i reads the stream entering layer i, in the same pass as the attention norm
-    hipLaunchKernelGGL(k_rmsnorm_router<WT>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_attn,
+    hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_attn,
                        c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps);
     hipLaunchKernelGGL(k_router_reduce, dim3(1), dim3(WG), 0, st, c->p_sig, T, c->d_rho + (size_t)b * L + i,
                        c->d_mask + (size_t)b * L + i);
     int rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wq, c->p_q, T, c->nq, D, 0))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wk, c->p_k, T, c->nkv, D, 0))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wv, c->p_v, T, c->nkv, D, 0))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wq, c->p_q, T, c->nq, D, 0, true))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wk, c->p_k, T, c->nkv, D, 0, true))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wv, c->p_v, T, c->nkv, D, 0, true))) return rc;
     hipLaunchKernelGGL(k_rope_kvwrite<WT>, dim3(T), dim3(WG), 0, st, c->p_q, c->p_k, c->p_v, c->p_cs, pt, pool,
                        c->page_elems, d.n_q_heads, d.n_kv_heads, hd, P, qscale);
-    hipLaunchKernelGGL((k_attn_prefill<WT, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
+    hipLaunchKernelGGL((k_attn_prefill<float, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
                        pt, pool, c->page_elems, T, d.n_q_heads, d.n_kv_heads, hd, P, QB);
-    if ((rc = launch_gemm(c, st, d.dtype, a, l.wo, c->p_H, T, D, c->nq, 1))) return rc;
-    hipLaunchKernelGGL(k_rmsnorm_router<WT>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
+    if ((rc = launch_gemm(c, st, d.dtype, a, l.wo, c->p_H, T, D, c->nq, 1, true))) return rc;
+    hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
                        (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps);
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wg, c->p_g, T, F, D, 0))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wu, c->p_u, T, F, D, 0))) return rc;
-    hipLaunchKernelGGL(k_silu_mul<WT>, dim3(std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536)), dim3(WG), 0, st,
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wg, c->p_g, T, F, D, 0, true))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, x, l.wu, c->p_u, T, F, D, 0, true))) return rc;
+    hipLaunchKernelGGL(k_silu_mul<float>, dim3(std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536)), dim3(WG), 0, st,
                        c->p_g, c->p_u, z, (size_t)T * F);
-    if ((rc = launch_gemm(c, st, d.dtype, z, l.wd, c->p_H, T, D, F, 1))) return rc;
+    if ((rc = launch_gemm(c, st, d.dtype, z, l.wd, c->p_H, T, D, F, 1, true))) return rc;
   }
   // last position -> decode residual slot of this sequence (+ optional copy out), first token
   hipLaunchKernelGGL(k_copy_f32, dim3((D + WG - 1) / WG), dim3(WG), 0, st, c->p_H + (size_t)(T - 1) * D,
@@ -373,10 +384,11 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, &c->p_k, (size_t)T * c->nkv)); A(dev_alloc(c, &c->p_v, (size_t)T * c->nkv));
   A(dev_alloc(c, &c->p_g, (size_t)T * d.d_ffn)); A(dev_alloc(c, &c->p_u, (size_t)T * d.d_ffn));
   A(dev_alloc(c, &c->p_sig, T)); A(dev_alloc(c, &c->p_cs, (size_t)T * c->half));
-  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * c->elem));
-  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * c->elem));
-  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * c->elem));
-  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, 4)); A(dev_alloc(c, &c->d_err, 4));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
+  A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * 4));
+  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)c->num_cu + 4)); A(dev_alloc(c, &c->d_err, 4));
+  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
     for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
@@ -385,7 +397,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
     if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
-    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, 4 * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, ((size_t)c->num_cu + 4) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
       std::vector<LayerDev> ld(L);
@@ -410,7 +422,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
     if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
     // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<bf16, bf16>),
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, bf16>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, float>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
@@ -584,6 +596,10 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
     case FIRST_OPT_DECODE_PATH:
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown decode path");
       c->decode_path = value; return FIRST_OK;
+    case FIRST_OPT_STEP_TIMING:
+      c->step_timing = value ? 1 : 0;
+      drop_graphs(c);
+      return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
   }
 }
@@ -693,6 +709,20 @@ int first_op_gemv(void* hip_stream, int32_t dtype, const void* W, const float* x
   return FIRST_OK;
 }
 
+int first_step_timing(first_ctx* c, uint64_t* stamps, int32_t capacity, int32_t* n_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!stamps || !n_out) return fail(c, FIRST_ERR_ARG, "first_step_timing: null output");
+  if (c->B < 1) return fail(c, FIRST_ERR_STATE, "first_step_timing: no live sequence");
+  int nk = 0;
+  for (int i = 0; i < c->d.n_layers; ++i) nk += c->hmask[0][i] ? 1 : 0;
+  const int n = (4 * nk + 1) * SK_TSLOTS;
+  if (capacity < n) return fail(c, FIRST_ERR_ARG, "first_step_timing: buffer too small");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(stamps, c->d_tdbg, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  *n_out = n;
+  return FIRST_OK;
+}
+
 int first_op_gateup(first_ctx* c, int32_t layer, int32_t seq) {
   if (!c) return FIRST_ERR_ARG;
   if (layer < 0 || layer >= c->d.n_layers || seq < 0 || seq >= c->d.max_batch)
@@ -712,6 +742,13 @@ int first_op_gemm_nt(void* hip_stream, int32_t dtype, const void* A, const void*
   if (!A || !W || !C || m < 1 || n < 1 || k < 8 || k % 8 || (dtype != FIRST_DTYPE_FP32 && dtype != FIRST_DTYPE_BF16))
     return fail(nullptr, FIRST_ERR_ARG, "first_op_gemm_nt: bad argument");
   return launch_gemm(nullptr, reinterpret_cast<hipStream_t>(hip_stream), dtype, A, W, C, m, n, k, accumulate);
+}
+
+int first_op_gemm_nt_f32a(void* hip_stream, const float* A, const void* W, float* C, int32_t m, int32_t n, int32_t k,
+                          int32_t accumulate) {
+  if (!A || !W || !C || m < 1 || n < 1 || k < 8 || k % 8)
+    return fail(nullptr, FIRST_ERR_ARG, "first_op_gemm_nt_f32a: bad argument");
+  return launch_gemm(nullptr, reinterpret_cast<hipStream_t>(hip_stream), FIRST_DTYPE_BF16, A, W, C, m, n, k, accumulate, true);
 }
 
 }  // extern "C"

@@ -176,6 +176,105 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16(const bf16* __restrict__ A,
     }
 }
 
+// Same contraction with fp32 activations A and bf16 weights W.  Each activation is split into
+// two bf16 numbers, a = hi + lo with hi = bf16(a) and lo = bf16(a - hi), and both parts go
+// through the matrix cores against the same weight tile, so the product carries about 16
+// mantissa bits of the activation instead of 8 (the weights are bf16 exactly).  This keeps
+// the prompt's hidden states, KV and first-token logits close to full-precision arithmetic
+// at twice the matrix-core work.
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_split(const float* __restrict__ A, const bf16* __restrict__ W,
+                                                           float* __restrict__ C, int M, int N, int K, int accumulate) {
+  __shared__ __align__(16) uint16_t sAh[GB_M * GB_PITCH];
+  __shared__ __align__(16) uint16_t sAl[GB_M * GB_PITCH];
+  __shared__ __align__(16) uint16_t sB[GB_N * GB_PITCH];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  floatx16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float4 ra[4][2];
+  uint4 rb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      const int k = k0 + kc;
+      ra[i][0] = make_float4(0, 0, 0, 0); ra[i][1] = make_float4(0, 0, 0, 0);
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (k < K) {
+        if (m0 + row < M) {
+          ra[i][0] = *reinterpret_cast<const float4*>(A + (size_t)(m0 + row) * K + k);
+          ra[i][1] = *reinterpret_cast<const float4*>(A + (size_t)(m0 + row) * K + k + 4);
+        }
+        if (n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
+      }
+    }
+  };
+  auto split2 = [](float a, float b, uint32_t& hi, uint32_t& lo) {
+    const uint32_t ha = f2bf(a), hb = f2bf(b);
+    hi = ha | (hb << 16);
+    lo = (uint32_t)f2bf(a - bf2f(ha)) | ((uint32_t)f2bf(b - bf2f(hb)) << 16);
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      uint4 h, l;
+      split2(ra[i][0].x, ra[i][0].y, h.x, l.x); split2(ra[i][0].z, ra[i][0].w, h.y, l.y);
+      split2(ra[i][1].x, ra[i][1].y, h.z, l.z); split2(ra[i][1].z, ra[i][1].w, h.w, l.w);
+      *reinterpret_cast<uint4*>(sAh + row * GB_PITCH + kc) = h;
+      *reinterpret_cast<uint4*>(sAl + row * GB_PITCH + kc) = l;
+      *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
+    }
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += GB_K) {
+    __syncthreads();
+    stash();
+    __syncthreads();
+    if (k0 + GB_K < K) fetch(k0 + GB_K);
+#pragma unroll
+    for (int kk = 0; kk < GB_K; kk += 16) {
+      bf16x8_t ah[2], al[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int ao = (wm + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3);
+        ah[i] = *reinterpret_cast<const bf16x8_t*>(sAh + ao);
+        al[i] = *reinterpret_cast<const bf16x8_t*>(sAl + ao);
+        b[i] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < M && col < N) {
+          float* c = C + (size_t)row * N + col;
+          *c = accumulate ? *c + acc[i][j][r] : acc[i][j][r];
+        }
+      }
+    }
+}
+
 // fp32 variant (the small full-precision configuration): 64x64 tile, 4x4 per thread.
 __global__ void __launch_bounds__(WG) k_gemm_nt_f32(const float* __restrict__ A, const float* __restrict__ W,
                                                     float* __restrict__ C, int M, int N, int K, int accumulate) {

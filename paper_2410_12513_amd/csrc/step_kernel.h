@@ -10,12 +10,13 @@ namespace first {
 
 constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = SK_THREADS / 64;
+constexpr int SK_SWAVES = SK_WAVES - 1;  // streaming waves; the last wave is the service wave (see k_step)
 constexpr int SK_SEG = 2048;          // elements of a weight row handled by one wave at a time (4 x 16 B per lane)
-constexpr int SK_PD = 8;              // row segments in flight per wave (32 KB)
-constexpr int SK_PD_ATT = 4;          // ring slots kept in flight across the attention phase
+constexpr int SK_PD = 4;              // row segments in flight per wave (32 KB)
+constexpr int SK_PD_EARLY = 4;        // ring slots that stay in flight across the attention phase
 constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row segments per phase)
-constexpr int SK_SMAX = 8;            // attention splits merged by the O-projection prologue
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
+constexpr int SK_TSLOTS = 12;         // timestamps per segment: arrive, barrier, attention, stage, stream, results
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -41,6 +42,43 @@ __device__ __forceinline__ uint4 ld_global16(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ float ldg(const float* p) { return *as_global(p); }
+
+// Activations exchanged between workgroups inside the kernel are written and read with
+// device-scope (cache-coherent) accesses, so that the grid barrier needs no cache flushes:
+// the L2 of each XCD is not coherent with the others for ordinary loads and stores.
+__device__ __forceinline__ float ld_coh(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_coh(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(int* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Batched coherent loads: request several, then wait once.  The value is defined only after
+// coh_wait() followed by coh_use() on it.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void coh_issue16(f32x4_t& v, const float* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
+}
+__device__ __forceinline__ void coh_issue4(float& v, const float* p) {
+  asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
+}
+__device__ __forceinline__ void coh_issue4(unsigned& v, const unsigned* p) {
+  asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
+}
+__device__ __forceinline__ void coh_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <typename T>
+__device__ __forceinline__ void coh_use(T& v) { asm volatile("" : "+v"(v)); }
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait
+// for outstanding global loads, so weight prefetches stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// Waits until every global load and store this wave has issued is complete.
+__device__ __forceinline__ void vm_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void stg_bf16(bf16* p, bf16 v) { *as_global(&p->v) = v.v; }
 
 struct LayerDev {
@@ -73,6 +111,7 @@ struct StepParams {
   int L;
   unsigned* bar;               // grid barrier counter, zero at launch
   int* err;                    // set to 1 if a barrier wait gives up
+  unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
 
 // LDS carve-up (floats)
@@ -113,63 +152,127 @@ __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int
   return s;
 }
 
-// Arrive-and-wait over all workgroups.  Every thread releases its writes, thread 0 arrives
-// and polls with a bounded spin; a wait that gives up (or sees another workgroup's give-up
-// flag) makes the whole workgroup return false so that every wave still exits.
-__device__ __forceinline__ bool grid_barrier(unsigned* bar, int* err, unsigned target, int* flag) {
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned spins = 0;
-    int good = 1;
-    while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      __builtin_amdgcn_s_sleep(1);
-      if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        good = 0;
-        break;
-      }
+// Arrive-and-wait over all workgroups without read-modify-write traffic, executed by ONE
+// wave (the service wave, which never has weight loads in flight: loads return in order, so
+// a poll issued behind a prefetch queue would wait for all of it).  Workgroup c stores the
+// barrier's epoch into flags[c]; the wave polls all flags until none is older.  The wave has
+// already waited for its own stores and exchanged data is accessed coherently, so no cache
+// maintenance is needed.  The poll is bounded: returns 0 if it gives up or sees another
+// workgroup's give-up flag, so that every wave of the grid still exits.
+__device__ __forceinline__ int grid_sync_wave(unsigned* flags, int* err, unsigned epoch, int cu, int ncu) {
+  const int lane = threadIdx.x & 63;
+  if (lane == 0) __hip_atomic_store(flags + cu, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  unsigned spins = 0;
+  for (;;) {
+    bool ok = true;
+    for (int base = 0; base < ncu; base += 256) {
+      unsigned f[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) coh_issue4(f[i], flags + min(base + i * 64 + lane, ncu - 1));
+      coh_wait();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { coh_use(f[i]); ok = ok && (f[i] >= epoch); }
     }
-    *flag = good;
+    if (__all(ok)) return 1;
+    if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+      __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return 0;
+    }
   }
-  __syncthreads();
-  __threadfence();
-  return *flag != 0;
 }
 
-// Sum over the workgroup's threads in a fixed order; every thread gets the total.
-__device__ __forceinline__ float sk_block_sum(float v, float* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float t = 0.f;
+// RMSNorm gains of a vector of at most 4096 elements, 8 groups of 8 per lane.  They are
+// constants, so the service wave fetches them before it waits at the grid barrier.
+struct SkGains { f32x4_t a[8], b[8]; };
+__device__ __forceinline__ void sk_load_gains(SkGains& G, const float* gain, int K) {
+  const int lane = threadIdx.x & 63, ngroups = K >> 3;
 #pragma unroll
-  for (int w = 0; w < SK_WAVES; ++w) t += red[w];
-  return t;
+  for (int i = 0; i < 8; ++i) {
+    const int k = min(i * 64 + lane, ngroups - 1) << 3;
+    G.a[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k));
+    G.b[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k + 4));
+  }
+}
+
+// xs <- RMSNorm(x; gains) for K <= 4096 in one pass: one batch of coherent loads, the sum of
+// squares over the wave, one write of the scaled values.  Executed by the service wave.
+__device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, int K, const SkGains& G, float eps) {
+  const int lane = threadIdx.x & 63, ngroups = K >> 3;
+  f32x4_t a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int k = min(i * 64 + lane, ngroups - 1) << 3;
+    coh_issue16(a[i], x + k);
+    coh_issue16(b[i], x + k + 4);
+  }
+  coh_wait();
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    coh_use(a[i]); coh_use(b[i]);
+    if (i * 64 + lane < ngroups) {
+      const f32x4_t u = a[i], v = b[i];
+      ss += u.x * u.x + u.y * u.y + u.z * u.z + u.w * u.w + v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  }
+  const float r = 1.0f / sqrtf(wave_sum(ss) / (float)K + eps);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int g = i * 64 + lane;
+    if (g < ngroups) {
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i] * G.a[i] * r;
+      *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = b[i] * G.b[i] * r;
+    }
+  }
 }
 
 // xs <- x or RMSNorm(x; gain), in the two-plane layout the 8-wide weight vectors read.
-__device__ __forceinline__ void sk_stage(float* xs, float* red, const float* x, int K, const float* gain, float eps) {
+// Executed by ONE wave (the service wave).  x was written by other workgroups in this
+// kernel: coherent 16-byte loads, 16 requested per lane before each wait.
+__device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int ngroups = K >> 3;
   float ss = 0.f;
-  for (int k = threadIdx.x; k < K; k += SK_THREADS) {
-    const float v = ldg(x + k);
-    ss = fmaf(v, v, ss);
-    xs[xs_index<8>(k, K)] = gain ? v * ldg(gain + k) : v;
+  for (int g0 = 0; g0 < ngroups; g0 += 512) {
+    f32x4_t a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = min(g0 + i * 64 + lane, ngroups - 1) << 3;      // out-of-range groups re-read the last one
+      coh_issue16(a[i], x + k);
+      coh_issue16(b[i], x + k + 4);
+    }
+    coh_wait();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      coh_use(a[i]); coh_use(b[i]);
+      const int g = g0 + i * 64 + lane;
+      if (g < ngroups) {
+        f32x4_t u = a[i], v = b[i];
+        ss += u.x * u.x + u.y * u.y + u.z * u.z + u.w * u.w + v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        if (gain) {
+          const f32x4_t g0v = *as_global(reinterpret_cast<const f32x4_t*>(gain + (g << 3)));
+          const f32x4_t g1v = *as_global(reinterpret_cast<const f32x4_t*>(gain + (g << 3) + 4));
+          u *= g0v; v *= g1v;
+        }
+        *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = u;
+        *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = v;
+      }
+    }
   }
   if (gain) {
-    const float tot = sk_block_sum(ss, red);
-    const float r = 1.0f / sqrtf(tot / (float)K + eps);
-    for (int k = threadIdx.x; k < K; k += SK_THREADS) xs[xs_index<8>(k, K)] *= r;
+    const float r = 1.0f / sqrtf(wave_sum(ss) / (float)K + eps);
+    for (int g = lane; g < ngroups; g += 64) {                      // each lane rescales what it wrote
+      f32x4_t* u = reinterpret_cast<f32x4_t*>(xs + (g << 2));
+      f32x4_t* v = reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2));
+      *u = *u * r; *v = *v * r;
+    }
   }
-  __syncthreads();
 }
 
 // A segment is one mat-vec phase of the step (QKV, O, gate/up, down of a kept layer, or the
 // LM head).  Rows [row0, row0+nrows) of its [N, K] matrix belong to this workgroup; a unit
-// is one 2048-element piece of one row and goes to wave (unit % SK_WAVES) in round
-// (unit / SK_WAVES).  The number of rounds is padded to a multiple of SK_PD so that the ring
+// is one 2048-element piece of one row and goes to streaming wave (unit % SK_SWAVES) in round
+// (unit / SK_SWAVES).  The number of rounds is padded to a multiple of SK_PD so that the ring
 // of in-flight loads keeps a static register assignment across segments.
 enum { SEG_QKV = 0, SEG_O = 1, SEG_GU = 2, SEG_DN = 3, SEG_HEAD = 4, SEG_NONE = 5 };
 struct SegDesc {
@@ -184,15 +287,24 @@ struct SegDesc {
 __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int ncu, int pair) {
   const int n = N / pair;
   d.K = K;
-  d.row0 = (int)(((long long)n * cu) / ncu) * pair;
-  d.nrows = (int)(((long long)n * (cu + 1)) / ncu) * pair - d.row0;
+  // 32-bit arithmetic (rows * workgroups < 2^31 is checked on the host): 64-bit division is
+  // emulated and costs dozens of registers
+  d.row0 = (int)((unsigned)(n * cu) / (unsigned)ncu) * pair;
+  d.nrows = (int)((unsigned)(n * (cu + 1)) / (unsigned)ncu) * pair - d.row0;
   d.nseg = K / SK_SEG;
   d.nunits = d.nrows * d.nseg;
-  const int nr = (d.nunits + SK_WAVES - 1) / SK_WAVES;
+  const int nr = (d.nunits + SK_SWAVES - 1) / SK_SWAVES;
   d.nr_pad = max(SK_PD, (nr + SK_PD - 1) / SK_PD * SK_PD);
 }
 
-__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
+__device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
+  d.m0 = uni(d.m0); d.m1 = uni(d.m1); d.m2 = uni(d.m2); d.gain = uni(d.gain); d.kv = uni(d.kv);
+  d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
+  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
+  return d;
+}
+
+__device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
   const DecParams& p = P.d;
   const int nq = p.Hq * p.hd, nkv = p.Hkv * p.hd;
   SegDesc d{};
@@ -227,47 +339,76 @@ __device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, 
   return d;
 }
 
-__device__ __forceinline__ const bf16* seg_row(const SegDesc& d, int r) {
-  if (d.inter) return ((r & 1) ? d.m1 : d.m0) + (size_t)(r >> 1) * d.K;
-  if (r < d.n0) return d.m0 + (size_t)r * d.K;
-  if (r < d.n0 + d.n1) return d.m1 + (size_t)(r - d.n0) * d.K;
-  return d.m2 + (size_t)(r - d.n0 - d.n1) * d.K;
+// Address of row r of a segment, as branch-free integer arithmetic (pointer selects would be
+// turned into an indexed table in scratch memory, and a scratch load in the request path
+// would drain the ring of in-flight loads).
+// Descriptor of segment s for this workgroup, every field in scalar registers.  Recomputed
+// where needed rather than carried through the segment loop.
+__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
+  return seg_uniform(seg_desc_raw(P, s, nk, kept, cu, ncu));
 }
 
-// Requests one round (4 x 16 B per lane) of a segment into a ring slot.
-__device__ __forceinline__ void sk_issue(const SegDesc& d, int round, uint4 (&b)[4]) {
-  const int u = round * SK_WAVES + (threadIdx.x >> 6);
-  if (d.kind != SEG_NONE && u < d.nunits) {
-    const int rl = u / d.nseg, sg = u - rl * d.nseg;
-    const bf16* p = seg_row(d, d.row0 + rl) + (size_t)sg * SK_SEG + (threadIdx.x & 63) * 8;
+__device__ __forceinline__ const bf16* seg_row(const SegDesc& d, int r) {
+  const unsigned long long b0 = reinterpret_cast<unsigned long long>(d.m0);
+  const unsigned long long b1 = reinterpret_cast<unsigned long long>(d.m1);
+  const unsigned long long b2 = reinterpret_cast<unsigned long long>(d.m2);
+  // which matrix, and which of its rows
+  const int m_stack = (r >= d.n0 ? 1 : 0) + (r >= d.n0 + d.n1 ? 1 : 0);
+  const int mat = d.inter ? (r & 1) : m_stack;
+  const int sub = (m_stack >= 1 ? d.n0 : 0) + (m_stack == 2 ? d.n1 : 0);
+  const int rr = d.inter ? (r >> 1) : r - sub;
+  const unsigned long long base = b0 + (mat >= 1 ? b1 - b0 : 0ull) + (mat == 2 ? b2 - b1 : 0ull);
+  return reinterpret_cast<const bf16*>(base + (unsigned long long)rr * (unsigned long long)d.K * 2ull);
+}
+
+// Requests one round (4 x 16 B per lane) of a segment into a ring slot.  Branch-free: the
+// row is addressed through a buffer descriptor that spans exactly that row, and a round that
+// does not exist (padding, past the last segment, or disabled) uses an offset beyond the
+// descriptor, for which the hardware returns zeros without touching memory.  Every call
+// therefore issues exactly four loads, which lets the compiler keep exact counts of the
+// loads in flight instead of draining the ring at every step.
+__device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enable, int wave, uint4 (&b)[4]) {
+  // everything but the lane offset is the same for the whole wave: keep it in scalar registers
+  const int u = uni(round * SK_SWAVES + wave);
+  const int valid = uni((int)(enable && u < d.nunits));   // SEG_NONE has no units
+  const int uu = valid ? u : 0;
+  const int nseg = uni(max(d.nseg, 1));
+  const int rl = uni(uu / nseg), sg = uu - rl * nseg;
+  const bf16* row = uni(seg_row(d, uni(d.row0) + rl));
+  const int row_bytes = uni(d.K * 2);
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(row), (short)0, row_bytes, 0x00020000);
+  const int off = valid ? sg * (SK_SEG * 2) + (int)(threadIdx.x & 63) * 16 : row_bytes;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) b[j] = ld_stream16(p + j * 512);
+  for (int j = 0; j < 4; ++j) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, off + j * 1024, 0, 2);   // 2 = non-temporal
+    b[j] = make_uint4(v.x, v.y, v.z, v.w);
   }
 }
 
 // Dot product of one ring slot with the staged activation vector -> psum[unit].
-__device__ __forceinline__ void sk_consume(const SegDesc& d, int round, const uint4 (&b)[4], const float* xs,
+__device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave, const uint4 (&b)[4], const float* xs,
                                            float* psum) {
-  const int u = round * SK_WAVES + (threadIdx.x >> 6);
-  if (u < d.nunits) {
-    const int lane = threadIdx.x & 63, K = d.K;
-    const int rl = u / d.nseg, sg = u - rl * d.nseg;
-    float acc = 0.f;
+  const int u = uni(round * SK_SWAVES + wave);
+  const int valid = uni((int)(u < d.nunits));
+  const int lane = threadIdx.x & 63, K = uni(d.K);
+  const int uu = valid ? u : 0;
+  const int nseg = uni(d.nseg);
+  const int rl = uni(uu / nseg), sg = uu - rl * nseg;
+  float acc = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = sg * SK_SEG + j * 512 + lane * 8;
-      const int q = (k >> 3) << 2;
-      const float4 x0 = *reinterpret_cast<const float4*>(xs + q);
-      const float4 x1 = *reinterpret_cast<const float4*>(xs + (K >> 1) + q);
-      const uint4 w = b[j];
-      acc = fmaf(__uint_as_float(w.x << 16), x0.x, acc); acc = fmaf(__uint_as_float(w.x & 0xffff0000u), x0.y, acc);
-      acc = fmaf(__uint_as_float(w.y << 16), x0.z, acc); acc = fmaf(__uint_as_float(w.y & 0xffff0000u), x0.w, acc);
-      acc = fmaf(__uint_as_float(w.z << 16), x1.x, acc); acc = fmaf(__uint_as_float(w.z & 0xffff0000u), x1.y, acc);
-      acc = fmaf(__uint_as_float(w.w << 16), x1.z, acc); acc = fmaf(__uint_as_float(w.w & 0xffff0000u), x1.w, acc);
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) psum[u] = acc;
+  for (int j = 0; j < 4; ++j) {
+    const int k = sg * SK_SEG + j * 512 + lane * 8;
+    const int q = (k >> 3) << 2;
+    const float4 x0 = *reinterpret_cast<const float4*>(xs + q);
+    const float4 x1 = *reinterpret_cast<const float4*>(xs + (K >> 1) + q);
+    const uint4 w = b[j];
+    acc = fmaf(__uint_as_float(w.x << 16), x0.x, acc); acc = fmaf(__uint_as_float(w.x & 0xffff0000u), x0.y, acc);
+    acc = fmaf(__uint_as_float(w.y << 16), x0.z, acc); acc = fmaf(__uint_as_float(w.y & 0xffff0000u), x0.w, acc);
+    acc = fmaf(__uint_as_float(w.z << 16), x1.x, acc); acc = fmaf(__uint_as_float(w.z & 0xffff0000u), x1.y, acc);
+    acc = fmaf(__uint_as_float(w.w << 16), x1.z, acc); acc = fmaf(__uint_as_float(w.w & 0xffff0000u), x1.w, acc);
   }
+  acc = wave_sum(acc);
+  if (valid && lane == 0) psum[u] = acc;
 }
 
 __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg) {
@@ -280,12 +421,19 @@ __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg)
 // Attention of workgroup (KV head g, split s): the waves = G query heads x (SK_WAVES/G) key groups,
 // lane = key for the scores, lane = (key subgroup, 8-dim chunk) for the weighted values.
 template <int HD>
-__device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit) {
+__device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
+                                             unsigned long long* stamps) {
   const DecParams& p = P.d;
+#define SK_ASTAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
+  SK_ASTAMP(6);
   constexpr int HALF = HD / 2, LPR = HD / 8, RPI = 64 / LPR;   // lanes per V row, V rows per load
+  constexpr int NKL = HD / 8;                                  // 16-byte loads per key row
   const int b = p.b, G = p.G, Pg = p.P;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int hq = wave % G, kg = wave / G, nkg = SK_WAVES / G;
+  const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
+  // workers: the first G * nkg streaming waves = G query heads x nkg key groups
+  const int nkg = SK_SWAVES / G;
+  const bool worker = wave < G * nkg;
+  const int hq = wave % G, kg = worker ? wave / G : nkg;       // kg == nkg: no tiles, no results
   const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps);
@@ -294,62 +442,92 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
   const int* pt = p.page_table + (size_t)b * p.max_pages;
   const size_t head_off = (size_t)g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
   const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
+  const int sub = lane / LPR, dc = lane % LPR;
 
-  // rotated queries of the G heads (pre-scaled), and the new key / value as stored
-  for (int i = tid; i < G * HALF; i += SK_THREADS) {
-    const int h = i / HALF, d = i - h * HALF;
-    const float x1 = qkv[(g * G + h) * HD + d], x2 = qkv[(g * G + h) * HD + d + HALF];
-    const float2 c = S.cs[d];
-    S.qs[h * HD + d] = (x1 * c.x - x2 * c.y) * p.qscale;
-    S.qs[h * HD + d + HALF] = (x2 * c.x + x1 * c.y) * p.qscale;
-  }
-  if (owns_new) {
-    const size_t base = (size_t)pt[pos / Pg] * p.page_elems + head_off + (size_t)(pos % Pg) * HD;
-    for (int d = tid; d < HALF; d += SK_THREADS) {
-      const float x1 = qkv[nq + g * HD + d], x2 = qkv[nq + g * HD + d + HALF];
-      const float2 c = S.cs[d];
-      const bf16 k1 = from_f32<bf16>(x1 * c.x - x2 * c.y), k2 = from_f32<bf16>(x2 * c.x + x1 * c.y);
-      stg_bf16(pool + base + d, k1); stg_bf16(pool + base + d + HALF, k2);
-      S.knew[d] = to_f32(k1); S.knew[d + HALF] = to_f32(k2);
+  // Requests for one 64-key tile: the key row of key t0+lane (lane = key), and the value
+  // rows in the (key subgroup, 8-dim chunk) layout.  Keys past the end re-read position pos.
+  // (the values are requested once the scores are done and reuse the registers of the keys)
+  uint4 kr[NKL], vr[NKL];
+  auto request_keys = [&](int t) {
+    const int ksafe = min((t << 6) + lane, pos);
+    const bf16* krow = pool + (size_t)pt[ksafe / Pg] * p.page_elems + head_off + (size_t)(ksafe % Pg) * HD;
+#pragma unroll
+    for (int c = 0; c < NKL; ++c) kr[c] = ld_global16(krow + c * 8);
+  };
+  // a tile is 64 / Pg whole pages (Pg = 16 is required on this path); their bases are
+  // wave-uniform, so the value loads are base + small per-lane offset.  Pages past the
+  // sequence's last one are clamped to it (in bounds; those keys get weight 0 and their
+  // values are zeroed below).
+  auto request_values = [&](int t) {
+    const int last_page = pos / Pg;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      const int kin = RPI * i;                         // first key of this load within the tile (+ sub)
+      const int page = uni(pt[min((t << 6) / Pg + kin / Pg, last_page)]);
+      const bf16* base = uni(pool + (size_t)page * p.page_elems + head_off + v_off) + (kin % Pg) * HD;
+      vr[i] = ld_global16(base + sub * HD + dc * 8);
     }
-    for (int d = tid; d < HD; d += SK_THREADS) {
-      const bf16 v = from_f32<bf16>(qkv[nq + nkv + g * HD + d]);
-      stg_bf16(pool + base + v_off + d, v);
-      S.vnew[d] = to_f32(v);
+  };
+  int t = t_first + kg;
+  request_keys(min(t, max(tiles - 1, 0)));          // a wave without a tile still issues (harmless) loads
+
+  // this step's q (G heads), k and v of the KV head: one batch of coherent loads
+  {
+    float q1, q2, k1, k2, vv;
+    const int iq = min(tid, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
+    const int dk = min(tid, HALF - 1), dv = min(tid, HD - 1);
+    coh_issue4(q1, qkv + (g * G + hh) * HD + dq);
+    coh_issue4(q2, qkv + (g * G + hh) * HD + dq + HALF);
+    coh_issue4(k1, qkv + nq + g * HD + dk);
+    coh_issue4(k2, qkv + nq + g * HD + dk + HALF);
+    coh_issue4(vv, qkv + nq + nkv + g * HD + dv);
+    coh_wait();
+    SK_ASTAMP(7);
+    coh_use(q1); coh_use(q2); coh_use(k1); coh_use(k2); coh_use(vv);
+    if (tid < G * HALF) {                            // rotate and pre-scale the queries
+      const float2 c = S.cs[dq];
+      S.qs[hh * HD + dq] = (q1 * c.x - q2 * c.y) * p.qscale;
+      S.qs[hh * HD + dq + HALF] = (q2 * c.x + q1 * c.y) * p.qscale;
+    }
+    if (owns_new) {                                  // append the new key / value; keep the stored values in LDS
+      const size_t base = (size_t)pt[pos / Pg] * p.page_elems + head_off + (size_t)(pos % Pg) * HD;
+      if (tid < HALF) {
+        const float2 c = S.cs[dk];
+        const bf16 r1 = from_f32<bf16>(k1 * c.x - k2 * c.y), r2 = from_f32<bf16>(k2 * c.x + k1 * c.y);
+        stg_bf16(pool + base + dk, r1); stg_bf16(pool + base + dk + HALF, r2);
+        S.knew[dk] = to_f32(r1); S.knew[dk + HALF] = to_f32(r2);
+      }
+      if (tid < HD) {
+        const bf16 r = from_f32<bf16>(vv);
+        stg_bf16(pool + base + v_off + dv, r);
+        S.vnew[dv] = to_f32(r);
+      }
     }
   }
-  __syncthreads();
+  lds_barrier();
 
   float m = -INFINITY, l = 0.f, o[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) o[e] = 0.f;
   const float* q = S.qs + hq * HD;
   float* ps = S.ps + wave * 64;
-  const int sub = lane / LPR, dc = lane % LPR;
 
-  for (int t = t_first + kg; t < t_last; t += nkg) {
+  for (; t < t_last; t += nkg) {
     const int t0 = t << 6;
     const int key = t0 + lane;
     const bool valid = key < nkeys;
-    const int ksafe = valid ? key : pos;
-    const bf16* krow = pool + (size_t)pt[ksafe / Pg] * p.page_elems + head_off + (size_t)(ksafe % Pg) * HD;
     float sc = 0.f;
 #pragma unroll
-    for (int hf = 0; hf < HD / 32; ++hf) {             // 32 dims (4 x 16 B) of the key row at a time
-      uint4 kr[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) kr[c] = ld_global16(krow + hf * 32 + c * 8);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const float4 q0 = *reinterpret_cast<const float4*>(q + hf * 32 + c * 8);
-        const float4 q1 = *reinterpret_cast<const float4*>(q + hf * 32 + c * 8 + 4);
-        const uint4 w = kr[c];
-        sc = fmaf(__uint_as_float(w.x << 16), q0.x, sc); sc = fmaf(__uint_as_float(w.x & 0xffff0000u), q0.y, sc);
-        sc = fmaf(__uint_as_float(w.y << 16), q0.z, sc); sc = fmaf(__uint_as_float(w.y & 0xffff0000u), q0.w, sc);
-        sc = fmaf(__uint_as_float(w.z << 16), q1.x, sc); sc = fmaf(__uint_as_float(w.z & 0xffff0000u), q1.y, sc);
-        sc = fmaf(__uint_as_float(w.w << 16), q1.z, sc); sc = fmaf(__uint_as_float(w.w & 0xffff0000u), q1.w, sc);
-      }
+    for (int c = 0; c < NKL; ++c) {
+      const float4 q0 = *reinterpret_cast<const float4*>(q + c * 8);
+      const float4 q1 = *reinterpret_cast<const float4*>(q + c * 8 + 4);
+      const uint4 w = kr[c];
+      sc = fmaf(__uint_as_float(w.x << 16), q0.x, sc); sc = fmaf(__uint_as_float(w.x & 0xffff0000u), q0.y, sc);
+      sc = fmaf(__uint_as_float(w.y << 16), q0.z, sc); sc = fmaf(__uint_as_float(w.y & 0xffff0000u), q0.w, sc);
+      sc = fmaf(__uint_as_float(w.z << 16), q1.x, sc); sc = fmaf(__uint_as_float(w.z & 0xffff0000u), q1.y, sc);
+      sc = fmaf(__uint_as_float(w.w << 16), q1.z, sc); sc = fmaf(__uint_as_float(w.w & 0xffff0000u), q1.w, sc);
     }
+    request_values(t);
     if (t0 <= pos && pos < t0 + 64) {
       // the key appended in this step: take it from LDS (the stored, rounded value)
       float part = 0.f;
@@ -368,46 +546,40 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
     ps[lane] = pj;
     // weighted values: load i covers keys t0 + RPI*i + sub, dims dc*8 .. dc*8+7
 #pragma unroll
-    for (int vh = 0; vh < LPR / 4; ++vh) {
-      uint4 vr[4];
+    for (int i = 0; i < NKL; ++i) {
+      const int jj = RPI * i + sub;
+      const float pw = ps[jj];
+      float v[8];
+      const uint4 w = vr[i];
+      v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+      v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+      v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+      v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+      if (t0 + jj == pos) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int kv = t0 + RPI * (vh * 4 + i) + sub;
-        const int kvs = kv < nkeys ? kv : pos;
-        vr[i] = ld_global16(pool + (size_t)pt[kvs / Pg] * p.page_elems + head_off + v_off + (size_t)(kvs % Pg) * HD +
-                            dc * 8);
+        for (int e = 0; e < 8; ++e) v[e] = S.vnew[dc * 8 + e];
+      } else if (t0 + jj > pos) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.f;        // never-written slot: do not let a NaN pattern through
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int jj = RPI * (vh * 4 + i) + sub;
-        const float pw = ps[jj];
-        float v[8];
-        const uint4 w = vr[i];
-        v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
-        v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
-        v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
-        v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
-        if (t0 + jj == pos) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = S.vnew[dc * 8 + e];
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = fmaf(pw, v[e], o[e]);
-      }
+      for (int e = 0; e < 8; ++e) o[e] = fmaf(pw, v[e], o[e]);
     }
+    if (t + nkg < t_last) request_keys(t + nkg);
   }
+  SK_ASTAMP(8);
   // fold the key subgroups: afterwards lanes 0..LPR-1 hold dims lane*8 .. lane*8+7
 #pragma unroll
   for (int off = LPR; off < 64; off <<= 1)
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] += __shfl_xor(o[e], off, 64);
   float* mb = S.mb + wave * (HD + 2);
-  if (lane < LPR) {
+  if (worker && lane < LPR) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) mb[lane * 8 + e] = o[e];
   }
-  if (lane == 0) { mb[HD] = m; mb[HD + 1] = l; }
-  __syncthreads();
+  if (worker && lane == 0) { mb[HD] = m; mb[HD + 1] = l; }
+  lds_barrier();
   // key group 0 of each head merges the groups in order and writes the split's partial
   if (kg == 0) {
     float M = -INFINITY;
@@ -425,63 +597,115 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
     }
     const int H = g * G + hq;
     float* po = p.part_o + (((size_t)b * p.Hq + H) * S_MAX + s) * HD;
-    po[lane] = a0;
-    if (HD > 64) po[lane + 64] = a1;
+    st_coh(po + lane, a0);
+    if (HD > 64) st_coh(po + lane + 64, a1);
     if (lane == 0) {
       float* pml = p.part_ml + (((size_t)b * p.Hq + H) * S_MAX + s) * 2;
-      pml[0] = M; pml[1] = den;
+      st_coh(pml, M); st_coh(pml + 1, den);
     }
   }
-}
-
-// xs <- attention output merged over the splits (fixed order), two-plane layout.
-__device__ __forceinline__ void sk_stage_attn(const StepParams& P, const SkLds& S, int nsplit) {
-  const DecParams& p = P.d;
-  const int nq = p.Hq * p.hd;
-  for (int e = threadIdx.x; e < nq; e += SK_THREADS) {
-    const int H = e / p.hd, d = e - H * p.hd;
-    const float* pml = p.part_ml + ((size_t)p.b * p.Hq + H) * S_MAX * 2;
-    const float* po = p.part_o + ((size_t)p.b * p.Hq + H) * S_MAX * p.hd;
-    float M = -INFINITY;
-    for (int t = 0; t < nsplit; ++t) M = fmaxf(M, pml[2 * t]);
-    float den = 0.f, a = 0.f;
-    for (int t = 0; t < nsplit; ++t) {
-      const float lt = pml[2 * t + 1];
-      if (lt > 0.f) {
-        const float w = expf(pml[2 * t] - M);
-        den = fmaf(lt, w, den);
-        a = fmaf(po[t * p.hd + d], w, a);
+  // the last split of this KV head to finish merges all splits in split order (the result
+  // does not depend on which one that is) and writes the attention output
+  vm_wait_all();
+  lds_barrier();
+  SK_ASTAMP(9);
+  if (tid == 0) {
+    const unsigned old = __hip_atomic_fetch_add(p.attn_cnt + b * p.Hkv + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (old == (unsigned)(nsplit - 1));
+    if (last) __hip_atomic_store(p.attn_cnt + b * p.Hkv + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    S.flag[1] = last;
+  }
+  lds_barrier();
+  SK_ASTAMP(10);
+  if (uni(S.flag[1]) && kg == 0) {
+    const int H = g * G + hq;
+    const float* pml = p.part_ml + ((size_t)b * p.Hq + H) * S_MAX * 2;
+    const float* po = p.part_o + ((size_t)b * p.Hq + H) * S_MAX * HD;
+    float den = 0.f, a0 = 0.f, a1 = 0.f, M = -INFINITY;
+    // 8 splits per batch of coherent loads; a running maximum rescales between batches
+    for (int b0 = 0; b0 < nsplit; b0 += 8) {
+      float mv[8], lv[8], o0[8], o1[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int ts = min(b0 + i, nsplit - 1);
+        coh_issue4(mv[i], pml + 2 * ts);
+        coh_issue4(lv[i], pml + 2 * ts + 1);
+        coh_issue4(o0[i], po + ts * HD + lane);
+        coh_issue4(o1[i], po + ts * HD + (HD > 64 ? lane + 64 : lane));
+      }
+      coh_wait();
+      float Mb = M;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { coh_use(mv[i]); coh_use(lv[i]); coh_use(o0[i]); coh_use(o1[i]); if (b0 + i < nsplit) Mb = fmaxf(Mb, mv[i]); }
+      const float resc = expf(M - Mb);               // 0 for the first batch (M = -inf)
+      den *= resc; a0 *= resc; a1 *= resc;
+      M = Mb;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (b0 + i < nsplit && lv[i] > 0.f) {
+          const float w = expf(mv[i] - M);
+          den = fmaf(lv[i], w, den);
+          a0 = fmaf(o0[i], w, a0);
+          a1 = fmaf(o1[i], w, a1);
+        }
       }
     }
-    S.xs[xs_index<8>(e, nq)] = a / den;
+    float* out = p.attn + (size_t)b * nq + H * HD;
+    st_coh(out + lane, a0 / den);
+    if (HD > 64) st_coh(out + lane + 64, a1 / den);
+    vm_wait_all();
   }
-  __syncthreads();
+  SK_ASTAMP(11);
+#undef SK_ASTAMP
+}
+
+// The service wave's part of the attention phase: it only keeps step with the workgroup
+// barriers of sk_attention.
+__device__ __forceinline__ void sk_attention_service() {
+  lds_barrier();
+  lds_barrier();
+  lds_barrier();
+  lds_barrier();
 }
 
 // ---------------------------------------------------------------------------------------
+// Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds
+// (32 KB) in flight that runs on across phase boundaries, so HBM stays busy while the
+// workgroups synchronise.  The last wave is the service wave: it turns the partial sums of a
+// finished phase into its outputs, takes part in the grid barrier and stages the next
+// phase's input vector into LDS.  It never has weight loads in flight, which matters because
+// a wave's loads return in order: a barrier poll or an input load issued behind a prefetch
+// queue would wait for all of it.
 template <int HD>
 __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   extern __shared__ __align__(16) float smem_f[];
   const DecParams& p = P.d;
-  const int cu = blockIdx.x, ncu = gridDim.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int cu = blockIdx.x, ncu = gridDim.x, tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
+  const bool service = wave == SK_SWAVES;
   const int b = p.b, D = p.D, F = p.F, nq = p.Hq * HD, nkv = p.Hkv * HD;
   const SkLds S = sk_carve(smem_f, D, nq, F, p.G, HD);
-  uint4 buf[SK_PD][4];
-  unsigned bar_target = 0;
+  unsigned epoch = 0;
   float* h = p.h + (size_t)b * D;
   const int nk = uni(P.n_kept[b]);
   const int* kept = P.kept + (size_t)b * P.L;
   const int pos = uni(p.len[b]);
   const int nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
   // attention splits: enough workgroups that each wave sees about one 64-key tile
-  const int nkg = SK_WAVES / p.G;
+  const int nkg = max(1, SK_SWAVES / p.G);
   int nsplit = (tiles + nkg - 1) / nkg;
-  nsplit = max(1, min(nsplit, min(SK_SMAX, ncu / p.Hkv)));
+  nsplit = max(1, min(nsplit, min(S_MAX, ncu / p.Hkv)));
 
-#define SK_BARRIER()                                                                   \
+#define SK_STAMP(slot)                                                                 \
   do {                                                                                 \
-    bar_target += (unsigned)ncu;                                                       \
-    if (!grid_barrier(P.bar, P.err, bar_target, S.flag)) return;                       \
+    if (P.tdbg && cu == 0 && tid == SK_SWAVES * 64) P.tdbg[s * SK_TSLOTS + (slot)] = wall_clock64(); \
+  } while (0)
+  // grid barrier: service wave synchronises, then the workgroup barrier hands the verdict on
+#define SK_GRID_SYNC()                                                                 \
+  do {                                                                                 \
+    if (service) {                                                                     \
+      const int ok_ = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);                  \
+      if (lane == 0) *S.flag = ok_;                                                    \
+    }                                                                                  \
   } while (0)
 
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
@@ -489,111 +713,145 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
     int tok = uni(p.tokens[b]);
     tok = min(max(tok, 0), p.V - 1);
     const bf16* row = reinterpret_cast<const bf16*>(p.embed) + (size_t)tok * D;
-    const int r0 = (int)(((long long)D * cu) / ncu), r1 = (int)(((long long)D * (cu + 1)) / ncu);
-    for (int k = r0 + tid; k < r1; k += SK_THREADS) h[k] = to_f32(row[k]);
+    const int r0 = (int)((unsigned)(D * cu) / (unsigned)ncu), r1 = (int)((unsigned)(D * (cu + 1)) / (unsigned)ncu);
+    for (int k = r0 + tid; k < r1; k += SK_THREADS) st_coh(h + k, to_f32(row[k]));
     for (int i = tid; i < HD / 2; i += SK_THREADS) {
       const double a = (double)pos * p.theta[i];
       S.cs[i] = make_float2((float)cos(a), (float)sin(a));
     }
   }
+  vm_wait_all();                                   // this wave's h rows are out
 
-  // ---- the segments: one ring of SK_PD in-flight rounds per wave runs through all of them
   const int nsegs = 4 * nk + 1;
-  SegDesc cur = seg_desc(P, 0, nk, kept, cu, ncu);
-  SegDesc nxt = seg_desc(P, 1, nk, kept, cu, ncu);
-#pragma unroll
-  for (int j = 0; j < SK_PD; ++j) sk_issue(cur, j, buf[j]);
+  const bool attn_wg = cu < p.Hkv * nsplit;
 
-  for (int s = 0; s < nsegs; ++s) {
-    // -- entering the segment: everything it reads was written before this barrier
-    SK_BARRIER();
-    const float* xsrc = S.xs;
-    if (cur.kind == SEG_O) {
-      // only SK_PD_ATT ring slots stay in flight across attention (it needs the registers);
-      // the upper slots hold nothing here and are refilled right after
+  // The two roles run separate loops (so that the service wave carries no ring registers and
+  // the streaming waves no staging registers) with the same sequence of workgroup barriers.
+  if (service) {
+    lds_barrier();                                 // every wave's stores of the embedding are complete
+    for (int s = 0; s < nsegs; ++s) {
+      const SegDesc cur = seg_desc(P, s, nk, kept, cu, ncu);
+      SK_STAMP(0);
+      SkGains gains;
+      const bool fast_norm = cur.gain != nullptr && D <= 4096;
+      if (fast_norm) sk_load_gains(gains, cur.gain, D);
+      SK_GRID_SYNC();                              // everything the segment reads has been written
+      SK_STAMP(1);
+      if (cur.kind == SEG_O) {
+        lds_barrier();
+        if (uni(*S.flag) == 0) return;
+        if (attn_wg) sk_attention_service();
+        lds_barrier();                             // the attention output of this workgroup is out
+        SK_GRID_SYNC();
+        SK_STAMP(2);
+        sk_stage_wave(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f);
+      } else if (cur.kind == SEG_DN) {
+        sk_stage_wave(S.zs, p.z + (size_t)b * F, F, nullptr, 0.f);
+      } else if (fast_norm) {
+        sk_stage_norm_wave(S.xs, h, D, gains, p.eps);
+      } else {
+        sk_stage_wave(S.xs, h, D, cur.gain, p.eps);
+      }
+      SK_STAMP(3);
+      lds_barrier();                               // input vector staged; barrier verdict visible
+      if (uni(*S.flag) == 0) return;
+      lds_barrier();                               // partial sums complete
+      SK_STAMP(4);
+      // results of the segment
+      if (cur.kind == SEG_QKV) {
+        float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
+        for (int r = lane; r < cur.nrows; r += 64) st_coh(out + cur.row0 + r, sk_row_sum(S.psum, r, cur.nseg));
+      } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
+        for (int r = lane; r < cur.nrows; r += 64)
+          st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg));
+      } else if (cur.kind == SEG_GU) {
+        float* z = p.z + (size_t)b * F;
+        for (int r = lane; r < cur.nrows / 2; r += 64) {
+          const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg);
+          st_coh(z + cur.row0 / 2 + r, siluf(gt) * up);
+        }
+      } else {
+        float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
+        Best best{-INFINITY, 0x7fffffff};
+        for (int r = lane; r < cur.nrows; r += 64) {
+          const float v = sk_row_sum(S.psum, r, cur.nseg);
+          if (lg) lg[cur.row0 + r] = v;
+          const Best c{v, cur.row0 + r};
+          if (better(c, best)) best = c;
+        }
 #pragma unroll
-      for (int j = SK_PD_ATT; j < SK_PD; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) buf[j][i] = make_uint4(0, 0, 0, 0);
-      if (cu < p.Hkv * nsplit) sk_attention<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit);
-#pragma unroll
-      for (int j = SK_PD_ATT; j < SK_PD; ++j) sk_issue(cur, j, buf[j]);
-      SK_BARRIER();
-      sk_stage_attn(P, S, nsplit);
-    } else if (cur.kind == SEG_DN) {
-      sk_stage(S.zs, S.red, p.z + (size_t)b * F, F, nullptr, 0.f);
-      xsrc = S.zs;
-    } else {
-      sk_stage(S.xs, S.red, h, D, cur.gain, p.eps);
+        for (int o = 32; o > 0; o >>= 1) {
+          const Best c{__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
+          if (better(c, best)) best = c;
+        }
+        if (lane == 0) {
+          Best* dst = p.arg_part + (size_t)b * ARG_MAX_WG + cu;
+          st_coh(&dst->v, best.v); st_coh(&dst->i, best.i);
+        }
+      }
+      vm_wait_all();                               // the stores are complete before this workgroup arrives
+      SK_STAMP(5);
     }
-    // -- stream the segment's weights through the ring
-    for (int r0 = 0; r0 < cur.nr_pad; r0 += SK_PD) {
-#pragma unroll
-      for (int j = 0; j < SK_PD; ++j) {
-        sk_consume(cur, r0 + j, buf[j], xsrc, S.psum);
-        const int t = r0 + j + SK_PD;
-        if (t < cur.nr_pad) sk_issue(cur, t, buf[j]);
-        else if (nxt.kind != SEG_O || j < SK_PD_ATT) sk_issue(nxt, t - cur.nr_pad, buf[j]);
-      }
-    }
-    __syncthreads();
-    // -- results of the segment
-    if (cur.kind == SEG_QKV) {
-      float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
-      for (int r = tid; r < cur.nrows; r += SK_THREADS) out[cur.row0 + r] = sk_row_sum(S.psum, r, cur.nseg);
-    } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
-      for (int r = tid; r < cur.nrows; r += SK_THREADS) h[cur.row0 + r] += sk_row_sum(S.psum, r, cur.nseg);
-    } else if (cur.kind == SEG_GU) {
-      float* z = p.z + (size_t)b * F;
-      for (int r = tid; r < cur.nrows / 2; r += SK_THREADS) {
-        const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg);
-        z[cur.row0 / 2 + r] = siluf(gt) * up;
-      }
-    } else {
-      float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
-      Best best{-INFINITY, 0x7fffffff};
-      for (int r = tid; r < cur.nrows; r += SK_THREADS) {
-        const float v = sk_row_sum(S.psum, r, cur.nseg);
-        if (lg) lg[cur.row0 + r] = v;
-        const Best c{v, cur.row0 + r};
-        if (better(c, best)) best = c;
-      }
+    // greedy token: workgroup 0 reduces the per-workgroup candidates
+    const int ok = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);
+    if (ok && cu == 0) {
+      Best bb{-INFINITY, 0x7fffffff};
+      const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
+      for (int i = lane; i < ncu; i += 64) { const Best c{ld_coh(&ap[i].v), ld_coh(&ap[i].i)}; if (better(c, bb)) bb = c; }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) {
-        const Best c{__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
-        if (better(c, best)) best = c;
+        const Best c{__shfl_xor(bb.v, o, 64), __shfl_xor(bb.i, o, 64)};
+        if (better(c, bb)) bb = c;
       }
-      Best* wb = reinterpret_cast<Best*>(S.psum);          // psum is free once every thread has read its rows
-      __syncthreads();
-      if (lane == 0) wb[wave] = best;
-      __syncthreads();
-      if (tid == 0) {
-        Best r = wb[0];
-        for (int w = 1; w < SK_WAVES; ++w) if (better(wb[w], r)) r = wb[w];
-        p.arg_part[(size_t)b * ARG_MAX_WG + cu] = r;
+      if (lane == 0) {
+        if (p.token_out) p.token_out[b] = bb.i;
+        if (p.advance_len) p.len[b] = pos + 1;
       }
     }
-    cur = nxt;
-    nxt = seg_desc(P, s + 2, nk, kept, cu, ncu);
-  }
-
-  // ---- greedy token: workgroup 0 reduces the per-workgroup candidates
-  SK_BARRIER();
-  if (cu == 0 && wave == 0) {
-    Best bb{-INFINITY, 0x7fffffff};
-    const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
-    for (int i = lane; i < ncu; i += 64) { const Best c = ap[i]; if (better(c, bb)) bb = c; }
+  } else {
+    uint4 buf[SK_PD][4];
+    {
+      const SegDesc first = seg_desc(P, 0, nk, kept, cu, ncu);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const Best c{__shfl_xor(bb.v, o, 64), __shfl_xor(bb.i, o, 64)};
-      if (better(c, bb)) bb = c;
+      for (int j = 0; j < SK_PD; ++j) sk_issue(first, j, true, wave, buf[j]);
     }
-    if (lane == 0) {
-      if (p.token_out) p.token_out[b] = bb.i;
-      if (p.advance_len) p.len[b] = pos + 1;
+    lds_barrier();
+    for (int s = 0; s < nsegs; ++s) {
+      const SegDesc cur = seg_desc(P, s, nk, kept, cu, ncu);
+      const SegDesc nxt = seg_desc(P, s + 1, nk, kept, cu, ncu);
+      const float* xsrc = cur.kind == SEG_DN ? S.zs : S.xs;
+      if (cur.kind == SEG_O) {
+        lds_barrier();
+        if (uni(*S.flag) == 0) return;
+        // only the SK_PD_EARLY lower ring slots stay in flight across attention (it needs the
+        // registers); the upper slots hold nothing here and are refilled right after
+#pragma unroll
+        for (int j = SK_PD_EARLY; j < SK_PD; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) buf[j][i] = make_uint4(0, 0, 0, 0);
+        if (attn_wg) sk_attention<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit,
+                                      (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr);
+#pragma unroll
+        for (int j = SK_PD_EARLY; j < SK_PD; ++j) sk_issue(cur, j, true, wave, buf[j]);
+        lds_barrier();
+      }
+      lds_barrier();                               // input vector staged
+      if (uni(*S.flag) == 0) return;
+      for (int r0 = 0; r0 < cur.nr_pad; r0 += SK_PD) {
+#pragma unroll
+        for (int j = 0; j < SK_PD; ++j) {
+          sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum);
+          const int t = r0 + j + SK_PD;
+          const bool ahead = t >= cur.nr_pad;                 // the request belongs to the next segment
+          sk_issue(ahead ? nxt : cur, ahead ? t - cur.nr_pad : t, !ahead || nxt.kind != SEG_O || j < SK_PD_EARLY, wave,
+                   buf[j]);
+        }
+      }
+      lds_barrier();                               // partial sums complete
     }
   }
-#undef SK_BARRIER
+#undef SK_GRID_SYNC
+#undef SK_STAMP
 }
 
 }  // namespace first

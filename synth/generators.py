@@ -61,7 +61,7 @@ CONFIGS: Dict[str, ModelDesc] = {
     # widths that are multiples of 2048: shapes the persistent whole-step decode kernel accepts
     "step_hd128": ModelDesc(3, 2048, 16, 4, 128, 4096, 5003, dtype="bf16"),
     "step_hd64": ModelDesc(2, 2048, 32, 8, 64, 2048, 3001, dtype="bf16"),
-    "step_g8": ModelDesc(2, 2048, 16, 2, 128, 2048, 2999, dtype="bf16"),
+    "step_g2": ModelDesc(2, 2048, 16, 8, 128, 2048, 2999, dtype="bf16"),
     "step_mha": ModelDesc(2, 2048, 16, 16, 128, 2048, 2999, dtype="bf16"),
 }
 

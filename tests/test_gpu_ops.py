@@ -58,3 +58,18 @@ def test_bad_arguments_are_rejected():
     with pytest.raises(P.FirstError) as e:
         P.op_gemv(W, x, y)
     assert e.value.code == -1
+
+
+@pytest.mark.parametrize("m,n,k", [(1, 1, 8), (70, 200, 136), (129, 257, 520), (300, 130, 1416)])
+def test_gemm_nt_fp32_activations_split_precision(m, n, k):
+    """fp32 activations against bf16 weights: the hi/lo split must recover ~16 bits of A."""
+    import paper_2410_12513_amd as P
+    A = _rand((m, k), 7, torch.float32)
+    W = _rand((n, k), 8, torch.bfloat16)
+    ref = A.double() @ W.double().T
+    Cd = torch.full((m, n), float("nan"), dtype=torch.float32, device="cuda")
+    P.op_gemm_nt_f32a(A.cuda(), W.cuda(), Cd)
+    torch.cuda.synchronize()
+    scale = float((A.double().abs() @ W.double().abs().T).max())
+    err = float((Cd.cpu().double() - ref).abs().max())
+    assert err <= 1.5e-5 * scale, err / scale          # a bf16-rounded A alone would give ~2e-3
