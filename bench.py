@@ -8,8 +8,8 @@ last layers kept) fed through first_set_mask; prefill + route runs once per mask
 timed region, so weights, KV and tokens are resident in HBM when timing starts.
 
 Prints ONE JSON line: decode tokens/s (headline skip fraction), a sweep over the skip
-fractions, the HBM roofline of the dominant kernel (gate/up mat-vec) measured with events on
-the library's stream, and the CPU oracle timed on this machine's host cores.
+fractions, the HBM roofline of the dominant kernel (the persistent whole-step kernel) measured
+with events on the library's stream, and the CPU oracle timed on this machine's host cores.
 """
 import argparse
 import json
@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--headline-skip", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--per-op", action="store_true", help="one kernel per fused op instead of the persistent kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -70,6 +71,7 @@ def main():
     ctx = P.FirstContext(desc, weights, router, max_batch=1, max_seq_len=n_prompt + W + K + 16, stream=stream)
     if args.no_graph:
         ctx.set_option(1, 0)
+    ctx.set_option(3, 0 if args.per_op else 1)       # persistent kernel or error: never a silent fallback
     logits = torch.zeros(1, desc.vocab, device="cuda")
     tok = torch.zeros(1, dtype=torch.int32, device="cuda")
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -100,31 +102,40 @@ def main():
                       "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)})
     head = min(sweep, key=lambda r: abs(r["skip_fraction"] - args.headline_skip))
 
-    # dominant kernel: gate/up mat-vec of one layer; rotate over layers so no launch finds
-    # its weights in cache
+    # Dominant kernel.  With the persistent path the whole step is ONE kernel (k_step), so its
+    # launch duration is the step time measured above with events on the library's stream;
+    # with the per-op path it is the gate/up mat-vec, timed below over all layers' weights.
+    persistent = head["ms_per_step"] is not None and not args.per_op
     reps = max(64, K)
     for i in range(8):
         ctx.op_gateup(i % L)
     ctx.sync()
     ev0.record(stream)
     for i in range(reps):
-        ctx.op_gateup(i % L)
+        ctx.op_gateup(i % L)                                      # rotate: no launch finds its weights cached
     ev1.record(stream)
     ev1.synchronize()
     gu_ms = ev0.elapsed_time(ev1) / reps
     gu_bytes = 2 * desc.d_ffn * desc.d_model * desc.bytes_per_elem       # both matrices, once
-    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+    per_op = {"kernel": "k_gateup (RMSNorm + gate/up mat-vec + SiLU*up of one layer, per-op path)",
+              "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3, "GB/s": gu_bytes / (gu_ms * 1e-3) / 1e9}
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gateup_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload)
+            traffic = json.load(open(tpath)).get("k_step" if persistent else "k_gateup")
         except Exception:
             traffic = None
-    roofline = {"bound": "hbm", "kernel": "k_gateup (RMSNorm + gate/up mat-vec + SiLU*up, one layer)",
-                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": traffic, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3,
-                "launches_timed": reps}
+    if persistent:
+        achieved = head["step_bytes"] / (head["ms_per_step"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "k_step (whole decode step of the kept layers + LM head as one persistent kernel)",
+                    "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": traffic, "bytes_per_launch": head["step_bytes"],
+                    "avg_launch_us": head["ms_per_step"] * 1e3, "launches_timed": K, "per_op_gateup": per_op}
+    else:
+        roofline = {"bound": "hbm", "kernel": per_op["kernel"], "achieved": per_op["GB/s"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": per_op["GB/s"] / HBM_PEAK_GBS, "traffic": traffic,
+                    "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3, "launches_timed": reps}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -138,7 +149,8 @@ def main():
         "config": {"workload": f"{args.workload}: {wl['model']} Llama-style decoder, batch 1, prompt {n_prompt}, "
                                f"greedy decode, seeded skip mask (first/last kept)",
                    "skip_fraction": head["skip_fraction"], "kept_layers": head["kept_layers"],
-                   "kv_page_tokens": 16, "graph": not args.no_graph},
+                   "kv_page_tokens": 16, "graph": not args.no_graph,
+                   "decode_path": "per-op kernels" if args.per_op else "persistent kernel"},
         "hbm_roofline_frac_step": head["hbm_frac"],
         "sweep": sweep,
         "prefill": {"tokens": n_prompt, "ms": prefill_ms,
