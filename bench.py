@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--headline-skip", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--per-op", action="store_true", help="one kernel per fused op instead of the persistent kernel")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -136,6 +138,14 @@ def main():
         roofline = {"bound": "hbm", "kernel": per_op["kernel"], "achieved": per_op["GB/s"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": per_op["GB/s"] / HBM_PEAK_GBS, "traffic": traffic,
                     "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3, "launches_timed": reps}
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
