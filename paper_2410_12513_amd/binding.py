@@ -211,10 +211,11 @@ class FirstContext:
 
     def step_timing(self):
         """Timestamps [phases, 6] (100 MHz ticks) of the last persistent-kernel step."""
-        cap = (4 * self.desc.n_layers + 1) * 12
+        cap = (4 * self.desc.n_layers + 1) * 12 + 2 * 1024
         arr = (C.c_uint64 * cap)()
         n = C.c_int32()
         self._chk(self.lib.first_step_timing(self.h, arr, C.c_int32(cap), C.byref(n)))
+        self.barrier_trace = list(arr[n.value:n.value + 2 * 256])     # arrival / release per workgroup (timing aid)
         return [list(arr[i:i + 12]) for i in range(0, n.value, 12)]
 
     def num_pages(self) -> int:

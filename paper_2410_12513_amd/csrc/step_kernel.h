@@ -70,6 +70,11 @@ __device__ __forceinline__ void coh_issue4(float& v, const float* p) {
 __device__ __forceinline__ void coh_issue4(unsigned& v, const unsigned* p) {
   asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
 }
+// Ordinary (cached) 16-byte load with the same request / wait / use protocol: where register
+// pressure matters this keeps the compiler from overlapping more requests than intended.
+__device__ __forceinline__ void gl_issue16(u32x4_t& v, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(as_global(reinterpret_cast<const u32x4_t*>(p))) : "memory");
+}
 __device__ __forceinline__ void coh_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 template <typename T>
 __device__ __forceinline__ void coh_use(T& v) { asm volatile("" : "+v"(v)); }
@@ -162,18 +167,57 @@ __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int
 __device__ __forceinline__ int grid_sync_wave(unsigned* flags, int* err, unsigned epoch, int cu, int ncu) {
   const int lane = threadIdx.x & 63;
   if (lane == 0) __hip_atomic_store(flags + cu, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (ncu > 256) {                                   // generic path: one poll at a time
+    unsigned spins = 0;
+    for (;;) {
+      bool ok = true;
+      for (int base = 0; base < ncu; base += 256) {
+        unsigned f[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) coh_issue4(f[i], flags + min(base + i * 64 + lane, ncu - 1));
+        coh_wait();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { coh_use(f[i]); ok = ok && (f[i] >= epoch); }
+      }
+      if (__all(ok)) return 1;
+      if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return 0;
+      }
+    }
+  }
+  // Up to 256 workgroups: four polls (4 loads per lane each) are kept in flight, so the flags
+  // are sampled several times per memory round trip instead of once.  The wave has nothing
+  // else outstanding (vmcnt(0) first), so the explicit counts below are exact.
+  const unsigned* f0 = flags + min(lane, ncu - 1);
+  const unsigned* f1 = flags + min(64 + lane, ncu - 1);
+  const unsigned* f2 = flags + min(128 + lane, ncu - 1);
+  const unsigned* f3 = flags + min(192 + lane, ncu - 1);
+  coh_wait();
   unsigned spins = 0;
   for (;;) {
-    bool ok = true;
-    for (int base = 0; base < ncu; base += 256) {
-      unsigned f[4];
+    // (all four polls are requested and consumed inside one iteration: a requested value must
+    // not be carried across the loop edge, where the compiler may copy it before it lands)
+    unsigned a[4][4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) coh_issue4(f[i], flags + min(base + i * 64 + lane, ncu - 1));
-      coh_wait();
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { coh_use(f[i]); ok = ok && (f[i] >= epoch); }
+    for (int q = 0; q < 4; ++q) {
+      coh_issue4(a[q][0], f0); coh_issue4(a[q][1], f1); coh_issue4(a[q][2], f2); coh_issue4(a[q][3], f3);
+      if (q < 3) __builtin_amdgcn_s_sleep(12);       // spread the polls over about one round trip
     }
-    if (__all(ok)) return 1;
+    bool done = false;
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    coh_use(a[0][0]); coh_use(a[0][1]); coh_use(a[0][2]); coh_use(a[0][3]);
+    done = done || __all(a[0][0] >= epoch && a[0][1] >= epoch && a[0][2] >= epoch && a[0][3] >= epoch);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    coh_use(a[1][0]); coh_use(a[1][1]); coh_use(a[1][2]); coh_use(a[1][3]);
+    done = done || __all(a[1][0] >= epoch && a[1][1] >= epoch && a[1][2] >= epoch && a[1][3] >= epoch);
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    coh_use(a[2][0]); coh_use(a[2][1]); coh_use(a[2][2]); coh_use(a[2][3]);
+    done = done || __all(a[2][0] >= epoch && a[2][1] >= epoch && a[2][2] >= epoch && a[2][3] >= epoch);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    coh_use(a[3][0]); coh_use(a[3][1]); coh_use(a[3][2]); coh_use(a[3][3]);
+    done = done || __all(a[3][0] >= epoch && a[3][1] >= epoch && a[3][2] >= epoch && a[3][3] >= epoch);
+    if (done) return 1;
     if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
       __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return 0;
@@ -444,32 +488,41 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
   const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
   const int sub = lane / LPR, dc = lane % LPR;
 
-  // Requests for one 64-key tile: the key row of key t0+lane (lane = key), and the value
-  // rows in the (key subgroup, 8-dim chunk) layout.  Keys past the end re-read position pos.
-  // (the values are requested once the scores are done and reuse the registers of the keys)
-  uint4 kr[NKL], vr[NKL];
-  auto request_keys = [&](int t) {
-    const int ksafe = min((t << 6) + lane, pos);
-    const bf16* krow = pool + (size_t)pt[ksafe / Pg] * p.page_elems + head_off + (size_t)(ksafe % Pg) * HD;
-#pragma unroll
-    for (int c = 0; c < NKL; ++c) kr[c] = ld_global16(krow + c * 8);
-  };
-  // a tile is 64 / Pg whole pages (Pg = 16 is required on this path); their bases are
-  // wave-uniform, so the value loads are base + small per-lane offset.  Pages past the
-  // sequence's last one are clamped to it (in bounds; those keys get weight 0 and their
-  // values are zeroed below).
-  auto request_values = [&](int t) {
+  // One 64-key tile, keys and values in the same layout: load i of lane (sub, dc) holds dims
+  // dc*8 .. dc*8+7 of key t0 + RPI*i + sub, so every load instruction reads whole 2*HD-byte
+  // rows (coalesced) and a lane ends up with the scores / weights of exactly the keys whose
+  // values it will hold.  A tile is 64 / Pg whole pages (Pg = 16 on this path); their bases are
+  // wave-uniform.  Pages past the sequence's last one are clamped to it (in bounds; those keys
+  // get weight 0).  Explicit request / wait keeps keys and values from sharing registers.
+  u32x4_t kv[NKL];
+  constexpr int PPT = 4;                               // pages per tile (Pg = 16)
+  const bf16* pbase[PPT];
+  // page bases of a tile: the four table entries are fetched together (one wait), before the
+  // explicitly ordered row requests
+  auto tile_pages = [&](int t) {
     const int last_page = pos / Pg;
+    int pg[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) pg[j] = pt[min(t * PPT + j, last_page)];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) pbase[j] = uni(pool + (size_t)uni(pg[j]) * p.page_elems + head_off);
+  };
+  auto request = [&](size_t kv_off) {
 #pragma unroll
     for (int i = 0; i < NKL; ++i) {
       const int kin = RPI * i;                         // first key of this load within the tile (+ sub)
-      const int page = uni(pt[min((t << 6) / Pg + kin / Pg, last_page)]);
-      const bf16* base = uni(pool + (size_t)page * p.page_elems + head_off + v_off) + (kin % Pg) * HD;
-      vr[i] = ld_global16(base + sub * HD + dc * 8);
+      gl_issue16(kv[i], pbase[kin / 16] + kv_off + (kin % 16) * HD + sub * HD + dc * 8);
     }
   };
+  auto unpack = [](const u32x4_t w, float (&v)[8]) {
+    v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+    v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+    v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+    v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+  };
   int t = t_first + kg;
-  request_keys(min(t, max(tiles - 1, 0)));          // a wave without a tile still issues (harmless) loads
+  tile_pages(min(t, max(tiles - 1, 0)));            // a wave without a tile still issues (harmless) loads
+  request(0);
 
   // this step's q (G heads), k and v of the KV head: one batch of coherent loads
   {
@@ -506,66 +559,70 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
   }
   lds_barrier();
 
-  float m = -INFINITY, l = 0.f, o[8];
+  float m = -INFINITY, l = 0.f, o[8], qv[8], kn[8], vn[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = 0.f;
-  const float* q = S.qs + hq * HD;
-  float* ps = S.ps + wave * 64;
+  for (int e = 0; e < 8; ++e) {
+    o[e] = 0.f;
+    qv[e] = S.qs[hq * HD + dc * 8 + e];              // this lane's 8 dims of its head's query
+    kn[e] = S.knew[dc * 8 + e];                      // ... and of the key / value appended in this step
+    vn[e] = S.vnew[dc * 8 + e];                      //     (meaningful only in the workgroup that owns it)
+  }
 
   for (; t < t_last; t += nkg) {
     const int t0 = t << 6;
-    const int key = t0 + lane;
-    const bool valid = key < nkeys;
-    float sc = 0.f;
+    if (t != t_first + kg) { tile_pages(t); request(0); }   // (the first tile's keys were requested up front)
+    coh_wait();
+    float sc[NKL];
 #pragma unroll
-    for (int c = 0; c < NKL; ++c) {
-      const float4 q0 = *reinterpret_cast<const float4*>(q + c * 8);
-      const float4 q1 = *reinterpret_cast<const float4*>(q + c * 8 + 4);
-      const uint4 w = kr[c];
-      sc = fmaf(__uint_as_float(w.x << 16), q0.x, sc); sc = fmaf(__uint_as_float(w.x & 0xffff0000u), q0.y, sc);
-      sc = fmaf(__uint_as_float(w.y << 16), q0.z, sc); sc = fmaf(__uint_as_float(w.y & 0xffff0000u), q0.w, sc);
-      sc = fmaf(__uint_as_float(w.z << 16), q1.x, sc); sc = fmaf(__uint_as_float(w.z & 0xffff0000u), q1.y, sc);
-      sc = fmaf(__uint_as_float(w.w << 16), q1.z, sc); sc = fmaf(__uint_as_float(w.w & 0xffff0000u), q1.w, sc);
+    for (int i = 0; i < NKL; ++i) {
+      coh_use(kv[i]);
+      float kf[8];
+      unpack(kv[i], kf);
+      const int key = t0 + RPI * i + sub;
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d = fmaf(key == pos ? kn[e] : kf[e], qv[e], d);
+      sc[i] = d;
     }
-    request_values(t);
-    if (t0 <= pos && pos < t0 + 64) {
-      // the key appended in this step: take it from LDS (the stored, rounded value)
-      float part = 0.f;
-      for (int d = lane; d < HD; d += 64) part = fmaf(q[d], S.knew[d], part);
-      part = wave_sum(part);
-      if (key == pos) sc = part;
+    request(v_off);                                  // values into the registers the keys used
+    // finish the dot products across the LPR lanes that share a key, then the tile's softmax
+    float mt = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) sc[i] += __shfl_xor(sc[i], off, 64);
+      if (t0 + RPI * i + sub >= nkeys) sc[i] = -INFINITY;
+      mt = fmaxf(mt, sc[i]);
     }
-    if (!valid) sc = -INFINITY;
-    const float mn = fmaxf(m, wave_max(sc));
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off, 64));
+    const float mn = fmaxf(m, mt);
     const float corr = expf(m - mn);
-    const float pj = valid ? expf(sc - mn) : 0.f;
-    l = l * corr + wave_sum(pj);
+    float ls = 0.f;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      sc[i] = (t0 + RPI * i + sub < nkeys) ? expf(sc[i] - mn) : 0.f;     // sc now holds the weights
+      ls += sc[i];
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) ls += __shfl_xor(ls, off, 64);
+    l = l * corr + ls;
     m = mn;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] *= corr;
-    ps[lane] = pj;
-    // weighted values: load i covers keys t0 + RPI*i + sub, dims dc*8 .. dc*8+7
+    coh_wait();
 #pragma unroll
     for (int i = 0; i < NKL; ++i) {
-      const int jj = RPI * i + sub;
-      const float pw = ps[jj];
-      float v[8];
-      const uint4 w = vr[i];
-      v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
-      v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
-      v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
-      v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
-      if (t0 + jj == pos) {
+      coh_use(kv[i]);
+      float vf[8];
+      unpack(kv[i], vf);
+      const int key = t0 + RPI * i + sub;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = S.vnew[dc * 8 + e];
-      } else if (t0 + jj > pos) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = 0.f;        // never-written slot: do not let a NaN pattern through
+      for (int e = 0; e < 8; ++e) {
+        const float v = key == pos ? vn[e] : (key > pos ? 0.f : vf[e]);   // never-written slots: no NaN patterns
+        o[e] = fmaf(sc[i], v, o[e]);
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = fmaf(pw, v[e], o[e]);
     }
-    if (t + nkg < t_last) request_keys(t + nkg);
   }
   SK_ASTAMP(8);
   // fold the key subgroups: afterwards lanes 0..LPR-1 hold dims lane*8 .. lane*8+7
@@ -707,6 +764,17 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       if (lane == 0) *S.flag = ok_;                                                    \
     }                                                                                  \
   } while (0)
+  // timing aid: arrival / release of EVERY workgroup at the barrier that opens segment 6
+#define SK_GRID_SYNC_TRACED()                                                          \
+  do {                                                                                 \
+    if (service) {                                                                     \
+      unsigned long long* tb_ = (P.tdbg && s == 6) ? P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 2 * cu : nullptr; \
+      if (tb_ && lane == 0) tb_[0] = wall_clock64();                                   \
+      const int ok_ = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);                  \
+      if (tb_ && lane == 0) tb_[1] = wall_clock64();                                   \
+      if (lane == 0) *S.flag = ok_;                                                    \
+    }                                                                                  \
+  } while (0)
 
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
   {
@@ -735,7 +803,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       SkGains gains;
       const bool fast_norm = cur.gain != nullptr && D <= 4096;
       if (fast_norm) sk_load_gains(gains, cur.gain, D);
-      SK_GRID_SYNC();                              // everything the segment reads has been written
+      SK_GRID_SYNC_TRACED();                       // everything the segment reads has been written
       SK_STAMP(1);
       if (cur.kind == SEG_O) {
         lds_barrier();
@@ -851,6 +919,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
     }
   }
 #undef SK_GRID_SYNC
+#undef SK_GRID_SYNC_TRACED
 #undef SK_STAMP
 }
 
