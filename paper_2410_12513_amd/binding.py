@@ -216,6 +216,7 @@ class FirstContext:
         n = C.c_int32()
         self._chk(self.lib.first_step_timing(self.h, arr, C.c_int32(cap), C.byref(n)))
         self.barrier_trace = list(arr[n.value:n.value + 2 * 256])     # arrival / release per workgroup (timing aid)
+        self.stream_trace = list(arr[n.value + 2 * 256:n.value + 2 * 256 + 16])
         return [list(arr[i:i + 12]) for i in range(0, n.value, 12)]
 
     def num_pages(self) -> int:

@@ -388,7 +388,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * 4));
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)c->num_cu + 4)); A(dev_alloc(c, &c->d_err, 4));
-  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu));
+  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
     for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
@@ -720,7 +720,7 @@ int first_step_timing(first_ctx* c, uint64_t* stamps, int32_t capacity, int32_t*
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(stamps, c->d_tdbg, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost));
   // optional tail: arrival / release of every workgroup at one barrier (timing aid)
-  const int tail = 2 * c->num_cu;
+  const int tail = 2 * c->num_cu + 16;
   if (capacity >= n + tail) {
     HIPCHK(c, hipMemcpy(stamps + n, c->d_tdbg + (size_t)(4 * c->d.n_layers + 1) * SK_TSLOTS, (size_t)tail * sizeof(uint64_t),
                         hipMemcpyDeviceToHost));

@@ -12,7 +12,7 @@ constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = SK_THREADS / 64;
 constexpr int SK_SWAVES = SK_WAVES - 1;  // streaming waves; the last wave is the service wave (see k_step)
 constexpr int SK_SEG = 2048;          // elements of a weight row handled by one wave at a time (4 x 16 B per lane)
-constexpr int SK_PD = 4;              // row segments in flight per wave (32 KB)
+constexpr int SK_PD = 8;              // row segments in flight per wave (32 KB)
 constexpr int SK_PD_EARLY = 4;        // ring slots that stay in flight across the attention phase
 constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row segments per phase)
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
@@ -82,6 +82,22 @@ __device__ __forceinline__ void coh_use(T& v) { asm volatile("" : "+v"(v)); }
 // Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait
 // for outstanding global loads, so weight prefetches stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// Wave-wide sum through the DPP cross-lane paths (a few cycles per step instead of an LDS
+// round trip per step): quads, half rows, rows, then the two row broadcasts of gfx9.  The
+// total ends up in lane 63.  Fixed order, so results are reproducible.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_lane63(float v) {
+  v = dpp_add<0xB1, 0xf>(v);     // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xf>(v);     // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xf>(v);    // row_half_mirror
+  v = dpp_add<0x140, 0xf>(v);    // row_mirror: every lane holds its row's sum
+  v = dpp_add<0x142, 0xa>(v);    // row_bcast15 into rows 1 and 3
+  v = dpp_add<0x143, 0xc>(v);    // row_bcast31 into rows 2 and 3
+  return v;
+}
 // Waits until every global load and store this wave has issued is complete.
 __device__ __forceinline__ void vm_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void stg_bf16(bf16* p, bf16 v) { *as_global(&p->v) = v.v; }
@@ -323,6 +339,7 @@ struct SegDesc {
   const bf16 *m0, *m1, *m2;     // up to three stacked matrices (or two interleaved ones)
   int n0, n1, K, inter;
   int row0, nrows, nseg, nunits, nr_pad;
+  unsigned inv_nseg;            // ceil(2^32 / nseg): unit / nseg = umulhi(unit, inv_nseg) for the small units here
   int kind;
   const float* gain;            // RMSNorm gain of the phase's input (null: no norm)
   bf16* kv;                     // KV pool of the layer (attention precedes SEG_O)
@@ -336,6 +353,7 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int 
   d.row0 = (int)((unsigned)(n * cu) / (unsigned)ncu) * pair;
   d.nrows = (int)((unsigned)(n * (cu + 1)) / (unsigned)ncu) * pair - d.row0;
   d.nseg = K / SK_SEG;
+  d.inv_nseg = d.nseg == 1 ? 0u : (unsigned)((0x100000000ull + d.nseg - 1) / d.nseg);   // (nseg == 1 handled at use)
   d.nunits = d.nrows * d.nseg;
   const int nr = (d.nunits + SK_SWAVES - 1) / SK_SWAVES;
   d.nr_pad = max(SK_PD, (nr + SK_PD - 1) / SK_PD * SK_PD);
@@ -344,7 +362,7 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int 
 __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   d.m0 = uni(d.m0); d.m1 = uni(d.m1); d.m2 = uni(d.m2); d.gain = uni(d.gain); d.kv = uni(d.kv);
   d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
-  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
+  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.inv_nseg = (unsigned)uni((int)d.inv_nseg); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
   return d;
 }
 
@@ -383,26 +401,28 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
   return d;
 }
 
-// Address of row r of a segment, as branch-free integer arithmetic (pointer selects would be
-// turned into an indexed table in scratch memory, and a scratch load in the request path
-// would drain the ring of in-flight loads).
 // Descriptor of segment s for this workgroup, every field in scalar registers.  Recomputed
 // where needed rather than carried through the segment loop.
 __device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
   return seg_uniform(seg_desc_raw(P, s, nk, kept, cu, ncu));
 }
 
-__device__ __forceinline__ const bf16* seg_row(const SegDesc& d, int r) {
+// Address of row r of a segment.  All inputs are wave-uniform, so the cases are scalar
+// branches; the arithmetic is on integers (selects between pointers would be turned into an
+// indexed table in scratch memory, and a scratch load in the request path would drain the
+// ring of in-flight loads).
+__device__ __forceinline__ unsigned long long seg_row_addr(const SegDesc& d, int r) {
   const unsigned long long b0 = reinterpret_cast<unsigned long long>(d.m0);
   const unsigned long long b1 = reinterpret_cast<unsigned long long>(d.m1);
   const unsigned long long b2 = reinterpret_cast<unsigned long long>(d.m2);
-  // which matrix, and which of its rows
-  const int m_stack = (r >= d.n0 ? 1 : 0) + (r >= d.n0 + d.n1 ? 1 : 0);
-  const int mat = d.inter ? (r & 1) : m_stack;
-  const int sub = (m_stack >= 1 ? d.n0 : 0) + (m_stack == 2 ? d.n1 : 0);
-  const int rr = d.inter ? (r >> 1) : r - sub;
-  const unsigned long long base = b0 + (mat >= 1 ? b1 - b0 : 0ull) + (mat == 2 ? b2 - b1 : 0ull);
-  return reinterpret_cast<const bf16*>(base + (unsigned long long)rr * (unsigned long long)d.K * 2ull);
+  const unsigned row_bytes = (unsigned)d.K * 2u;
+  unsigned long long base;
+  unsigned rr;
+  if (d.inter) { base = (r & 1) ? b1 : b0; rr = (unsigned)r >> 1; }
+  else if (r < d.n0) { base = b0; rr = (unsigned)r; }
+  else if (r < d.n0 + d.n1) { base = b1; rr = (unsigned)(r - d.n0); }
+  else { base = b2; rr = (unsigned)(r - d.n0 - d.n1); }
+  return base + (unsigned long long)rr * row_bytes;
 }
 
 // Requests one round (4 x 16 B per lane) of a segment into a ring slot.  Branch-free: the
@@ -417,10 +437,11 @@ __device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enabl
   const int valid = uni((int)(enable && u < d.nunits));   // SEG_NONE has no units
   const int uu = valid ? u : 0;
   const int nseg = uni(max(d.nseg, 1));
-  const int rl = uni(uu / nseg), sg = uu - rl * nseg;
-  const bf16* row = uni(seg_row(d, uni(d.row0) + rl));
+  const int rl = nseg == 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nseg)), sg = uu - rl * nseg;
+  const unsigned long long ra = seg_row_addr(d, uni(d.row0) + rl);
+  bf16* row = reinterpret_cast<bf16*>(((unsigned long long)(unsigned)uni((int)(ra >> 32)) << 32) | (unsigned)uni((int)(unsigned)ra));
   const int row_bytes = uni(d.K * 2);
-  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(row), (short)0, row_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, row_bytes, 0x00020000);
   const int off = valid ? sg * (SK_SEG * 2) + (int)(threadIdx.x & 63) * 16 : row_bytes;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -429,7 +450,9 @@ __device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enabl
   }
 }
 
-// Dot product of one ring slot with the staged activation vector -> psum[unit].
+// Dot product of one ring slot with the staged activation vector -> psum[unit].  The LDS
+// reads are issued together and eight independent accumulators keep the FMA chains short:
+// with two waves per SIMD there is little else to hide latency behind.
 __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave, const uint4 (&b)[4], const float* xs,
                                            float* psum) {
   const int u = uni(round * SK_SWAVES + wave);
@@ -437,22 +460,27 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
   const int lane = threadIdx.x & 63, K = uni(d.K);
   const int uu = valid ? u : 0;
   const int nseg = uni(d.nseg);
-  const int rl = uni(uu / nseg), sg = uu - rl * nseg;
-  float acc = 0.f;
+  const int sg = nseg == 1 ? 0 : uu - uni((int)__umulhi((unsigned)uu, d.inv_nseg)) * nseg;
+  const float* x0p = xs + ((sg * SK_SEG + lane * 8) >> 1);
+  const float* x1p = x0p + (K >> 1);
+  float4 x0[4], x1[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int k = sg * SK_SEG + j * 512 + lane * 8;
-    const int q = (k >> 3) << 2;
-    const float4 x0 = *reinterpret_cast<const float4*>(xs + q);
-    const float4 x1 = *reinterpret_cast<const float4*>(xs + (K >> 1) + q);
-    const uint4 w = b[j];
-    acc = fmaf(__uint_as_float(w.x << 16), x0.x, acc); acc = fmaf(__uint_as_float(w.x & 0xffff0000u), x0.y, acc);
-    acc = fmaf(__uint_as_float(w.y << 16), x0.z, acc); acc = fmaf(__uint_as_float(w.y & 0xffff0000u), x0.w, acc);
-    acc = fmaf(__uint_as_float(w.z << 16), x1.x, acc); acc = fmaf(__uint_as_float(w.z & 0xffff0000u), x1.y, acc);
-    acc = fmaf(__uint_as_float(w.w << 16), x1.z, acc); acc = fmaf(__uint_as_float(w.w & 0xffff0000u), x1.w, acc);
+    x0[j] = *reinterpret_cast<const float4*>(x0p + j * 256);
+    x1[j] = *reinterpret_cast<const float4*>(x1p + j * 256);
   }
-  acc = wave_sum(acc);
-  if (valid && lane == 0) psum[u] = acc;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint4 w = b[j];
+    float e = __uint_as_float(w.x << 16) * x0[j].x, o = __uint_as_float(w.x & 0xffff0000u) * x0[j].y;
+    e = fmaf(__uint_as_float(w.y << 16), x0[j].z, e); o = fmaf(__uint_as_float(w.y & 0xffff0000u), x0[j].w, o);
+    e = fmaf(__uint_as_float(w.z << 16), x1[j].x, e); o = fmaf(__uint_as_float(w.z & 0xffff0000u), x1[j].y, o);
+    e = fmaf(__uint_as_float(w.w << 16), x1[j].z, e); o = fmaf(__uint_as_float(w.w & 0xffff0000u), x1[j].w, o);
+    acc[2 * j] = e; acc[2 * j + 1] = o;
+  }
+  const float tot = wave_sum_lane63(((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
+  if (valid && lane == 63) psum[u] = tot;
 }
 
 __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg) {
@@ -905,15 +933,22 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       }
       lds_barrier();                               // input vector staged
       if (uni(*S.flag) == 0) return;
-      for (int r0 = 0; r0 < cur.nr_pad; r0 += SK_PD) {
+      // all blocks but the last request ahead inside this segment; the last one requests the
+      // first rounds of the next segment (no per-round choice between the two descriptors)
+      const int last0 = cur.nr_pad - SK_PD;
+      for (int r0 = 0; r0 < last0; r0 += SK_PD) {
+        if (P.tdbg && s == 6 && cu == 0 && tid == 0 && r0 / SK_PD < 10)          // timing aid: progress of the GU stream
+          P.tdbg[(4 * P.L + 1) * SK_TSLOTS + 2 * ncu + r0 / SK_PD] = wall_clock64();
 #pragma unroll
         for (int j = 0; j < SK_PD; ++j) {
           sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum);
-          const int t = r0 + j + SK_PD;
-          const bool ahead = t >= cur.nr_pad;                 // the request belongs to the next segment
-          sk_issue(ahead ? nxt : cur, ahead ? t - cur.nr_pad : t, !ahead || nxt.kind != SEG_O || j < SK_PD_EARLY, wave,
-                   buf[j]);
+          sk_issue(cur, r0 + j + SK_PD, true, wave, buf[j]);
         }
+      }
+#pragma unroll
+      for (int j = 0; j < SK_PD; ++j) {
+        sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum);
+        sk_issue(nxt, j, nxt.kind != SEG_O || j < SK_PD_EARLY, wave, buf[j]);
       }
       lds_barrier();                               // partial sums complete
     }
