@@ -67,6 +67,7 @@ struct first_ctx {
   // persistent whole-step kernel (bf16, one live sequence)
   LayerDev* d_layers = nullptr;
   unsigned* d_bar = nullptr;
+  int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
   int step_timing = 0;
@@ -203,9 +204,9 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d = base_params(c, 0, 1);
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
-  P.bar = c->d_bar; P.err = c->d_err;
+  P.bar = c->d_bar; P.err = c->d_err; P.two_level = c->step_two_level;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
-  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)c->num_cu);
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)sk_bar_words(c->num_cu));
   if (c->d.head_dim == 128)
     hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
   else
@@ -387,7 +388,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * 4));
-  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)c->num_cu + 4)); A(dev_alloc(c, &c->d_err, 4));
+  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
   A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
@@ -397,7 +398,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
     if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
-    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, ((size_t)c->num_cu + 4) * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, (size_t)sk_bar_words(c->num_cu) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
       std::vector<LayerDev> ld(L);
@@ -598,6 +599,11 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->decode_path = value; return FIRST_OK;
     case FIRST_OPT_STEP_TIMING:
       c->step_timing = value ? 1 : 0;
+      drop_graphs(c);
+      return FIRST_OK;
+    case FIRST_OPT_STEP_BARRIER:
+      if (value < 0 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
+      c->step_two_level = value;
       drop_graphs(c);
       return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");

@@ -52,6 +52,9 @@ __device__ __forceinline__ float ld_coh(const float* p) {
 __device__ __forceinline__ int ld_coh(const int* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ unsigned ld_coh(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void st_coh(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -130,7 +133,8 @@ struct StepParams {
   const int* kept;             // [B][L] ascending kept-layer indices
   const int* n_kept;           // [B]
   int L;
-  unsigned* bar;               // grid barrier counter, zero at launch
+  unsigned* bar;               // grid barrier words (sk_bar_words(grid size) of them), zero at launch
+  int two_level;               // 1: per-XCD arrival counters + one flag per XCD; 0: every workgroup polls every flag
   int* err;                    // set to 1 if a barrier wait gives up
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
@@ -236,6 +240,97 @@ __device__ __forceinline__ int grid_sync_wave(unsigned* flags, int* err, unsigne
     if (done) return 1;
     if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
       __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return 0;
+    }
+  }
+}
+
+// Two-level variant.  All workgroups polling all flags makes a few cache lines very hot, and
+// that queueing dominates the barrier's latency.  Instead: workgroups on the same XCD (they
+// share an L2, where read-modify-write operations execute) count arrivals in a per-XCD
+// counter; the last arriver of an XCD publishes the epoch in that XCD's device-scope flag;
+// every workgroup then polls only those few flags (one cache line each).
+//
+// Layout behind the per-workgroup flags (at flags + sk_bar_x(ncu)), 32-dword stride per XCD:
+//   [0, 16*32): workgroups per XCD, counted at kernel start;  [16*32, 32*32): arrival counters;
+//   [32*32, 48*32): published epochs.  All zero at launch.
+constexpr int SK_XCD_SLOTS = 16, SK_XCD_STRIDE = 32;
+__host__ __device__ inline int sk_bar_x(int ncu) { return (ncu + 31) / 32 * 32; }
+__host__ __device__ inline int sk_bar_words(int ncu) { return sk_bar_x(ncu) + 3 * SK_XCD_SLOTS * SK_XCD_STRIDE; }
+
+__device__ __forceinline__ unsigned sk_xcc_id() {
+  unsigned v;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+  return v & (SK_XCD_SLOTS - 1);
+}
+// Fetch-and-add executed in this XCD's L2; waits for the old value (and for every older
+// memory operation of the wave).
+__device__ __forceinline__ unsigned sk_l2_add_ret(unsigned* ptr, unsigned v) {
+  unsigned r;
+  asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(r) : "v"(ptr), "v"(v) : "memory");
+  return r;
+}
+
+struct SkBar {
+  unsigned* flags;     // [ncu] per-workgroup epochs (flat barrier)
+  unsigned* xbase;     // per-XCD words (see layout above)
+  int* err;
+  unsigned x;          // this workgroup's XCD
+  unsigned my_n;       // workgroups on this XCD
+  unsigned n_lane;     // lane l < SK_XCD_SLOTS: workgroups on XCD l
+  int two_level;
+};
+
+// Executed by the service wave before the first barrier: count this workgroup on its XCD.
+__device__ __forceinline__ void sk_bar_init(SkBar& B, unsigned* bar, int* err, int ncu, int two_level) {
+  B.flags = bar; B.xbase = bar + sk_bar_x(ncu); B.err = err; B.two_level = two_level;
+  B.x = sk_xcc_id(); B.my_n = 0; B.n_lane = 0;
+  if (two_level && (threadIdx.x & 63) == 0) {
+    const unsigned old = __hip_atomic_fetch_add(B.xbase + B.x * SK_XCD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" :: "v"(old));                  // the add has completed before the first arrival is published
+  }
+}
+
+__device__ __forceinline__ int grid_sync(SkBar& B, unsigned epoch, int cu, int ncu) {
+  const int lane = threadIdx.x & 63;
+  if (!B.two_level || epoch == 1) {
+    const int ok = grid_sync_wave(B.flags, B.err, epoch, cu, ncu);
+    if (B.two_level) {                             // every workgroup has been counted: read the census
+      B.n_lane = ld_coh(B.xbase + (lane & (SK_XCD_SLOTS - 1)) * SK_XCD_STRIDE);
+      B.my_n = __builtin_amdgcn_readlane(B.n_lane, B.x);
+    }
+    return ok;
+  }
+  const unsigned k = epoch - 1;
+  unsigned* cnt = B.xbase + (SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
+  unsigned* pub = B.xbase + (2 * SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
+  if (lane == 0) {
+    const unsigned old = sk_l2_add_ret(cnt, 1u);
+    if (old + 1u == B.my_n * k) __hip_atomic_store(pub, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  const unsigned* f = B.xbase + (2 * SK_XCD_SLOTS + (lane & (SK_XCD_SLOTS - 1))) * SK_XCD_STRIDE;
+  const bool need = B.n_lane != 0;
+  coh_wait();
+  unsigned spins = 0;
+  for (;;) {
+    unsigned a[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      coh_issue4(a[q], f);
+      if (q < 3) __builtin_amdgcn_s_sleep(8);
+    }
+    bool done = false;
+    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+    coh_use(a[0]); done = done || __all(!need || a[0] >= k);
+    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    coh_use(a[1]); done = done || __all(!need || a[1] >= k);
+    asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+    coh_use(a[2]); done = done || __all(!need || a[2] >= k);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    coh_use(a[3]); done = done || __all(!need || a[3] >= k);
+    if (done) return 1;
+    if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(B.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+      __hip_atomic_store(B.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return 0;
     }
   }
@@ -457,6 +552,13 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
                                            float* psum) {
   const int u = uni(round * SK_SWAVES + wave);
   const int valid = uni((int)(u < d.nunits));
+#ifdef SK_FAKE_CONSUME
+  {
+    unsigned t = (b[0].x ^ b[0].y ^ b[0].z ^ b[0].w) ^ (b[1].x ^ b[1].y ^ b[1].z ^ b[1].w) ^ (b[2].x ^ b[2].y ^ b[2].z ^ b[2].w) ^ (b[3].x ^ b[3].y ^ b[3].z ^ b[3].w);
+    if (valid && (threadIdx.x & 63) == 63) psum[u] = __uint_as_float(t & 0x3fffffffu) * 1e-3f;
+    return;
+  }
+#endif
   const int lane = threadIdx.x & 63, K = uni(d.K);
   const int uu = valid ? u : 0;
   const int nseg = uni(d.nseg);
@@ -770,6 +872,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const int b = p.b, D = p.D, F = p.F, nq = p.Hq * HD, nkv = p.Hkv * HD;
   const SkLds S = sk_carve(smem_f, D, nq, F, p.G, HD);
   unsigned epoch = 0;
+  SkBar bar;
+  if (service) sk_bar_init(bar, P.bar, P.err, ncu, P.two_level);
   float* h = p.h + (size_t)b * D;
   const int nk = uni(P.n_kept[b]);
   const int* kept = P.kept + (size_t)b * P.L;
@@ -788,17 +892,17 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
 #define SK_GRID_SYNC()                                                                 \
   do {                                                                                 \
     if (service) {                                                                     \
-      const int ok_ = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);                  \
+      const int ok_ = grid_sync(bar, ++epoch, cu, ncu);                                \
       if (lane == 0) *S.flag = ok_;                                                    \
     }                                                                                  \
   } while (0)
-  // timing aid: arrival / release of EVERY workgroup at the barrier that opens segment 6
+  // timing aid: arrival / release of EVERY workgroup at the barrier that opens segment 7 (the first down projection)
 #define SK_GRID_SYNC_TRACED()                                                          \
   do {                                                                                 \
     if (service) {                                                                     \
-      unsigned long long* tb_ = (P.tdbg && s == 6) ? P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 2 * cu : nullptr; \
+      unsigned long long* tb_ = (P.tdbg && s == 7) ? P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 2 * cu : nullptr; \
       if (tb_ && lane == 0) tb_[0] = wall_clock64();                                   \
-      const int ok_ = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);                  \
+      const int ok_ = grid_sync(bar, ++epoch, cu, ncu);                                \
       if (tb_ && lane == 0) tb_[1] = wall_clock64();                                   \
       if (lane == 0) *S.flag = ok_;                                                    \
     }                                                                                  \
@@ -889,7 +993,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       SK_STAMP(5);
     }
     // greedy token: workgroup 0 reduces the per-workgroup candidates
-    const int ok = grid_sync_wave(P.bar, P.err, ++epoch, cu, ncu);
+    const int ok = grid_sync(bar, ++epoch, cu, ncu);
     if (ok && cu == 0) {
       Best bb{-INFINITY, 0x7fffffff};
       const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
