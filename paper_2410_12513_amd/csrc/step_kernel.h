@@ -383,22 +383,24 @@ __device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, in
 
 // xs <- x or RMSNorm(x; gain), in the two-plane layout the 8-wide weight vectors read.
 // Executed by ONE wave (the service wave).  x was written by other workgroups in this
-// kernel: coherent 16-byte loads, 16 requested per lane before each wait.
+// kernel: coherent 16-byte loads, 16 requested per lane before each wait (more in flight per
+// wave measured slower while the weight stream is running).
 __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps) {
+  constexpr int NB = 8;
   const int lane = threadIdx.x & 63;
   const int ngroups = K >> 3;
   float ss = 0.f;
-  for (int g0 = 0; g0 < ngroups; g0 += 512) {
-    f32x4_t a[8], b[8];
+  for (int g0 = 0; g0 < ngroups; g0 += NB * 64) {
+    f32x4_t a[NB], b[NB];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NB; ++i) {
       const int k = min(g0 + i * 64 + lane, ngroups - 1) << 3;      // out-of-range groups re-read the last one
       coh_issue16(a[i], x + k);
       coh_issue16(b[i], x + k + 4);
     }
     coh_wait();
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NB; ++i) {
       coh_use(a[i]); coh_use(b[i]);
       const int g = g0 + i * 64 + lane;
       if (g < ngroups) {
@@ -955,6 +957,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       SK_STAMP(3);
       lds_barrier();                               // input vector staged; barrier verdict visible
       if (uni(*S.flag) == 0) return;
+      // residual rows this workgroup will update: final since the barrier above, so they are
+      // fetched while the weights stream
+      float h_prev = 0.f;
+      if ((cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
       lds_barrier();                               // partial sums complete
       SK_STAMP(4);
       // results of the segment
@@ -962,7 +968,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
         for (int r = lane; r < cur.nrows; r += 64) st_coh(out + cur.row0 + r, sk_row_sum(S.psum, r, cur.nseg));
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
-        for (int r = lane; r < cur.nrows; r += 64)
+        if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg));
+        for (int r = 64 + lane; r < cur.nrows; r += 64)
           st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg));
       } else if (cur.kind == SEG_GU) {
         float* z = p.z + (size_t)b * F;
