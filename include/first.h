@@ -52,6 +52,9 @@ extern "C" {
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
+#define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
+                                      keep it share one pass over its weights (bf16 models, widths multiples of 8),
+                                      else one pass per sequence; 0: always one pass per sequence; 1: shared pass or error */
 #define FIRST_OPT_STEP_BARRIER  5  /* grid barrier of the persistent kernel.  1 (default): workgroups of one XCD
                                       count arrivals in their shared L2 and the last one publishes one flag per
                                       XCD; 0: every workgroup publishes a flag and polls all of them */

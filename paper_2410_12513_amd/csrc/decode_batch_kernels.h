@@ -1,0 +1,290 @@
+// Decode step of a BATCH of sequences with per-sequence skip masks (Section 4.3 item 2 with
+// the batch sizes of Section 5's latency tables).  For each layer the host forms the list of
+// sequences that keep it; the layer's weights are then streamed from HBM ONCE for the whole
+// list: every mat-vec becomes a skinny matrix product  Y[seq][row] = sum_k W[row][k] X[seq][k]
+// with up to 16 sequences, which is one MFMA tile wide.
+//
+// Activations stay fp32 between ops.  For the matrix cores each activation vector is split
+// as x = hi + lo with hi = bf16(x), lo = bf16(x - hi) (16 significant bits), and every weight
+// tile is multiplied with both halves, accumulating in fp32.  RMSNorm's gain is applied before
+// the split and its 1/rms after the product (it is one scalar per sequence).
+#pragma once
+#include "decode_kernels.h"
+#include "step_kernel.h"
+
+namespace first {
+
+constexpr int BATCH_SLOTS = 16;      // sequences per pass = rows of one MFMA tile
+constexpr int BG_THREADS = 512;      // 8 waves: (row tiles per workgroup) x (slices of K) = 8
+constexpr int BG_WAVES = BG_THREADS / 64;
+
+struct SeqList {
+  int n;
+  int id[BATCH_SLOTS];
+};
+
+struct BatchParams {
+  DecParams d;          // geometry, per-sequence state, layer pointers (d.b unused)
+  SeqList seqs;         // sequences of this pass; slot j <-> sequence seqs.id[j]
+  bf16* xh;             // [BATCH_SLOTS][xpitch] high halves of the op's input vectors
+  bf16* xl;             // [BATCH_SLOTS][xpitch] low halves
+  bf16* zh;             // [BATCH_SLOTS][xpitch] MLP activation (written by gate/up, read by down), high halves
+  bf16* zl;             //                       low halves
+  float* rinv;          // [BATCH_SLOTS] 1/rms of the vector that was split last (norm ops)
+  int xpitch;
+  float* logits_all;    // [B][V] logits of the step (caller's buffer or the library's)
+};
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v_t;
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) {
+  union { uint4 u; bf16x8_t b; } c;
+  c.u = v;
+  return c.b;
+}
+
+// hi/lo split of x (times gain) for slot blockIdx.x, elements [blockIdx.y * chunk, +chunk);
+// rinv = 1/sqrt(mean(x^2) + eps) if gain (every workgroup of a slot sums the whole vector, the
+// first one stores the result).  src: 0 = residual stream h, 1 = attention output.
+__global__ void __launch_bounds__(WG) k_xsplit(BatchParams P, int src, int K, int chunk, const float* gain) {
+  __shared__ float red[WAVES];
+  const DecParams& p = P.d;
+  const int j = blockIdx.x, b = P.seqs.id[j];
+  const float* x = src == 0 ? p.h + (size_t)b * p.D : p.attn + (size_t)b * p.Hq * p.hd;
+  bf16* xh = P.xh + (size_t)j * P.xpitch;
+  bf16* xl = P.xl + (size_t)j * P.xpitch;
+  if (gain && blockIdx.y == 0) {
+    float ss = 0.f;
+    for (int k = threadIdx.x; k < K; k += WG) { const float v = x[k]; ss = fmaf(v, v, ss); }
+    const float tot = block_sum(ss, red);
+    if (threadIdx.x == 0) P.rinv[j] = 1.0f / sqrtf(tot / (float)K + p.eps);
+  }
+  const int k0 = blockIdx.y * chunk, k1 = min(K, k0 + chunk);
+  for (int k = k0 + threadIdx.x; k < k1; k += WG) {
+    float v = x[k];
+    if (gain) v *= gain[k];
+    const bf16 hi = from_f32<bf16>(v);
+    xh[k] = hi;
+    xl[k] = from_f32<bf16>(v - to_f32(hi));
+  }
+}
+
+// h = E[token] and the rotation table of the position, for slot blockIdx.x.
+__global__ void __launch_bounds__(WG) k_embed_b(BatchParams P) {
+  DecParams p = P.d;
+  p.b = P.seqs.id[blockIdx.x];
+  phase_embed<bf16>(p);
+}
+
+// Decode attention of (split, KV head, slot).
+__global__ void __launch_bounds__(WG) k_attn_b(BatchParams P) {
+  extern __shared__ __align__(16) char smem_raw[];
+  DecParams p = P.d;
+  p.b = P.seqs.id[blockIdx.z];
+  phase_attn<bf16>(p, blockIdx.y, blockIdx.x, smem_raw);
+}
+
+// Decode attention of (split, KV head, slot) with the persistent kernel's attention phase
+// (register-resident 64-key tiles, page lookups batched per tile): 7 worker waves + the wave
+// that only keeps step with the workgroup barriers.  Needs 16-token pages and G <= 7.
+template <int HD>
+__global__ void __launch_bounds__(SK_THREADS) k_attn_tiles_b(BatchParams P) {
+  extern __shared__ __align__(16) float smem_f[];
+  StepParams SP{};
+  SP.d = P.d;
+  SP.d.b = P.seqs.id[blockIdx.z];
+  const DecParams& p = SP.d;
+  const SkLds S = sk_carve(smem_f, 0, 0, 0, p.G, HD);
+  const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6));
+  const int pos = uni(p.len[p.b]);
+  for (int i = tid; i < HD / 2; i += SK_THREADS) {
+    const double a = (double)pos * p.theta[i];
+    S.cs[i] = make_float2((float)cos(a), (float)sin(a));
+  }
+  lds_barrier();
+  if (wave == SK_SWAVES) sk_attention_service();
+  else sk_attention<HD>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, gridDim.x, nullptr);
+}
+
+enum { BG_QKV = 0, BG_O = 1, BG_GU = 2, BG_DN = 3, BG_HEAD = 4 };
+
+// Y[slot][row] for a tile of 16 rows per wave group.  Workgroup = 8 waves = (8 / kslices) row
+// tiles x kslices slices of the contraction; the slices of a tile are added in slice order in
+// LDS, so results do not depend on timing.
+//
+// MFMA 16x16x32 operands: A = activations (rows = slots, lane l: slot l % 16, k = 8 (l / 16) ..+8),
+// B = weights (columns = weight rows, lane l: row l % 16, same k), C: lane l holds weight row
+// l % 16 for slots 4 (l / 16) .. +4.
+template <int MODE>
+__global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int K, int kslices) {
+  __shared__ float red[BG_WAVES][2][4][64];
+  const DecParams& p = P.d;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, g = lane >> 4;
+  const int tiles_per_wg = BG_WAVES / kslices;
+  const int tile = blockIdx.x * tiles_per_wg + wave / kslices, slice = wave % kslices;
+  const int row = tile * 16 + n, rowc = min(row, N - 1);
+  const int ksteps = (K + 31) >> 5;
+  const int per = (ksteps + kslices - 1) / kslices;
+  const int s0 = slice * per, s1 = min(ksteps, s0 + per);
+
+  const bf16 *w0, *w1 = nullptr;
+  if (MODE == BG_QKV) {
+    const int nq = p.Hq * p.hd, nk = p.Hkv * p.hd;
+    w0 = rowc < nq ? reinterpret_cast<const bf16*>(p.wq) + (size_t)rowc * K
+       : rowc < nq + nk ? reinterpret_cast<const bf16*>(p.wk) + (size_t)(rowc - nq) * K
+                        : reinterpret_cast<const bf16*>(p.wv) + (size_t)(rowc - nq - nk) * K;
+  } else if (MODE == BG_O) {
+    w0 = reinterpret_cast<const bf16*>(p.wo) + (size_t)rowc * K;
+  } else if (MODE == BG_GU) {
+    w0 = reinterpret_cast<const bf16*>(p.wg) + (size_t)rowc * K;
+    w1 = reinterpret_cast<const bf16*>(p.wu) + (size_t)rowc * K;
+  } else if (MODE == BG_DN) {
+    w0 = reinterpret_cast<const bf16*>(p.wd) + (size_t)rowc * K;
+  } else {
+    w0 = reinterpret_cast<const bf16*>(p.lm_head) + (size_t)rowc * K;
+  }
+  const bf16* xh = (MODE == BG_DN ? P.zh : P.xh) + (size_t)n * P.xpitch;
+  const bf16* xl = (MODE == BG_DN ? P.zl : P.xl) + (size_t)n * P.xpitch;
+
+  f32x4v_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  const int full1 = min(s1, K >> 5);               // steps in which every lane's 8 elements are in range
+  int s = s0;
+  constexpr int UN = 4;                            // k-steps requested together (256 contiguous bytes per row)
+  for (; s + UN <= full1; s += UN) {
+    uint4 a_h[UN], a_l[UN], w_0[UN], w_1[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int k = ((s + u) << 5) + (g << 3);
+      w_0[u] = ld_stream16(w0 + k);
+      if (MODE == BG_GU) w_1[u] = ld_stream16(w1 + k);
+      a_h[u] = *reinterpret_cast<const uint4*>(xh + k);
+      a_l[u] = *reinterpret_cast<const uint4*>(xl + k);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const bf16x8_t ah = as_bf16x8(a_h[u]), al = as_bf16x8(a_l[u]), b0 = as_bf16x8(w_0[u]);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, b0, acc0, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, b0, acc0, 0, 0, 0);
+      if (MODE == BG_GU) {
+        const bf16x8_t b1 = as_bf16x8(w_1[u]);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, b1, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, b1, acc1, 0, 0, 0);
+      }
+    }
+  }
+  for (; s < full1; ++s) {
+    const int k = (s << 5) + (g << 3);
+    const bf16x8_t ah = as_bf16x8(*reinterpret_cast<const uint4*>(xh + k));
+    const bf16x8_t al = as_bf16x8(*reinterpret_cast<const uint4*>(xl + k));
+    const bf16x8_t b0 = as_bf16x8(ld_stream16(w0 + k));
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, b0, acc0, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, b0, acc0, 0, 0, 0);
+    if (MODE == BG_GU) {
+      const bf16x8_t b1 = as_bf16x8(ld_stream16(w1 + k));
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, b1, acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, b1, acc1, 0, 0, 0);
+    }
+  }
+  for (; s < s1; ++s) {                            // ragged last step (K a multiple of 8, not of 32)
+    const int k = (s << 5) + (g << 3);
+    uint4 ah4 = make_uint4(0, 0, 0, 0), al4 = ah4, b04 = ah4, b14 = ah4;
+    if (k < K) {
+      ah4 = *reinterpret_cast<const uint4*>(xh + k);
+      al4 = *reinterpret_cast<const uint4*>(xl + k);
+      b04 = *reinterpret_cast<const uint4*>(w0 + k);
+      if (MODE == BG_GU) b14 = *reinterpret_cast<const uint4*>(w1 + k);
+    }
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ah4), as_bf16x8(b04), acc0, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(al4), as_bf16x8(b04), acc0, 0, 0, 0);
+    if (MODE == BG_GU) {
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ah4), as_bf16x8(b14), acc1, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(al4), as_bf16x8(b14), acc1, 0, 0, 0);
+    }
+  }
+
+  if (kslices > 1) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      red[wave][0][j][lane] = acc0[j];
+      if (MODE == BG_GU) red[wave][1][j][lane] = acc1[j];
+    }
+    __syncthreads();
+    if (slice != 0) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float a = red[wave][0][j][lane], c = MODE == BG_GU ? red[wave][1][j][lane] : 0.f;
+      for (int t = 1; t < kslices; ++t) {
+        a += red[wave + t][0][j][lane];
+        if (MODE == BG_GU) c += red[wave + t][1][j][lane];
+      }
+      acc0[j] = a; acc1[j] = c;
+    }
+  }
+  if (row >= N) return;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int slot = 4 * g + j;
+    if (slot >= P.seqs.n) continue;
+    const int b = P.seqs.id[slot];
+    if (MODE == BG_QKV) {
+      p.qkv[(size_t)b * N + row] = acc0[j] * P.rinv[slot];
+    } else if (MODE == BG_O || MODE == BG_DN) {
+      p.h[(size_t)b * p.D + row] += acc0[j];
+    } else if (MODE == BG_GU) {
+      const float r = P.rinv[slot];
+      const float z = siluf(acc0[j] * r) * (acc1[j] * r);
+      const bf16 hi = from_f32<bf16>(z);
+      P.zh[(size_t)slot * P.xpitch + row] = hi;              // input of the down projection, already split
+      P.zl[(size_t)slot * P.xpitch + row] = from_f32<bf16>(z - to_f32(hi));
+    } else {
+      P.logits_all[(size_t)b * N + row] = acc0[j] * P.rinv[slot];
+    }
+  }
+}
+
+// Greedy token, stage 1: candidate of chunk blockIdx.y of slot blockIdx.x's logits row.
+constexpr int ARG_CHUNKS = 64;
+__global__ void __launch_bounds__(WG) k_argmax_part_b(BatchParams P) {
+  __shared__ Best wbest[WAVES];
+  const DecParams& p = P.d;
+  const int b = P.seqs.id[blockIdx.x], tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* lg = P.logits_all + (size_t)b * p.V;
+  const int per = (p.V + ARG_CHUNKS - 1) / ARG_CHUNKS, r0 = blockIdx.y * per, r1 = min(p.V, r0 + per);
+  Best best{-INFINITY, 0x7fffffff};
+  for (int r = r0 + tid; r < r1; r += WG) {
+    const Best c{lg[r], r};
+    if (better(c, best)) best = c;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Best c{__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
+    if (better(c, best)) best = c;
+  }
+  if (lane == 0) wbest[wave] = best;
+  __syncthreads();
+  if (tid == 0) {
+    for (int wv = 1; wv < WAVES; ++wv)
+      if (better(wbest[wv], best)) best = wbest[wv];
+    p.arg_part[(size_t)b * ARG_MAX_WG + blockIdx.y] = best;
+  }
+}
+
+// Stage 2: lowest index among the best candidates; advances the sequence length.
+__global__ void __launch_bounds__(64) k_argmax_final_b(BatchParams P, int advance) {
+  const DecParams& p = P.d;
+  const int b = P.seqs.id[blockIdx.x], lane = threadIdx.x;
+  Best best = lane < ARG_CHUNKS ? p.arg_part[(size_t)b * ARG_MAX_WG + lane] : Best{-INFINITY, 0x7fffffff};
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const Best c{__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)};
+    if (better(c, best)) best = c;
+  }
+  if (lane == 0) {
+    if (p.token_out) p.token_out[b] = best.i;
+    if (advance) p.len[b] += 1;
+  }
+}
+
+}  // namespace first

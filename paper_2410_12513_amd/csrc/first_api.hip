@@ -13,6 +13,7 @@
 #include "decode_kernels.h"
 #include "prefill_kernels.h"
 #include "step_kernel.h"
+#include "decode_batch_kernels.h"
 
 using namespace first;
 
@@ -67,6 +68,11 @@ struct first_ctx {
   // persistent whole-step kernel (bf16, one live sequence)
   LayerDev* d_layers = nullptr;
   unsigned* d_bar = nullptr;
+  // batched decode (several live sequences): split activations, 1/rms per slot, logits when the caller wants none
+  bf16 *d_xh = nullptr, *d_xl = nullptr, *d_zh = nullptr, *d_zl = nullptr;
+  float *d_rinv = nullptr, *d_logits_all = nullptr;
+  int xpitch = 0;
+  int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
   int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
@@ -195,6 +201,83 @@ void enqueue_decode_ops(first_ctx* c, const int* tokens, float* logits, int* tok
       hipLaunchKernelGGL(k_down<WT>, dim3(g_o), dim3(WG), lds_f, c->stream, p);
     }
     enqueue_head<WT>(c, p, logits, token_out, 1);
+  }
+}
+
+// Workgroups and K-slices of a batched mat-vec over N rows: enough workgroups to fill the
+// chip; small N splits the contraction over the 8 waves of a workgroup instead.
+void bgemv_shape(int N, int num_cu, int* grid, int* kslices) {
+  const int tiles = (N + 15) / 16;
+  int ks = 1;
+  while (ks < BG_WAVES && tiles * ks < 16 * num_cu) ks *= 2;
+  *kslices = ks;
+  const int tiles_per_wg = BG_WAVES / ks;
+  *grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+}
+
+bool d_batch_fits(const first_ctx* c) {
+  return c->d.d_model % 8 == 0 && c->nq % 8 == 0 && c->d.d_ffn % 8 == 0;
+}
+
+template <int MODE>
+void launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
+  int grid, ks;
+  bgemv_shape(N, c->num_cu, &grid, &ks);
+  hipLaunchKernelGGL(k_bgemv<MODE>, dim3(grid), dim3(BG_THREADS), 0, c->stream, P, N, K, ks);
+}
+
+// One decode token for every live sequence (bf16 models), layer by layer: the sequences that
+// keep a layer go through it together, so its weights are read once per step and per group
+// of BATCH_SLOTS sequences whatever the masks are.
+void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int* token_out, int S) {
+  const first_model_desc& d = c->d;
+  const int nqkv = c->nq + 2 * c->nkv;
+  // attention on register-resident key tiles when the geometry allows, one 64-key tile per
+  // worker wave group and split where the longest sequence permits
+  const bool tiles_attn = (d.head_dim == 64 || d.head_dim == 128) && c->G <= SK_SWAVES && d.kv_page_tokens == 16;
+  const int nkg = std::max(1, SK_SWAVES / c->G);
+  const int nsplit = std::max(1, std::min(S_MAX, (2 * S + nkg - 1) / nkg));
+  const size_t attn_tiles_lds = sk_lds_floats(0, 0, 0, c->G, d.head_dim) * sizeof(float);
+  for (int b0 = 0; b0 < c->B; b0 += BATCH_SLOTS) {
+    BatchParams P{};
+    P.d = base_params(c, 0, S);
+    P.d.tokens = tokens; P.d.token_out = token_out;
+    P.xh = c->d_xh; P.xl = c->d_xl; P.zh = c->d_zh; P.zl = c->d_zl; P.rinv = c->d_rinv; P.xpitch = c->xpitch;
+    P.logits_all = logits ? logits : c->d_logits_all;
+    SeqList all{};
+    for (int b = b0; b < std::min(c->B, b0 + BATCH_SLOTS); ++b) all.id[all.n++] = b;
+    P.seqs = all;
+    hipLaunchKernelGGL(k_embed_b, dim3(all.n), dim3(WG), 0, c->stream, P);
+    auto xsplit = [&](int src, int K, const float* gain) {
+      const int chunk = 1024;
+      hipLaunchKernelGGL(k_xsplit, dim3(P.seqs.n, (K + chunk - 1) / chunk), dim3(WG), 0, c->stream, P, src, K, chunk, gain);
+    };
+    for (int i = 0; i < d.n_layers; ++i) {
+      SeqList keep{};
+      for (int j = 0; j < all.n; ++j)
+        if (c->hmask[all.id[j]][i]) keep.id[keep.n++] = all.id[j];
+      if (keep.n == 0) continue;                   // skipped by every sequence: no launch, no bytes
+      P.seqs = keep;
+      set_layer(c, P.d, i);
+      xsplit(0, d.d_model, P.d.g_attn);
+      launch_bgemv<BG_QKV>(c, P, nqkv, d.d_model);
+      if (tiles_attn && d.head_dim == 128)
+        hipLaunchKernelGGL(k_attn_tiles_b<128>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(SK_THREADS), attn_tiles_lds, c->stream, P);
+      else if (tiles_attn)
+        hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(SK_THREADS), attn_tiles_lds, c->stream, P);
+      else
+        hipLaunchKernelGGL(k_attn_b, dim3(S, d.n_kv_heads, keep.n), dim3(WG), attn_lds<bf16>(c), c->stream, P);
+      xsplit(1, c->nq, nullptr);
+      launch_bgemv<BG_O>(c, P, d.d_model, c->nq);
+      xsplit(0, d.d_model, P.d.g_mlp);
+      launch_bgemv<BG_GU>(c, P, d.d_ffn, d.d_model);
+      launch_bgemv<BG_DN>(c, P, d.d_model, d.d_ffn);
+    }
+    P.seqs = all;
+    xsplit(0, d.d_model, c->g_final);
+    launch_bgemv<BG_HEAD>(c, P, d.vocab, d.d_model);
+    hipLaunchKernelGGL(k_argmax_part_b, dim3(all.n, ARG_CHUNKS), dim3(WG), 0, c->stream, P);
+    hipLaunchKernelGGL(k_argmax_final_b, dim3(all.n), dim3(64), 0, c->stream, P, 1);
   }
 }
 
@@ -388,6 +471,12 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * 4));
+  c->xpitch = (std::max(std::max(d.d_model, c->nq), d.d_ffn) + 31) / 32 * 32;
+  if (B > 1) {
+    A(dev_alloc(c, &c->d_xh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_xl, (size_t)BATCH_SLOTS * c->xpitch));
+    A(dev_alloc(c, &c->d_zh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_zl, (size_t)BATCH_SLOTS * c->xpitch));
+    A(dev_alloc(c, &c->d_rinv, BATCH_SLOTS)); A(dev_alloc(c, &c->d_logits_all, (size_t)B * d.vocab));
+  }
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
   A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
   if (rc == FIRST_OK) {
@@ -553,8 +642,14 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   if (c->decode_path == 1 && !persistent)
     return fail(c, FIRST_ERR_STATE, "first_decode_step: the persistent kernel needs a bf16 model whose widths are "
                                     "multiples of 2048 and exactly one live sequence");
+  const bool batch_ok = bf && c->B > 1 && c->d_xh && d_batch_fits(c);
+  const bool batched = !persistent && batch_ok && c->batch_path != 0;
+  if (c->batch_path == 1 && !persistent && !batched)
+    return fail(c, FIRST_ERR_STATE, "first_decode_step: the batched path needs a bf16 model whose widths are multiples of 8 "
+                                    "and more than one live sequence");
   auto enqueue = [&]() {
     if (persistent) enqueue_decode_step_kernel(c, last_tokens, logits_out, token_out);
+    else if (batched) enqueue_decode_batched(c, last_tokens, logits_out, token_out, S);
     else if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
     else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
   };
@@ -562,8 +657,9 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
     enqueue();
     HIPCHK(c, hipGetLastError());
   } else {
-    if (persistent) S = -1;                        // the kernel reads the kept list from the device
-    std::string key(reinterpret_cast<const char*>(&S), sizeof(S));
+    // the persistent kernel reads the kept list from the device: one graph whatever the mask
+    const int kind = persistent ? -1 : batched ? S + 1000 : S;
+    std::string key(reinterpret_cast<const char*>(&kind), sizeof(kind));
     key.append(reinterpret_cast<const char*>(&last_tokens), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&logits_out), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&token_out), sizeof(void*));
@@ -601,6 +697,9 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->step_timing = value ? 1 : 0;
       drop_graphs(c);
       return FIRST_OK;
+    case FIRST_OPT_BATCH_PATH:
+      if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
+      c->batch_path = value; return FIRST_OK;
     case FIRST_OPT_STEP_BARRIER:
       if (value < 0 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
       c->step_two_level = value;
