@@ -426,6 +426,30 @@ __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, 
   }
 }
 
+// K-segments [c0, c1) (2048 elements each, c1 - c0 <= 2) of x into the two-plane layout, no
+// norm: one batch of coherent loads.  Executed by the service wave.
+__device__ __forceinline__ void sk_stage_segments(float* xs, const float* x, int K, int c0, int c1) {
+  const int lane = threadIdx.x & 63;
+  const int g_begin = c0 * (SK_SEG / 8), g_end = min(c1 * (SK_SEG / 8), K >> 3);
+  f32x4_t a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int k = min(g_begin + i * 64 + lane, g_end - 1) << 3;
+    coh_issue16(a[i], x + k);
+    coh_issue16(b[i], x + k + 4);
+  }
+  coh_wait();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    coh_use(a[i]); coh_use(b[i]);
+    const int g = g_begin + i * 64 + lane;
+    if (g < g_end) {
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i];
+      *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = b[i];
+    }
+  }
+}
+
 // A segment is one mat-vec phase of the step (QKV, O, gate/up, down of a kept layer, or the
 // LM head).  Rows [row0, row0+nrows) of its [N, K] matrix belong to this workgroup; a unit
 // is one 2048-element piece of one row and goes to streaming wave (unit % SK_SWAVES) in round
@@ -436,7 +460,7 @@ struct SegDesc {
   const bf16 *m0, *m1, *m2;     // up to three stacked matrices (or two interleaved ones)
   int n0, n1, K, inter;
   int row0, nrows, nseg, nunits, nr_pad;
-  unsigned inv_nseg;            // ceil(2^32 / nseg): unit / nseg = umulhi(unit, inv_nseg) for the small units here
+  unsigned inv_nrows;           // ceil(2^32 / nrows): unit / nrows = umulhi(unit, inv_nrows) for the small units here
   int kind;
   const float* gain;            // RMSNorm gain of the phase's input (null: no norm)
   bf16* kv;                     // KV pool of the layer (attention precedes SEG_O)
@@ -450,7 +474,7 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int 
   d.row0 = (int)((unsigned)(n * cu) / (unsigned)ncu) * pair;
   d.nrows = (int)((unsigned)(n * (cu + 1)) / (unsigned)ncu) * pair - d.row0;
   d.nseg = K / SK_SEG;
-  d.inv_nseg = d.nseg == 1 ? 0u : (unsigned)((0x100000000ull + d.nseg - 1) / d.nseg);   // (nseg == 1 handled at use)
+  d.inv_nrows = d.nrows <= 1 ? 0u : (unsigned)((0x100000000ull + d.nrows - 1) / d.nrows);   // (nrows <= 1 handled at use)
   d.nunits = d.nrows * d.nseg;
   const int nr = (d.nunits + SK_SWAVES - 1) / SK_SWAVES;
   d.nr_pad = max(SK_PD, (nr + SK_PD - 1) / SK_PD * SK_PD);
@@ -459,7 +483,7 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int 
 __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   d.m0 = uni(d.m0); d.m1 = uni(d.m1); d.m2 = uni(d.m2); d.gain = uni(d.gain); d.kv = uni(d.kv);
   d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
-  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.inv_nseg = (unsigned)uni((int)d.inv_nseg); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
+  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.inv_nrows = (unsigned)uni((int)d.inv_nrows); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
   return d;
 }
 
@@ -533,8 +557,10 @@ __device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enabl
   const int u = uni(round * SK_SWAVES + wave);
   const int valid = uni((int)(enable && u < d.nunits));   // SEG_NONE has no units
   const int uu = valid ? u : 0;
-  const int nseg = uni(max(d.nseg, 1));
-  const int rl = nseg == 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nseg)), sg = uu - rl * nseg;
+  // units are ordered segment-major (all rows of K-segment 0, then of segment 1, ...), so the
+  // first rounds of a phase need only the first part of its input vector
+  const int nrows = uni(d.nrows);
+  const int sg = nrows <= 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nrows)), rl = uu - sg * nrows;
   const unsigned long long ra = seg_row_addr(d, uni(d.row0) + rl);
   bf16* row = reinterpret_cast<bf16*>(((unsigned long long)(unsigned)uni((int)(ra >> 32)) << 32) | (unsigned)uni((int)(unsigned)ra));
   const int row_bytes = uni(d.K * 2);
@@ -550,8 +576,10 @@ __device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enabl
 // Dot product of one ring slot with the staged activation vector -> psum[unit].  The LDS
 // reads are issued together and eight independent accumulators keep the FMA chains short:
 // with two waves per SIMD there is little else to hide latency behind.
+// staged / seen: for a phase whose input is staged segment by segment while it already
+// streams (null otherwise): *staged = segments in LDS so far, seen = this wave's last reading.
 __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave, const uint4 (&b)[4], const float* xs,
-                                           float* psum) {
+                                           float* psum, const int* staged, int& seen) {
   const int u = uni(round * SK_SWAVES + wave);
   const int valid = uni((int)(u < d.nunits));
 #ifdef SK_FAKE_CONSUME
@@ -563,8 +591,15 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
 #endif
   const int lane = threadIdx.x & 63, K = uni(d.K);
   const int uu = valid ? u : 0;
-  const int nseg = uni(d.nseg);
-  const int sg = nseg == 1 ? 0 : uu - uni((int)__umulhi((unsigned)uu, d.inv_nseg)) * nseg;
+  const int nrows = uni(d.nrows);
+  const int sg = nrows <= 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nrows));
+  if (staged != nullptr && sg >= seen) {
+    unsigned spins = 0;
+    do {
+      seen = uni(__hip_atomic_load(staged, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+      if (seen <= sg) __builtin_amdgcn_s_sleep(4);
+    } while (seen <= sg && ++spins < SK_SPIN_LIMIT);      // bounded; the service wave always gets there
+  }
   const float* x0p = xs + ((sg * SK_SEG + lane * 8) >> 1);
   const float* x1p = x0p + (K >> 1);
   float4 x0[4], x1[4];
@@ -587,9 +622,9 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
   if (valid && lane == 63) psum[u] = tot;
 }
 
-__device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg) {
+__device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg, int nrows) {
   float s = 0.f;
-  for (int g = 0; g < nseg; ++g) s += psum[rl * nseg + g];
+  for (int g = 0; g < nseg; ++g) s += psum[g * nrows + rl];
   return s;
 }
 
@@ -948,7 +983,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         SK_STAMP(2);
         sk_stage_wave(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f);
       } else if (cur.kind == SEG_DN) {
-        sk_stage_wave(S.zs, p.z + (size_t)b * F, F, nullptr, 0.f);
+        // the down projection starts on the first K-segment of its input; the rest is staged
+        // while it streams (after the workgroup barrier below)
+        sk_stage_segments(S.zs, p.z + (size_t)b * F, F, 0, 1);
+        __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       } else if (fast_norm) {
         sk_stage_norm_wave(S.xs, h, D, gains, p.eps);
       } else {
@@ -961,27 +999,34 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // fetched while the weights stream
       float h_prev = 0.f;
       if ((cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
+      if (cur.kind == SEG_DN) {
+        for (int c = 1; c < cur.nseg; c += 2) {
+          const int c1 = min(c + 2, cur.nseg);
+          sk_stage_segments(S.zs, p.z + (size_t)b * F, F, c, c1);
+          __hip_atomic_store(S.flag + 2, c1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
       lds_barrier();                               // partial sums complete
       SK_STAMP(4);
       // results of the segment
       if (cur.kind == SEG_QKV) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
-        for (int r = lane; r < cur.nrows; r += 64) st_coh(out + cur.row0 + r, sk_row_sum(S.psum, r, cur.nseg));
+        for (int r = lane; r < cur.nrows; r += 64) st_coh(out + cur.row0 + r, sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
-        if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg));
+        if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
         for (int r = 64 + lane; r < cur.nrows; r += 64)
-          st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg));
+          st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
       } else if (cur.kind == SEG_GU) {
         float* z = p.z + (size_t)b * F;
         for (int r = lane; r < cur.nrows / 2; r += 64) {
-          const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg);
+          const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg, cur.nrows), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg, cur.nrows);
           st_coh(z + cur.row0 / 2 + r, siluf(gt) * up);
         }
       } else {
         float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
-          const float v = sk_row_sum(S.psum, r, cur.nseg);
+          const float v = sk_row_sum(S.psum, r, cur.nseg, cur.nrows);
           if (lg) lg[cur.row0 + r] = v;
           const Best c{v, cur.row0 + r};
           if (better(c, best)) best = c;
@@ -1047,18 +1092,20 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // all blocks but the last request ahead inside this segment; the last one requests the
       // first rounds of the next segment (no per-round choice between the two descriptors)
       const int last0 = cur.nr_pad - SK_PD;
+      const int* staged = cur.kind == SEG_DN ? S.flag + 2 : nullptr;
+      int seen = 1;
       for (int r0 = 0; r0 < last0; r0 += SK_PD) {
         if (P.tdbg && s == 6 && cu == 0 && tid == 0 && r0 / SK_PD < 10)          // timing aid: progress of the GU stream
           P.tdbg[(4 * P.L + 1) * SK_TSLOTS + 2 * ncu + r0 / SK_PD] = wall_clock64();
 #pragma unroll
         for (int j = 0; j < SK_PD; ++j) {
-          sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum);
+          sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
           sk_issue(cur, r0 + j + SK_PD, true, wave, buf[j]);
         }
       }
 #pragma unroll
       for (int j = 0; j < SK_PD; ++j) {
-        sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum);
+        sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
         sk_issue(nxt, j, nxt.kind != SEG_O || j < SK_PD_EARLY, wave, buf[j]);
       }
       lds_barrier();                               // partial sums complete
