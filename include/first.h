@@ -52,6 +52,8 @@ extern "C" {
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
+#define FIRST_OPT_PREFILL_ATTN  7  /* prompt attention.  1 (default): tiled kernel on the matrix cores when the cache is bf16
+                                      and head_dim is 64 or 128, else the plain kernel; 0: always the plain fp32 kernel */
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
                                       keep it share one pass over its weights (bf16 models, widths multiples of 8),
                                       else one pass per sequence; 0: always one pass per sequence; 1: shared pass or error */

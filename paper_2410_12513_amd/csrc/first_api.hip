@@ -57,6 +57,9 @@ struct first_ctx {
   // prefill workspace
   float *p_H = nullptr, *p_q = nullptr, *p_k = nullptr, *p_v = nullptr, *p_g = nullptr, *p_u = nullptr, *p_sig = nullptr;
   void *p_x = nullptr, *p_a = nullptr, *p_z = nullptr;
+  bf16 *p_qh = nullptr, *p_ql = nullptr, *p_kc = nullptr, *p_vt = nullptr;   // matrix-core prefill attention operands
+  int p_tp = 0;                           // key pitch of p_vt / rows of p_kc (max_seq_len padded to the key tile)
+  int prefill_flash = 1;                  // FIRST_OPT_PREFILL_ATTN
   float2* p_cs = nullptr;
   // host state
   int B = 0;
@@ -333,6 +336,24 @@ int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const vo
   return FIRST_OK;
 }
 
+// Prompt attention on the matrix cores: operand preparation (query split, key gather, value
+// transpose out of the cache pages) and the tiled kernel.
+void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int* pt, float* out, int T) {
+  const first_model_desc& d = c->d;
+  const size_t nq_all = (size_t)T * c->nq;
+  hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)std::min<size_t>((nq_all + WG - 1) / WG, 16384)), dim3(WG), 0, st, c->p_q,
+                     c->p_qh, c->p_ql, nq_all);
+  hipLaunchKernelGGL(k_kv_gather, dim3((T + 31) / 32, d.n_kv_heads), dim3(WG), 0, st, pool, c->page_elems, pt, c->p_kc,
+                     c->p_vt, T, c->p_tp, d.n_kv_heads, d.head_dim, d.kv_page_tokens);
+  const dim3 grid((T + WAVES * FA_QW - 1) / (WAVES * FA_QW), d.n_q_heads);
+  if (d.head_dim == 128)
+    hipLaunchKernelGGL(k_attn_flash<128>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, out, T, c->p_tp,
+                       d.n_q_heads, d.n_kv_heads);
+  else
+    hipLaunchKernelGGL(k_attn_flash<64>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, out, T, c->p_tp,
+                       d.n_q_heads, d.n_kv_heads);
+}
+
 // Prefill of one sequence: T prompt tokens at ids, all layers, routers scored on the way.
 template <typename WT>
 int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, float* logits_out, int* token_out) {
@@ -366,8 +387,12 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     if ((rc = launch_gemm(c, st, d.dtype, x, l.wv, c->p_v, T, c->nkv, D, 0, true))) return rc;
     hipLaunchKernelGGL(k_rope_kvwrite<WT>, dim3(T), dim3(WG), 0, st, c->p_q, c->p_k, c->p_v, c->p_cs, pt, pool,
                        c->page_elems, d.n_q_heads, d.n_kv_heads, hd, P, qscale);
-    hipLaunchKernelGGL((k_attn_prefill<float, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
-                       pt, pool, c->page_elems, T, d.n_q_heads, d.n_kv_heads, hd, P, QB);
+    if (c->p_qh && c->prefill_flash) {
+      launch_attn_flash(c, st, reinterpret_cast<const bf16*>(pool), pt, a, T);
+    } else {
+      hipLaunchKernelGGL((k_attn_prefill<float, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
+                         pt, pool, c->page_elems, T, d.n_q_heads, d.n_kv_heads, hd, P, QB);
+    }
     if ((rc = launch_gemm(c, st, d.dtype, a, l.wo, c->p_H, T, D, c->nq, 1, true))) return rc;
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
                        (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps);
@@ -470,6 +495,11 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, &c->p_sig, T)); A(dev_alloc(c, &c->p_cs, (size_t)T * c->half));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
+  c->p_tp = (T + FA_KT - 1) / FA_KT * FA_KT;
+  if (d.dtype == FIRST_DTYPE_BF16 && (d.head_dim == 64 || d.head_dim == 128)) {
+    A(dev_alloc(c, &c->p_qh, (size_t)T * c->nq)); A(dev_alloc(c, &c->p_ql, (size_t)T * c->nq));
+    A(dev_alloc(c, &c->p_kc, (size_t)c->p_tp * c->nkv)); A(dev_alloc(c, &c->p_vt, (size_t)c->p_tp * c->nkv));
+  }
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_z), (size_t)T * d.d_ffn * 4));
   c->xpitch = (std::max(std::max(d.d_model, c->nq), d.d_ffn) + 31) / 32 * 32;
   if (B > 1) {
@@ -697,6 +727,8 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->step_timing = value ? 1 : 0;
       drop_graphs(c);
       return FIRST_OK;
+    case FIRST_OPT_PREFILL_ATTN:
+      c->prefill_flash = value ? 1 : 0; return FIRST_OK;
     case FIRST_OPT_BATCH_PATH:
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
       c->batch_path = value; return FIRST_OK;

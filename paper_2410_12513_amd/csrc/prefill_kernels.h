@@ -460,6 +460,166 @@ __global__ void __launch_bounds__(WG) k_copy_f32(const float* __restrict__ src, 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Causal GQA attention over the prompt on the matrix cores (bf16 cache, head_dim 64 or 128).
+//
+// Operands are prepared per layer by two small kernels: the rotated, pre-scaled queries are
+// split as q = hi + lo (two bf16 parts, 16 significant bits); the keys the cache holds are
+// gathered into a contiguous [T][Hkv*hd] copy and its values into a transposed one
+// [Hkv*hd][Tp] (Tp = T padded to the key tile), so that every MFMA operand is a 16- or 8-byte
+// contiguous load.  Attention reads exactly the values the cache stores (Section 4.3: decode
+// later reads the same ones).
+//
+// One wave owns 32 query positions of one head and walks the key tiles (32 keys) up to its
+// diagonal.  Everything is computed transposed, so that a lane owns ONE query column:
+//   S^T[key][q] = K Q^T     (A = key rows, B = query columns; hi and lo parts of q)
+//   O^T[dim][q] = V^T P^T   (A = rows of the transposed values, B = the probabilities straight
+//                            from the accumulator registers of S^T, split hi + lo)
+// The softmax statistics of a query are then per lane (plus one exchange with lane ^ 32), and
+// rescaling O^T is a per-lane multiply.  Accumulator layout of the 32x32 MFMA: lane l holds
+// column l % 32, register r holds row 8 (r / 4) + 4 (l / 32) + r % 4.
+constexpr int FA_QW = 32;                 // queries per wave
+constexpr int FA_KT = 32;                 // keys per tile
+
+// q (fp32, rotated, scaled) -> hi / lo bf16.  grid-stride over n elements.
+__global__ void __launch_bounds__(WG) k_split_bf16(const float* __restrict__ x, bf16* __restrict__ hi, bf16* __restrict__ lo, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n; i += (size_t)gridDim.x * WG) {
+    const float v = x[i];
+    const bf16 h = from_f32<bf16>(v);
+    hi[i] = h;
+    lo[i] = from_f32<bf16>(v - to_f32(h));
+  }
+}
+
+// Cache pages -> kc[t][g*hd + d] and vt[(g*hd + d)][t] for 32 tokens of KV head g.
+// grid = (ceil(T/32), Hkv); hd <= 128.
+__global__ void __launch_bounds__(WG) k_kv_gather(const bf16* __restrict__ pool, size_t page_elems, const int* __restrict__ pt,
+                                                  bf16* __restrict__ kc, bf16* __restrict__ vt, int T, int Tp, int Hkv,
+                                                  int hd, int P) {
+  __shared__ uint16_t vs[32][128 + 2];
+  const int t0 = blockIdx.x * 32, g = blockIdx.y, nkv = Hkv * hd;
+  const size_t head_off = (size_t)g * P * hd, v_off = (size_t)Hkv * P * hd;
+  for (int i = threadIdx.x; i < 32 * hd; i += WG) {
+    const int tt = i / hd, d = i - tt * hd, t = t0 + tt;
+    uint16_t kvv = 0, vvv = 0;
+    if (t < T) {
+      const size_t base = (size_t)pt[t / P] * page_elems + head_off + (size_t)(t % P) * hd + d;
+      kvv = pool[base].v;
+      vvv = pool[base + v_off].v;
+    }
+    kc[(size_t)t * nkv + g * hd + d].v = kvv;                  // rows up to Tp exist
+    vs[tt][d] = vvv;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 32 * hd; i += WG) {
+    const int d = i / 32, tt = i - d * 32;
+    vt[(size_t)(g * hd + d) * Tp + t0 + tt].v = vs[tt][d];
+  }
+}
+
+template <int HD>
+__global__ void __launch_bounds__(WG) k_attn_flash(const bf16* __restrict__ qh, const bf16* __restrict__ ql,
+                                                   const bf16* __restrict__ kc, const bf16* __restrict__ vt,
+                                                   float* __restrict__ out, int T, int Tp, int Hq, int Hkv) {
+  constexpr int KS = HD / 16;             // k-steps of the score product
+  constexpr int DT = HD / 32;             // 32-dim tiles of the output
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, gl = lane >> 5;
+  const int h = blockIdx.y, g = h / (Hq / Hkv);
+  const int q0 = (blockIdx.x * WAVES + wave) * FA_QW;
+  if (q0 >= T) return;
+  const int nq = Hq * HD, nkv = Hkv * HD;
+  const int qi = q0 + col;                                       // this lane's query position
+  const int qc = min(qi, T - 1);
+
+  bf16x8_t Qh[KS], Ql[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const size_t o = (size_t)qc * nq + h * HD + 16 * s + 8 * gl;
+    Qh[s] = *reinterpret_cast<const bf16x8_t*>(qh + o);
+    Ql[s] = *reinterpret_cast<const bf16x8_t*>(ql + o);
+  }
+  floatx16_t O[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[t][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int n_tiles = (min(q0 + FA_QW, T) + FA_KT - 1) / FA_KT;  // keys 0 .. last query of the block
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    const int k0 = kt * FA_KT;
+    // S^T = K Q^T
+    floatx16_t S;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) S[r] = 0.f;
+    const bf16* krow = kc + (size_t)(k0 + col) * nkv + g * HD + 8 * gl;     // this lane's key row (A operand)
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(krow + 16 * s);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[s], S, 0, 0, 0);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[s], S, 0, 0, 0);
+    }
+    // causal mask and the tile's softmax statistics of this lane's query
+    float mt = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = k0 + 8 * (r >> 2) + 4 * gl + (r & 3);
+      if (key > qi) S[r] = -INFINITY;
+      mt = fmaxf(mt, S[r]);
+    }
+    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+    const float mn = fmaxf(m, mt);                 // finite: key 0 is visible to every query
+    const float corr = __expf(m - mn);
+    float ls = 0.f;
+    floatx16_t Pv;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { Pv[r] = __expf(S[r] - mn); ls += Pv[r]; }
+    ls += __shfl_xor(ls, 32, 64);
+    l = l * corr + ls;
+    m = mn;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) O[t][r] *= corr;
+    // O^T += V^T P^T: k-step s2 uses accumulator registers 8 s2 .. 8 s2 + 7 of P as they are;
+    // slot (gl, e) of that step is key k0 + 16 s2 + 8 (e / 4) + 4 gl + e % 4
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      bf16x8_t Ph, Pl;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float pv = Pv[8 * s2 + e];
+        const bf16 hi = from_f32<bf16>(pv);
+        const bf16 lo = from_f32<bf16>(pv - to_f32(hi));
+        Ph[e] = __builtin_bit_cast(__bf16, hi.v);
+        Pl[e] = __builtin_bit_cast(__bf16, lo.v);
+      }
+#pragma unroll
+      for (int t = 0; t < DT; ++t) {
+        const bf16* vrow = vt + (size_t)(g * HD + 32 * t + col) * Tp + k0 + 16 * s2 + 4 * gl;
+        const uint2 v0 = *reinterpret_cast<const uint2*>(vrow);          // keys +0..3
+        const uint2 v1 = *reinterpret_cast<const uint2*>(vrow + 8);      // keys +8..11
+        union { uint4 u; bf16x8_t b; } vf;
+        vf.u = make_uint4(v0.x, v0.y, v1.x, v1.y);
+        O[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, Pl, O[t], 0, 0, 0);
+        O[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, Ph, O[t], 0, 0, 0);
+      }
+    }
+  }
+  if (qi < T) {
+    const float inv = 1.0f / l;
+    float* orow = out + (size_t)qi * nq + h * HD;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const float4 v = make_float4(O[t][4 * rr] * inv, O[t][4 * rr + 1] * inv, O[t][4 * rr + 2] * inv, O[t][4 * rr + 3] * inv);
+        *reinterpret_cast<float4*>(orow + 32 * t + 8 * rr + 4 * gl) = v;
+      }
+  }
+}
+
 __global__ void k_set_int(int* p, int v) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = v; }
 
 __global__ void __launch_bounds__(WG) k_fill_u32(unsigned* p, unsigned v, size_t n) {

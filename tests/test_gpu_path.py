@@ -230,6 +230,28 @@ def test_page_permutation_and_graph_replay_do_not_change_a_bit():
         assert torch.equal(runs[0][0], r[0]) and torch.equal(runs[0][1], r[1]) and torch.equal(runs[0][2], r[2])
 
 
+@pytest.mark.parametrize("model,T", [("mini_bf16", 203), ("mini_hd128", 97), ("mini_hd128", 1)])
+def test_prompt_attention_on_matrix_cores_agrees_with_the_plain_kernel(model, T):
+    """Option 7: 1 = tiled MFMA kernel (default), 0 = plain fp32 kernel; same cache, same
+    logits up to the 16-bit split of queries and probabilities."""
+    desc = CONFIGS[model]
+    prompt = make_prompt(desc.vocab, T, 77)
+    outs = {}
+    for kind in (1, 0):
+        desc, w, router, ctx = build(model, 77, max_seq_len=T + 8)
+        ctx.set_option(7, kind)
+        outs[kind] = _prefill(ctx, desc, [prompt])
+        outs[kind]["k_last"] = ctx.kv_read(0, desc.n_layers - 1, 0, T)[0].float().cpu()
+        ctx.close()
+    scale = float(outs[0]["logits"].abs().max())
+    assert float((outs[1]["logits"] - outs[0]["logits"]).abs().max()) <= 2e-3 * max(scale, 1.0)
+    assert float((outs[1]["rho"] - outs[0]["rho"]).abs().max()) <= 1e-4
+    assert float((outs[1]["k_last"] - outs[0]["k_last"]).abs().max()) <= 2e-2 * float(outs[0]["k_last"].abs().max())
+    st = O.prefill_route(desc, w, router, prompt)
+    ok, ma, rel = logits_close(outs[1]["logits"][0], st.logits, desc.dtype)
+    assert ok, (ma, rel)
+
+
 def test_batch_of_sequences_equals_each_sequence_alone():
     desc = CONFIGS["mini_bf16"]
     prompts = [make_prompt(desc.vocab, n, 30 + i) for i, n in enumerate((17, 64, 33))]
