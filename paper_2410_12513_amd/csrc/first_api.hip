@@ -58,6 +58,7 @@ struct first_ctx {
   float *p_H = nullptr, *p_q = nullptr, *p_k = nullptr, *p_v = nullptr, *p_g = nullptr, *p_u = nullptr, *p_sig = nullptr;
   void *p_x = nullptr, *p_a = nullptr, *p_z = nullptr;
   bf16 *p_qh = nullptr, *p_ql = nullptr, *p_kc = nullptr, *p_vt = nullptr;   // matrix-core prefill attention operands
+  bf16 *p_xh = nullptr, *p_xl = nullptr, *p_ah = nullptr, *p_al = nullptr, *p_zh = nullptr, *p_zl = nullptr;   // split activations (bf16 models)
   int p_tp = 0;                           // key pitch of p_vt / rows of p_kc (max_seq_len padded to the key tile)
   int prefill_flash = 1;                  // FIRST_OPT_PREFILL_ATTN
   float2* p_cs = nullptr;
@@ -336,9 +337,17 @@ int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const vo
   return FIRST_OK;
 }
 
+int launch_gemm_hl(first_ctx* c, hipStream_t st, const bf16* Ah, const bf16* Al, const void* W, float* C, int M, int N, int K,
+                   int acc) {
+  dim3 grid((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M);
+  hipLaunchKernelGGL(k_gemm_nt_bf16_hl, grid, dim3(WG), 0, st, Ah, Al, reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
 // Prompt attention on the matrix cores: operand preparation (query split, key gather, value
 // transpose out of the cache pages) and the tiled kernel.
-void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int* pt, float* out, int T) {
+void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int* pt, int T) {
   const first_model_desc& d = c->d;
   const size_t nq_all = (size_t)T * c->nq;
   hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)std::min<size_t>((nq_all + WG - 1) / WG, 16384)), dim3(WG), 0, st, c->p_q,
@@ -347,10 +356,10 @@ void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int
                      c->p_vt, T, c->p_tp, d.n_kv_heads, d.head_dim, d.kv_page_tokens);
   const dim3 grid((T + WAVES * FA_QW - 1) / (WAVES * FA_QW), d.n_q_heads);
   if (d.head_dim == 128)
-    hipLaunchKernelGGL(k_attn_flash<128>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, out, T, c->p_tp,
+    hipLaunchKernelGGL(k_attn_flash<128>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, c->p_ah, c->p_al, T, c->p_tp,
                        d.n_q_heads, d.n_kv_heads);
   else
-    hipLaunchKernelGGL(k_attn_flash<64>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, out, T, c->p_tp,
+    hipLaunchKernelGGL(k_attn_flash<64>, grid, dim3(WG), 0, st, c->p_qh, c->p_ql, c->p_kc, c->p_vt, c->p_ah, c->p_al, T, c->p_tp,
                        d.n_q_heads, d.n_kv_heads);
 }
 
@@ -377,30 +386,42 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     const LayerPtrs& l = c->layers[i];
     WT* pool = reinterpret_cast<WT*>(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem);
     // router i reads the stream entering layer i, in the same pass as the attention norm
+    const bool hl = d.dtype == FIRST_DTYPE_BF16;   // activations leave their producers split for the matrix cores
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_attn,
-                       c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps);
+                       c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
     hipLaunchKernelGGL(k_router_reduce, dim3(1), dim3(WG), 0, st, c->p_sig, T, c->d_rho + (size_t)b * L + i,
                        c->d_mask + (size_t)b * L + i);
     int rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wq, c->p_q, T, c->nq, D, 0, true))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wk, c->p_k, T, c->nkv, D, 0, true))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wv, c->p_v, T, c->nkv, D, 0, true))) return rc;
+    auto gemm = [&](const float* A32, const bf16* Ah, const bf16* Al, const void* W, float* C, int N, int K, int acc) {
+      return hl ? launch_gemm_hl(c, st, Ah, Al, W, C, T, N, K, acc) : launch_gemm(c, st, d.dtype, A32, W, C, T, N, K, acc, true);
+    };
+    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wq, c->p_q, c->nq, D, 0))) return rc;
+    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wk, c->p_k, c->nkv, D, 0))) return rc;
+    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wv, c->p_v, c->nkv, D, 0))) return rc;
     hipLaunchKernelGGL(k_rope_kvwrite<WT>, dim3(T), dim3(WG), 0, st, c->p_q, c->p_k, c->p_v, c->p_cs, pt, pool,
                        c->page_elems, d.n_q_heads, d.n_kv_heads, hd, P, qscale);
     if (c->p_qh && c->prefill_flash) {
-      launch_attn_flash(c, st, reinterpret_cast<const bf16*>(pool), pt, a, T);
+      launch_attn_flash(c, st, reinterpret_cast<const bf16*>(pool), pt, T);
     } else {
       hipLaunchKernelGGL((k_attn_prefill<float, WT>), dim3((T + QB - 1) / QB, d.n_kv_heads), dim3(WG), lds_attn, st, c->p_q, a,
                          pt, pool, c->page_elems, T, d.n_q_heads, d.n_kv_heads, hd, P, QB);
+      if (hl) {
+        const size_t n = (size_t)T * c->nq;
+        hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)std::min<size_t>((n + WG - 1) / WG, 16384)), dim3(WG), 0, st, a, c->p_ah,
+                           c->p_al, n);
+      }
     }
-    if ((rc = launch_gemm(c, st, d.dtype, a, l.wo, c->p_H, T, D, c->nq, 1, true))) return rc;
+    if ((rc = gemm(a, c->p_ah, c->p_al, l.wo, c->p_H, D, c->nq, 1))) return rc;
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
-                       (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps);
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wg, c->p_g, T, F, D, 0, true))) return rc;
-    if ((rc = launch_gemm(c, st, d.dtype, x, l.wu, c->p_u, T, F, D, 0, true))) return rc;
-    hipLaunchKernelGGL(k_silu_mul<float>, dim3(std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536)), dim3(WG), 0, st,
-                       c->p_g, c->p_u, z, (size_t)T * F);
-    if ((rc = launch_gemm(c, st, d.dtype, z, l.wd, c->p_H, T, D, F, 1, true))) return rc;
+                       (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
+    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wg, c->p_g, F, D, 0))) return rc;
+    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wu, c->p_u, F, D, 0))) return rc;
+    const unsigned sm_grid = (unsigned)std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536);
+    if (hl)
+      hipLaunchKernelGGL(k_silu_mul_split, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, c->p_zh, c->p_zl, (size_t)T * F);
+    else
+      hipLaunchKernelGGL(k_silu_mul<float>, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, z, (size_t)T * F);
+    if ((rc = gemm(z, c->p_zh, c->p_zl, l.wd, c->p_H, D, F, 1))) return rc;
   }
   // last position -> decode residual slot of this sequence (+ optional copy out), first token
   hipLaunchKernelGGL(k_copy_f32, dim3((D + WG - 1) / WG), dim3(WG), 0, st, c->p_H + (size_t)(T - 1) * D,
@@ -495,6 +516,11 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, &c->p_sig, T)); A(dev_alloc(c, &c->p_cs, (size_t)T * c->half));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));
+  if (d.dtype == FIRST_DTYPE_BF16) {
+    A(dev_alloc(c, &c->p_xh, (size_t)T * d.d_model)); A(dev_alloc(c, &c->p_xl, (size_t)T * d.d_model));
+    A(dev_alloc(c, &c->p_ah, (size_t)T * c->nq)); A(dev_alloc(c, &c->p_al, (size_t)T * c->nq));
+    A(dev_alloc(c, &c->p_zh, (size_t)T * d.d_ffn)); A(dev_alloc(c, &c->p_zl, (size_t)T * d.d_ffn));
+  }
   c->p_tp = (T + FA_KT - 1) / FA_KT * FA_KT;
   if (d.dtype == FIRST_DTYPE_BF16 && (d.head_dim == 64 || d.head_dim == 128)) {
     A(dev_alloc(c, &c->p_qh, (size_t)T * c->nq)); A(dev_alloc(c, &c->p_ql, (size_t)T * c->nq));

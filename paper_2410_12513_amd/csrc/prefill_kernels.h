@@ -34,7 +34,8 @@ __global__ void __launch_bounds__(WG) k_rope_table(const double* __restrict__ th
 template <typename XT>
 __global__ void __launch_bounds__(WG) k_rmsnorm_router(const float* __restrict__ H, const float* __restrict__ gain,
                                                        const float* __restrict__ rw, XT* __restrict__ x,
-                                                       float* __restrict__ sig, int T, int D, float eps) {
+                                                       float* __restrict__ sig, int T, int D, float eps,
+                                                       bf16* __restrict__ xh = nullptr, bf16* __restrict__ xl = nullptr) {
   const int t = blockIdx.x * WAVES + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (t >= T) return;
@@ -53,9 +54,17 @@ __global__ void __launch_bounds__(WG) k_rmsnorm_router(const float* __restrict__
   for (int k = lane * 4; k < D; k += 256) {
     const float4 v = *reinterpret_cast<const float4*>(row + k);
     const float4 g = *reinterpret_cast<const float4*>(gain + k);
-    XT* o = x + (size_t)t * D + k;
-    o[0] = from_f32<XT>(v.x * g.x * r); o[1] = from_f32<XT>(v.y * g.y * r);
-    o[2] = from_f32<XT>(v.z * g.z * r); o[3] = from_f32<XT>(v.w * g.w * r);
+    const float y[4] = {v.x * g.x * r, v.y * g.y * r, v.z * g.z * r, v.w * g.w * r};
+    if (xh) {                                      // split for the matrix cores: y = hi + lo
+      uint16_t hi[4], lo[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { hi[e] = f2bf(y[e]); lo[e] = f2bf(y[e] - bf2f(hi[e])); }
+      *reinterpret_cast<uint2*>(xh + (size_t)t * D + k) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+      *reinterpret_cast<uint2*>(xl + (size_t)t * D + k) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+    } else {
+      XT* o = x + (size_t)t * D + k;
+      o[0] = from_f32<XT>(y[0]); o[1] = from_f32<XT>(y[1]); o[2] = from_f32<XT>(y[2]); o[3] = from_f32<XT>(y[3]);
+    }
   }
   if (rw) {
     dot = wave_sum(dot);
@@ -230,6 +239,92 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_split(const float* __restri
       split2(ra[i][1].x, ra[i][1].y, h.z, l.z); split2(ra[i][1].z, ra[i][1].w, h.w, l.w);
       *reinterpret_cast<uint4*>(sAh + row * GB_PITCH + kc) = h;
       *reinterpret_cast<uint4*>(sAl + row * GB_PITCH + kc) = l;
+      *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
+    }
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += GB_K) {
+    __syncthreads();
+    stash();
+    __syncthreads();
+    if (k0 + GB_K < K) fetch(k0 + GB_K);
+#pragma unroll
+    for (int kk = 0; kk < GB_K; kk += 16) {
+      bf16x8_t ah[2], al[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int ao = (wm + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3);
+        ah[i] = *reinterpret_cast<const bf16x8_t*>(sAh + ao);
+        al[i] = *reinterpret_cast<const bf16x8_t*>(sAl + ao);
+        b[i] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < M && col < N) {
+          float* c = C + (size_t)row * N + col;
+          *c = accumulate ? *c + acc[i][j][r] : acc[i][j][r];
+        }
+      }
+    }
+}
+
+// The same split-precision contraction with the activations already split by their producer
+// (Ah + Al, bf16 each): no conversion work here, which otherwise repeats once per column tile.
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                        const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
+                                                        int K, int accumulate) {
+  __shared__ __align__(16) uint16_t sAh[GB_M * GB_PITCH];
+  __shared__ __align__(16) uint16_t sAl[GB_M * GB_PITCH];
+  __shared__ __align__(16) uint16_t sB[GB_N * GB_PITCH];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  floatx16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint4 rh[4], rl[4], rb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      const int k = k0 + kc;
+      rh[i] = make_uint4(0, 0, 0, 0); rl[i] = rh[i]; rb[i] = rh[i];
+      if (k < K) {
+        if (m0 + row < M) {
+          rh[i] = *reinterpret_cast<const uint4*>(Ah + (size_t)(m0 + row) * K + k);
+          rl[i] = *reinterpret_cast<const uint4*>(Al + (size_t)(m0 + row) * K + k);
+        }
+        if (n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
+      }
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      *reinterpret_cast<uint4*>(sAh + row * GB_PITCH + kc) = rh[i];
+      *reinterpret_cast<uint4*>(sAl + row * GB_PITCH + kc) = rl[i];
       *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
     }
   };
@@ -451,6 +546,17 @@ __global__ void __launch_bounds__(WG) k_silu_mul(const float* __restrict__ g, co
     z[i] = from_f32<XT>(siluf(g[i]) * u[i]);
 }
 
+// z = silu(g) * u, written as hi + lo bf16 parts for the matrix cores.
+__global__ void __launch_bounds__(WG) k_silu_mul_split(const float* __restrict__ g, const float* __restrict__ u,
+                                                       bf16* __restrict__ zh, bf16* __restrict__ zl, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * WG + threadIdx.x; i < n; i += (size_t)gridDim.x * WG) {
+    const float z = siluf(g[i]) * u[i];
+    const bf16 h = from_f32<bf16>(z);
+    zh[i] = h;
+    zl[i] = from_f32<bf16>(z - to_f32(h));
+  }
+}
+
 __global__ void __launch_bounds__(WG) k_copy_f32(const float* __restrict__ src, float* __restrict__ dst,
                                                  float* __restrict__ dst2, int n) {
   for (int i = blockIdx.x * WG + threadIdx.x; i < n; i += gridDim.x * WG) {
@@ -517,10 +623,12 @@ __global__ void __launch_bounds__(WG) k_kv_gather(const bf16* __restrict__ pool,
   }
 }
 
+// Output: hi + lo bf16 parts (outh, outl), the form the output projection consumes.
 template <int HD>
 __global__ void __launch_bounds__(WG) k_attn_flash(const bf16* __restrict__ qh, const bf16* __restrict__ ql,
                                                    const bf16* __restrict__ kc, const bf16* __restrict__ vt,
-                                                   float* __restrict__ out, int T, int Tp, int Hq, int Hkv) {
+                                                   bf16* __restrict__ outh, bf16* __restrict__ outl, int T, int Tp, int Hq,
+                                                   int Hkv) {
   constexpr int KS = HD / 16;             // k-steps of the score product
   constexpr int DT = HD / 32;             // 32-dim tiles of the output
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -609,13 +717,21 @@ __global__ void __launch_bounds__(WG) k_attn_flash(const bf16* __restrict__ qh, 
   }
   if (qi < T) {
     const float inv = 1.0f / l;
-    float* orow = out + (size_t)qi * nq + h * HD;
+    const size_t orow = (size_t)qi * nq + h * HD;
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const float4 v = make_float4(O[t][4 * rr] * inv, O[t][4 * rr + 1] * inv, O[t][4 * rr + 2] * inv, O[t][4 * rr + 3] * inv);
-        *reinterpret_cast<float4*>(orow + 32 * t + 8 * rr + 4 * gl) = v;
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v = O[t][4 * rr + e] * inv;
+          hi[e] = f2bf(v);
+          lo[e] = f2bf(v - bf2f(hi[e]));
+        }
+        const size_t o = orow + 32 * t + 8 * rr + 4 * gl;
+        *reinterpret_cast<uint2*>(outh + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+        *reinterpret_cast<uint2*>(outl + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
       }
   }
 }
