@@ -40,7 +40,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="cfg3_8b", choices=["cfg3_8b", "cfg2_1b", "cfg1_tiny"])
+    ap.add_argument("--workload", default="cfg3_8b",
+                    choices=["cfg3_8b", "cfg2_1b", "cfg1_tiny", "cfg4_8b_b16", "cfg5_8b_16k"])
+    ap.add_argument("--prompt", type=int, default=0, help="override the prompt length of a batch workload")
     ap.add_argument("--headline-skip", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -57,6 +59,8 @@ def main():
 
     wl = WORKLOADS[args.workload]
     desc = CONFIGS[wl["model"]]
+    if wl["batch"] > 1:
+        return bench_batch(args, wl, desc)
     seed = wl["seed"]
     n_prompt, L = wl["prompt"], desc.n_layers
     K, W = args.steps, args.warmup
@@ -169,6 +173,87 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "setup_s": {"generate_weights": t_gen},
+    }
+    ctx.close()
+    print(json.dumps(out))
+
+
+def batch_step_bytes(desc, masks, ctx_lens):
+    """Algorithmic HBM bytes of one decode step of a batch: the weights of every layer that at
+    least one sequence keeps, once; LM head once; per sequence its embedding row, the KV of its
+    kept layers (read + append) and its logits."""
+    e = desc.bytes_per_elem
+    kvb = 2 * desc.n_kv_heads * desc.head_dim * e
+    L = desc.n_layers
+    used = sum(1 for i in range(L) if any(m[i] for m in masks))
+    by = used * (desc.layer_params * e + 2 * desc.d_model * 4) + desc.vocab * desc.d_model * e + desc.d_model * 4
+    for m, n in zip(masks, ctx_lens):
+        by += desc.d_model * e + sum(m) * kvb * (n + 2) + desc.vocab * 4
+    return by, used
+
+
+def bench_batch(args, wl, desc):
+    """Decode of a batch with one skip mask per sequence (the batch-16 mixed-mask and the batch-4
+    long-context workloads): aggregate tokens/s over all sequences."""
+    import numpy as np
+    import torch
+    import paper_2410_12513_amd as P
+    from synth import make_prompt, make_router, make_skip_mask, make_weights
+
+    seed, B, L = wl["seed"], wl["batch"], desc.n_layers
+    K, W = min(args.steps, wl["decode"]), args.warmup
+    rng = np.random.Generator(np.random.PCG64(seed))
+    if isinstance(wl["prompt"], tuple):
+        lens = [int(x) for x in rng.integers(wl["prompt"][0], wl["prompt"][1] + 1, size=B)]
+    else:
+        lens = [int(args.prompt or wl["prompt"])] * B
+    if isinstance(wl["skip"], str):                                  # "U[0,0.5]": one skip fraction per sequence
+        skips = [min(L - 2, int(round(float(f) * L))) for f in rng.uniform(0.0, 0.5, size=B)]
+    else:
+        skips = [int(wl["skip"][0])] * B
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    weights = make_weights(desc, seed, device="cuda")
+    router = make_router(desc, seed, device="cuda")
+    ctx = P.FirstContext(desc, weights, router, max_batch=B, max_seq_len=max(lens) + W + K + 16, stream=stream)
+    ctx.set_option(6, 0 if args.per_op else 1)                      # shared pass over the weights, or error
+    prompts = [make_prompt(desc.vocab, n, seed * 100 + b).cuda() for b, n in enumerate(lens)]
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    logits = torch.zeros(B, desc.vocab, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    ctx.prefill_route(torch.cat(prompts).to(torch.int32), lens, token=tok)
+    ev1.record(stream)
+    ev1.synchronize()
+    prefill_ms = ev0.elapsed_time(ev1)
+    masks = [make_skip_mask(L, k, seed * 100 + b).tolist() for b, k in enumerate(skips)]
+    for b, m in enumerate(masks):
+        ctx.set_mask(b, m)
+    for _ in range(W):
+        ctx.decode_step(tok, logits, tok)
+    ctx.sync()
+    ev0.record(stream)
+    for _ in range(K):
+        ctx.decode_step(tok, logits, tok)
+    ev1.record(stream)
+    ev1.synchronize()
+    ms = ev0.elapsed_time(ev1) / K
+    by, used = batch_step_bytes(desc, masks, [n + W + K // 2 for n in lens])
+    achieved = by / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "decode tokens/sec, batch with per-sequence skip masks (8B-class); % of HBM roofline",
+        "value": B * 1000.0 / ms, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if desc.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {wl['model']} Llama-style decoder, batch {B}, prompts {min(lens)}..{max(lens)} "
+                               f"tokens, skipped layers per sequence {min(skips)}..{max(skips)} of {L}",
+                   "layers_kept_by_some_sequence": used, "mean_kept_layers": sum(sum(m) for m in masks) / B,
+                   "kv_page_tokens": 16, "decode_path": "one pass per sequence" if args.per_op else "shared pass per layer"},
+        "prefill": {"tokens": sum(lens), "ms": prefill_ms},
+        "roofline": {"bound": "hbm", "kernel": "whole decode step (batched mat-vec, attention and LM-head kernels)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": by, "avg_launch_us": ms * 1e3, "launches_timed": K},
+        "cpu_baseline": None,
     }
     ctx.close()
     print(json.dumps(out))
