@@ -84,7 +84,7 @@ def main():
 
     sweep, prefill_ms = [], None
     for k in skips:
-        mask = make_skip_mask(L, k, seed).tolist()
+        mask = [0] * L if k >= L else make_skip_mask(L, k, seed).tolist()      # k = L: every layer skipped
         ev0.record(stream)
         ctx.prefill_route(prompt, [n_prompt], token=tok)          # synchronises
         ev1.record(stream)
