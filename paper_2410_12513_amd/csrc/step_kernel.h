@@ -582,15 +582,9 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
                                            float* psum, const int* staged, int& seen) {
   const int u = uni(round * SK_SWAVES + wave);
   const int valid = uni((int)(u < d.nunits));
-#ifdef SK_FAKE_CONSUME
-  {
-    unsigned t = (b[0].x ^ b[0].y ^ b[0].z ^ b[0].w) ^ (b[1].x ^ b[1].y ^ b[1].z ^ b[1].w) ^ (b[2].x ^ b[2].y ^ b[2].z ^ b[2].w) ^ (b[3].x ^ b[3].y ^ b[3].z ^ b[3].w);
-    if (valid && (threadIdx.x & 63) == 63) psum[u] = __uint_as_float(t & 0x3fffffffu) * 1e-3f;
-    return;
-  }
-#endif
+  if (!valid) return;                              // padding round: the (zero) loads are accounted for, nothing to add
   const int lane = threadIdx.x & 63, K = uni(d.K);
-  const int uu = valid ? u : 0;
+  const int uu = u;
   const int nrows = uni(d.nrows);
   const int sg = nrows <= 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nrows));
   if (staged != nullptr && sg >= seen) {
@@ -619,7 +613,7 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
     acc[2 * j] = e; acc[2 * j + 1] = o;
   }
   const float tot = wave_sum_lane63(((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7])));
-  if (valid && lane == 63) psum[u] = tot;
+  if (lane == 63) psum[u] = tot;
 }
 
 __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg, int nrows) {
