@@ -52,6 +52,9 @@ extern "C" {
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
+#define FIRST_OPT_STEP_BALANCE  8  /* persistent kernel: 1 (default) = after every step the per-XCD shares of the weight rows
+                                      follow the measured streaming times (results do not depend on the shares);
+                                      0 = even split.  Setting it resets the shares. */
 #define FIRST_OPT_PREFILL_ATTN  7  /* prompt attention.  1 (default): tiled kernel on the matrix cores when the cache is bf16
                                       and head_dim is 64 or 128, else the plain kernel; 0: always the plain fp32 kernel */
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
@@ -193,6 +196,12 @@ int first_op_gemm_nt_f32a(void *hip_stream, const float *A, const void *W, float
  * barrier passed, attention done (O phase only), input staged, weights streamed, results
  * stored, then six marks inside the attention of workgroup 0 (O phase only).  stamps HOST uint64 [capacity]; n_out HOST receives the count.  Synchronises. */
 int first_step_timing(first_ctx *ctx, uint64_t *stamps, int32_t capacity, int32_t *n_out);
+
+/* Row shares of the persistent kernel (FIRST_OPT_STEP_BALANCE): shares8 (host, 8 ints, 1024 = an even
+ * share per XCD, sum 8192).  times (host, may be null; capacity >= number of compute units): per workgroup
+ * of the last step, gate/up streaming time in 100 MHz ticks (low 24 bits) and its XCD (top byte).
+ * Synchronises the stream.  Inspection only: results never depend on the shares. */
+int first_step_shares(first_ctx *ctx, int32_t *shares8, uint32_t *times, int32_t capacity);
 
 /* Launches only the gate/up kernel of one layer (the largest kernel of a decode step,
  * Section 2 Eq. 1's phi_i: z = silu(Wg y) * (Wu y), y = RMSNorm(h)) for sequence slot seq, on

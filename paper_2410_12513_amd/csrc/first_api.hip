@@ -77,6 +77,9 @@ struct first_ctx {
   float *d_rinv = nullptr, *d_logits_all = nullptr;
   int xpitch = 0;
   int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
+  int *d_shares = nullptr;                // per-XCD row shares of the persistent kernel (1024 = equal)
+  unsigned* d_share_time = nullptr;
+  int step_balance = 1;                   // FIRST_OPT_STEP_BALANCE
   int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
@@ -127,6 +130,13 @@ int device_cus() {
 int gemv_grid(int rows, int R, int num_cu) {
   const int need = (rows + WAVES * R - 1) / (WAVES * R);
   return std::max(1, std::min(need, num_cu * 4));
+}
+
+hipError_t reset_shares(first_ctx* c) {
+  const int eq[8] = {1024, 1024, 1024, 1024, 1024, 1024, 1024, 1024};
+  hipError_t e = hipMemcpy(c->d_shares, eq, sizeof(eq), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemset(c->d_share_time, 0, (size_t)c->num_cu * sizeof(unsigned));
+  return e;
 }
 
 void release_sequences(first_ctx* c) {
@@ -292,12 +302,15 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
   P.bar = c->d_bar; P.err = c->d_err; P.two_level = c->step_two_level;
+  P.shares = c->d_shares; P.share_time = c->step_balance ? c->d_share_time : nullptr;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
   hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)sk_bar_words(c->num_cu));
   if (c->d.head_dim == 128)
     hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
   else
     hipLaunchKernelGGL(k_step<64>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  if (c->step_balance)
+    hipLaunchKernelGGL(k_rebalance, dim3(1), dim3(256), 0, c->stream, c->d_share_time, c->d_shares, c->num_cu);
 }
 
 // Does the geometry fit the persistent kernel's static work split?
@@ -309,7 +322,8 @@ bool step_kernel_fits(const first_ctx* c) {
   if (d.n_kv_heads > c->num_cu || d.d_ffn > 16384 || d.d_model > 16384 || c->nq > 16384) return false;
   const int ncu = c->num_cu;
   if ((long long)std::max({d.vocab, 2 * d.d_ffn, c->nq + 2 * c->nkv}) * (ncu + 1) >= (1LL << 31)) return false;
-  auto units = [&](long long rows, int K) { return (int)((rows + ncu - 1) / ncu + 2) * (K / SK_SEG); };
+  // (rows per workgroup: up to 15 % above an even share, see k_rebalance)
+  auto units = [&](long long rows, int K) { return (int)(((rows + ncu - 1) / ncu) * 6 / 5 + 4) * (K / SK_SEG); };
   const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), units(d.d_model, c->nq),
                               units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});
   if (worst > SK_PSUM) return false;
@@ -533,6 +547,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     A(dev_alloc(c, &c->d_zh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_zl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_rinv, BATCH_SLOTS)); A(dev_alloc(c, &c->d_logits_all, (size_t)B * d.vocab));
   }
+  A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
   A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
   if (rc == FIRST_OK) {
@@ -543,6 +558,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
     if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
+    if (e == hipSuccess) e = reset_shares(c);
     if (e == hipSuccess) e = hipMemset(c->d_bar, 0, (size_t)sk_bar_words(c->num_cu) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
@@ -753,6 +769,12 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->step_timing = value ? 1 : 0;
       drop_graphs(c);
       return FIRST_OK;
+    case FIRST_OPT_STEP_BALANCE:
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      c->step_balance = value ? 1 : 0;
+      HIPCHK(c, reset_shares(c));
+      drop_graphs(c);
+      return FIRST_OK;
     case FIRST_OPT_PREFILL_ATTN:
       c->prefill_flash = value ? 1 : 0; return FIRST_OK;
     case FIRST_OPT_BATCH_PATH:
@@ -889,6 +911,18 @@ int first_step_timing(first_ctx* c, uint64_t* stamps, int32_t capacity, int32_t*
                         hipMemcpyDeviceToHost));
   }
   *n_out = n;
+  return FIRST_OK;
+}
+
+int first_step_shares(first_ctx* c, int32_t* shares8, uint32_t* times, int32_t capacity) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!shares8) return fail(c, FIRST_ERR_ARG, "first_step_shares: null output");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(shares8, c->d_shares, 8 * sizeof(int32_t), hipMemcpyDeviceToHost));
+  if (times) {
+    if (capacity < c->num_cu) return fail(c, FIRST_ERR_ARG, "first_step_shares: buffer too small");
+    HIPCHK(c, hipMemcpy(times, c->d_share_time, (size_t)c->num_cu * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  }
   return FIRST_OK;
 }
 

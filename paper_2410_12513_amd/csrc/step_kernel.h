@@ -135,6 +135,8 @@ struct StepParams {
   int L;
   unsigned* bar;               // grid barrier words (sk_bar_words(grid size) of them), zero at launch
   int two_level;               // 1: per-XCD arrival counters + one flag per XCD; 0: every workgroup polls every flag
+  const int* shares;           // [8] per-XCD share of the rows (1024 = equal), or null: even split
+  unsigned* share_time;        // [grid] out: this workgroup's gate/up streaming time (100 MHz ticks), its XCD in the top byte
   int* err;                    // set to 1 if a barrier wait gives up
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
@@ -466,13 +468,18 @@ struct SegDesc {
   bf16* kv;                     // KV pool of the layer (attention precedes SEG_O)
 };
 
-__device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, int cu, int ncu, int pair) {
+// Rows of a phase are dealt out in proportion to per-XCD shares (1024 = an equal share): w0 and
+// w1 are the cumulative shares before this workgroup and before the next one, out of
+// 1024 * ncu.  Equal shares give the even split n * cu / ncu.
+struct SkShare { int w0, w1, ncu; };
+
+__device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, const SkShare& sh, int pair) {
   const int n = N / pair;
   d.K = K;
-  // 32-bit arithmetic (rows * workgroups < 2^31 is checked on the host): 64-bit division is
-  // emulated and costs dozens of registers
-  d.row0 = (int)((unsigned)(n * cu) / (unsigned)ncu) * pair;
-  d.nrows = (int)((unsigned)(n * (cu + 1)) / (unsigned)ncu) * pair - d.row0;
+  // 64-bit product, 32-bit division (n * w >> 10 < 2^31 is checked on the host): 64-bit
+  // division is emulated and costs dozens of registers
+  d.row0 = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w0) >> 10) / (unsigned)sh.ncu) * pair;
+  d.nrows = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w1) >> 10) / (unsigned)sh.ncu) * pair - d.row0;
   d.nseg = K / SK_SEG;
   d.inv_nrows = d.nrows <= 1 ? 0u : (unsigned)((0x100000000ull + d.nrows - 1) / d.nrows);   // (nrows <= 1 handled at use)
   d.nunits = d.nrows * d.nseg;
@@ -487,7 +494,7 @@ __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   return d;
 }
 
-__device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
+__device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh) {
   const DecParams& p = P.d;
   const int nq = p.Hq * p.hd, nkv = p.Hkv * p.hd;
   SegDesc d{};
@@ -495,7 +502,7 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
   if (s > 4 * nk) return d;
   if (s == 4 * nk) {
     d.kind = SEG_HEAD; d.m0 = reinterpret_cast<const bf16*>(p.lm_head); d.n0 = p.V; d.gain = p.g_final;
-    seg_split(d, p.V, p.D, cu, ncu, 1);
+    seg_split(d, p.V, p.D, sh, 1);
     return d;
   }
   const LayerDev lw = load_layer(P.layers, uni(kept[s >> 2]));
@@ -504,19 +511,19 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
   switch (d.kind) {
     case SEG_QKV:
       d.m0 = lw.wq; d.m1 = lw.wk; d.m2 = lw.wv; d.n0 = nq; d.n1 = nkv; d.gain = lw.g_attn;
-      seg_split(d, nq + 2 * nkv, p.D, cu, ncu, 1);
+      seg_split(d, nq + 2 * nkv, p.D, sh, 1);
       break;
     case SEG_O:
       d.m0 = lw.wo; d.n0 = p.D;
-      seg_split(d, p.D, nq, cu, ncu, 1);
+      seg_split(d, p.D, nq, sh, 1);
       break;
     case SEG_GU:
       d.m0 = lw.wg; d.m1 = lw.wu; d.inter = 1; d.gain = lw.g_mlp;
-      seg_split(d, 2 * p.F, p.D, cu, ncu, 2);
+      seg_split(d, 2 * p.F, p.D, sh, 2);
       break;
     default:
       d.m0 = lw.wd; d.n0 = p.D;
-      seg_split(d, p.D, p.F, cu, ncu, 1);
+      seg_split(d, p.D, p.F, sh, 1);
       break;
   }
   return d;
@@ -524,8 +531,8 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
 
 // Descriptor of segment s for this workgroup, every field in scalar registers.  Recomputed
 // where needed rather than carried through the segment loop.
-__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, int cu, int ncu) {
-  return seg_uniform(seg_desc_raw(P, s, nk, kept, cu, ncu));
+__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh) {
+  return seg_uniform(seg_desc_raw(P, s, nk, kept, sh));
 }
 
 // Address of row r of a segment.  All inputs are wave-uniform, so the cases are scalar
@@ -903,6 +910,20 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const int b = p.b, D = p.D, F = p.F, nq = p.Hq * HD, nkv = p.Hkv * HD;
   const SkLds S = sk_carve(smem_f, D, nq, F, p.G, HD);
   unsigned epoch = 0;
+  // cumulative row shares of this workgroup: workgroups are dealt to the XCDs round-robin, so
+  // workgroup c sits on XCD c % 8 (checked by the kernel that updates the shares)
+  SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
+  if (P.shares != nullptr && (ncu & 7) == 0) {
+    int pre = 0, pre1 = 0, tot = 0;
+    for (int j = 0; j < 8; ++j) {
+      const int sj = uni(P.shares[j]);
+      if (j < (cu & 7)) pre += sj;
+      if (j <= (cu & 7)) pre1 += sj;
+      tot += sj;
+    }
+    if (tot == 8192) { share.w0 = (cu >> 3) * 8192 + pre; share.w1 = (cu >> 3) * 8192 + pre1; }
+  }
+  share.w0 = uni(share.w0); share.w1 = uni(share.w1);
   SkBar bar;
   if (service) sk_bar_init(bar, P.bar, P.err, ncu, P.two_level);
   float* h = p.h + (size_t)b * D;
@@ -960,8 +981,9 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   // the streaming waves no staging registers) with the same sequence of workgroup barriers.
   if (service) {
     lds_barrier();                                 // every wave's stores of the embedding are complete
+    unsigned gu_ticks = 0;
     for (int s = 0; s < nsegs; ++s) {
-      const SegDesc cur = seg_desc(P, s, nk, kept, cu, ncu);
+      const SegDesc cur = seg_desc(P, s, nk, kept, share);
       SK_STAMP(0);
       SkGains gains;
       const bool fast_norm = cur.gain != nullptr && D <= 4096;
@@ -993,6 +1015,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // fetched while the weights stream
       float h_prev = 0.f;
       if ((cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
+      const bool timed = cur.kind == SEG_GU && P.share_time != nullptr;   // the longest phase measures this XCD's stream rate
+      const unsigned long long t_stream = timed ? wall_clock64() : 0ull;
       if (cur.kind == SEG_DN) {
         for (int c = 1; c < cur.nseg; c += 2) {
           const int c1 = min(c + 2, cur.nseg);
@@ -1001,6 +1025,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
       }
       lds_barrier();                               // partial sums complete
+      if (timed) gu_ticks += (unsigned)(wall_clock64() - t_stream);
       SK_STAMP(4);
       // results of the segment
       if (cur.kind == SEG_QKV) {
@@ -1038,6 +1063,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       vm_wait_all();                               // the stores are complete before this workgroup arrives
       SK_STAMP(5);
     }
+    if (P.share_time != nullptr && lane == 0) P.share_time[cu] = min(gu_ticks, 0xffffffu) | (bar.x << 24);
     // greedy token: workgroup 0 reduces the per-workgroup candidates
     const int ok = grid_sync(bar, ++epoch, cu, ncu);
     if (ok && cu == 0) {
@@ -1057,14 +1083,14 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   } else {
     uint4 buf[SK_PD][4];
     {
-      const SegDesc first = seg_desc(P, 0, nk, kept, cu, ncu);
+      const SegDesc first = seg_desc(P, 0, nk, kept, share);
 #pragma unroll
       for (int j = 0; j < SK_PD; ++j) sk_issue(first, j, true, wave, buf[j]);
     }
     lds_barrier();
     for (int s = 0; s < nsegs; ++s) {
-      const SegDesc cur = seg_desc(P, s, nk, kept, cu, ncu);
-      const SegDesc nxt = seg_desc(P, s + 1, nk, kept, cu, ncu);
+      const SegDesc cur = seg_desc(P, s, nk, kept, share);
+      const SegDesc nxt = seg_desc(P, s + 1, nk, kept, share);
       const float* xsrc = cur.kind == SEG_DN ? S.zs : S.xs;
       if (cur.kind == SEG_O) {
         lds_barrier();
@@ -1108,6 +1134,47 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
 #undef SK_GRID_SYNC
 #undef SK_GRID_SYNC_TRACED
 #undef SK_STAMP
+}
+
+// Runs after k_step (one workgroup): turns the gate/up streaming times of the workgroups into
+// per-XCD row shares for the next launches.  An XCD that streams slower (its workgroups took
+// longer for their share) gets fewer rows, so that all workgroups reach the phase barriers
+// together.  Shares never change results: every row is computed the same way whoever owns it.
+// Nothing changes unless every workgroup c reported XCD c % 8 and a time.
+__global__ void __launch_bounds__(256) k_rebalance(const unsigned* __restrict__ share_time, int* __restrict__ shares, int ncu) {
+  __shared__ unsigned long long tsum[8];
+  __shared__ unsigned cnt[8];
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  if (tid < 8) { tsum[tid] = 0ull; cnt[tid] = 0u; }
+  if (tid == 0) bad = (ncu & 7) != 0 || ncu > 2048;
+  __syncthreads();
+  for (int c = tid; c < ncu; c += 256) {
+    const unsigned v = share_time[c], x = v >> 24, t = v & 0xffffffu;
+    if (x != (unsigned)(c & 7) || t == 0u || t == 0xffffffu) atomicOr(&bad, 1);
+    else { atomicAdd(&tsum[x], (unsigned long long)t); atomicAdd(&cnt[x], 1u); }
+  }
+  __syncthreads();
+  if (tid != 0 || bad) return;
+  float rate[8], tot = 0.f;
+  int cur[8], csum = 0;
+  for (int x = 0; x < 8; ++x) { cur[x] = shares[x]; csum += cur[x]; }
+  if (csum != 8192) { for (int x = 0; x < 8; ++x) cur[x] = 1024; }
+  for (int x = 0; x < 8; ++x) {
+    if (cnt[x] == 0u) return;
+    rate[x] = (float)cur[x] / ((float)tsum[x] / (float)cnt[x]);     // rows per tick this XCD sustained
+    tot += rate[x];
+  }
+  int nw[8], sum = 0, big = 0;
+  for (int x = 0; x < 8; ++x) {
+    const float target = 8192.f * rate[x] / tot;
+    int v = (int)(0.5f * (float)cur[x] + 0.5f * target + 0.5f);      // damped
+    v = max(870, min(1178, v));                                      // within 15 % of an equal share
+    nw[x] = v; sum += v;
+    if (nw[x] > nw[big]) big = x;
+  }
+  nw[big] += 8192 - sum;                                             // shares add up exactly
+  for (int x = 0; x < 8; ++x) shares[x] = nw[x];
 }
 
 }  // namespace first

@@ -14,6 +14,7 @@ torch.set_grad_enabled(False)
 
 OPT_DECODE_PATH = 3
 OPT_STEP_BARRIER = 5
+OPT_STEP_BALANCE = 8
 
 
 @pytest.mark.parametrize("model,n_prompt", [("step_hd128", 150), ("step_hd64", 70), ("step_g2", 200),
@@ -59,12 +60,14 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
     mask = make_skip_mask(desc.n_layers, 1 if desc.n_layers > 2 else 0, 43).tolist()
     inputs = [[int(t)] for t in make_prompt(desc.vocab, 24, 44)]
     runs = {}
-    for name, path, graph, barrier in (("ops", 0, 1, 1), ("step", 1, 1, 1), ("step_again", 1, 1, 1), ("step_eager", 1, 0, 1),
-                                       ("step_flat_barrier", 1, 1, 0)):
+    for name, path, graph, barrier, balance in (("ops", 0, 1, 1, 1), ("step", 1, 1, 1, 1), ("step_again", 1, 1, 1, 1),
+                                                ("step_eager", 1, 0, 1, 1), ("step_flat_barrier", 1, 1, 0, 1),
+                                                ("step_even_split", 1, 1, 1, 0)):
         desc, w, router, ctx = build(model, 43, max_seq_len=200)
         ctx.set_option(OPT_DECODE_PATH, path)
         ctx.set_option(1, graph)
         ctx.set_option(OPT_STEP_BARRIER, barrier)
+        ctx.set_option(OPT_STEP_BALANCE, balance)
         _prefill(ctx, desc, [prompt])
         ctx.set_mask(0, mask)
         lg, tk = _decode(ctx, desc, inputs)
@@ -73,6 +76,8 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
         ctx.close()
     assert torch.equal(runs["step"][0], runs["step_again"][0]) and torch.equal(runs["step"][1], runs["step_again"][1])
     assert torch.equal(runs["step"][0], runs["step_eager"][0])
+    # who owns which weight rows (the shares move with the measured streaming times) changes no arithmetic
+    assert torch.equal(runs["step"][0], runs["step_even_split"][0]) and torch.equal(runs["step"][1], runs["step_even_split"][1])
     # the kind of grid barrier changes no arithmetic
     assert torch.equal(runs["step"][0], runs["step_flat_barrier"][0]) and torch.equal(runs["step"][1], runs["step_flat_barrier"][1])
     # same arithmetic up to fp32 summation order
