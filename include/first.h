@@ -52,9 +52,10 @@ extern "C" {
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
-#define FIRST_OPT_STEP_BALANCE  8  /* persistent kernel: 1 (default) = after every step the per-XCD shares of the weight rows
-                                      follow the measured streaming times (results do not depend on the shares);
-                                      0 = even split.  Setting it resets the shares. */
+#define FIRST_OPT_STEP_BALANCE  8  /* persistent kernel: 1 = after every step the per-XCD shares of the weight rows follow
+                                      the measured streaming times (results do not depend on the shares); 0 (default) =
+                                      even split.  Setting it resets the shares.  Measured: evens the per-XCD arrival
+                                      times at the barriers, no gain in step time (the spread inside an XCD remains). */
 #define FIRST_OPT_PREFILL_ATTN  7  /* prompt attention.  1 (default): tiled kernel on the matrix cores when the cache is bf16
                                       and head_dim is 64 or 128, else the plain kernel; 0: always the plain fp32 kernel */
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that

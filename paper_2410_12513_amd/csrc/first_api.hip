@@ -79,7 +79,7 @@ struct first_ctx {
   int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
   int *d_shares = nullptr;                // per-XCD row shares of the persistent kernel (1024 = equal)
   unsigned* d_share_time = nullptr;
-  int step_balance = 1;                   // FIRST_OPT_STEP_BALANCE
+  int step_balance = 0;                   // FIRST_OPT_STEP_BALANCE
   int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
