@@ -25,7 +25,7 @@ def _masks(L, B, seed):
     return out
 
 
-def _run(model, lens, n_steps, seed, page=16, splits=0):
+def _run(model, lens, n_steps, seed, page=16, splits=0, masks=None):
     desc = CONFIGS[model]
     B = len(lens)
     prompts = [make_prompt(desc.vocab, n, seed + 10 * b) for b, n in enumerate(lens)]
@@ -33,7 +33,7 @@ def _run(model, lens, n_steps, seed, page=16, splits=0):
     ctx.set_option(OPT_BATCH_PATH, 1)
     ctx.set_option(2, splits)
     _prefill(ctx, desc, prompts)
-    masks = _masks(desc.n_layers, B, seed)
+    masks = masks or _masks(desc.n_layers, B, seed)
     for b, m in enumerate(masks):
         ctx.set_mask(b, m)
     states, refs = [], []
@@ -84,6 +84,13 @@ def test_few_attention_splits_walk_several_key_tiles_per_wave():
 
 def test_other_page_size_uses_the_generic_attention_kernel():
     _run("mini_bf16", [70, 130, 45], 4, 68, page=32)
+
+
+def test_degenerate_masks_in_one_batch():
+    # one sequence skips every layer, one keeps every layer, one keeps a layer nobody else keeps
+    # alone, and layer 2 is kept by nobody but the all-keep sequence
+    masks = [[0, 0, 0, 0], [1, 1, 1, 1], [0, 1, 0, 0], [1, 0, 0, 1]]
+    _run("mini_bf16", [16, 31, 48, 17], 5, 69, masks=masks)      # prompts end exactly at / next to page boundaries
 
 
 def test_more_sequences_than_slots_run_in_groups():
