@@ -52,6 +52,10 @@ extern "C" {
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
+#define FIRST_OPT_BATCH_TILED   9  /* batched decode: 1 (default when max_batch > 1 and device memory allows) = the mat-vecs
+                                      read copies of the matrices in MFMA tile order, made at first_create (as much memory
+                                      again as the weights; the caller's matrices must not change afterwards); 0 = they
+                                      read the caller's row-major matrices */
 #define FIRST_OPT_STEP_BALANCE  8  /* persistent kernel: 1 = after every step the per-XCD shares of the weight rows follow
                                       the measured streaming times (results do not depend on the shares); 0 (default) =
                                       even split.  Setting it resets the shares.  Measured: evens the per-XCD arrival

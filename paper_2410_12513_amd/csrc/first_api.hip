@@ -24,6 +24,7 @@ thread_local std::string g_create_error;
 struct LayerPtrs {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
   const float *g_attn, *g_mlp;
+  bf16 *t_qkv = nullptr, *t_o = nullptr, *t_g = nullptr, *t_u = nullptr, *t_d = nullptr;   // tile-order copies (batched decode)
 };
 
 }  // namespace
@@ -77,6 +78,8 @@ struct first_ctx {
   float *d_rinv = nullptr, *d_logits_all = nullptr;
   int xpitch = 0;
   int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
+  bf16* t_head = nullptr;                 // tile-order copy of the LM head
+  bool tiled = false;                     // tile-order copies of all matrices exist
   int *d_shares = nullptr;                // per-XCD row shares of the persistent kernel (1024 = equal)
   unsigned* d_share_time = nullptr;
   int step_balance = 0;                   // FIRST_OPT_STEP_BALANCE
@@ -218,15 +221,18 @@ void enqueue_decode_ops(first_ctx* c, const int* tokens, float* logits, int* tok
   }
 }
 
-// Workgroups and K-slices of a batched mat-vec over N rows: enough workgroups to fill the
-// chip; small N splits the contraction over the 8 waves of a workgroup instead.
-void bgemv_shape(int N, int num_cu, int* grid, int* kslices) {
-  const int tiles = (N + 15) / 16;
+// Shape of a batched mat-vec over N rows: RT row tiles per wave (they share the activation
+// operands), K-slices over the 8 waves of a workgroup when N alone does not fill the chip.
+template <int MODE, int RT>
+void launch_bgemv_rt(first_ctx* c, const BatchParams& P, int N, int K) {
+  const bool tiled = c->tiled;
+  const int groups = ((N + 15) / 16 + RT - 1) / RT;
   int ks = 1;
-  while (ks < BG_WAVES && tiles * ks < 16 * num_cu) ks *= 2;
-  *kslices = ks;
-  const int tiles_per_wg = BG_WAVES / ks;
-  *grid = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+  while (ks < BG_WAVES && groups * ks < 12 * c->num_cu) ks *= 2;
+  const int groups_per_wg = BG_WAVES / ks;
+  const int grid = (groups + groups_per_wg - 1) / groups_per_wg;
+  if (tiled) hipLaunchKernelGGL((k_bgemv<MODE, RT, true>), dim3(grid), dim3(BG_THREADS), 0, c->stream, P, N, K, ks);
+  else hipLaunchKernelGGL((k_bgemv<MODE, RT, false>), dim3(grid), dim3(BG_THREADS), 0, c->stream, P, N, K, ks);
 }
 
 bool d_batch_fits(const first_ctx* c) {
@@ -235,9 +241,49 @@ bool d_batch_fits(const first_ctx* c) {
 
 template <int MODE>
 void launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
-  int grid, ks;
-  bgemv_shape(N, c->num_cu, &grid, &ks);
-  hipLaunchKernelGGL(k_bgemv<MODE>, dim3(grid), dim3(BG_THREADS), 0, c->stream, P, N, K, ks);
+  // two tiles per wave once that still leaves every SIMD several waves
+  if ((N + 15) / 16 >= 16 * c->num_cu / 8) launch_bgemv_rt<MODE, 2>(c, P, N, K);
+  else launch_bgemv_rt<MODE, 1>(c, P, N, K);
+}
+
+// Tile-order copies of every matrix for the batched mat-vecs (as much again as the weights),
+// made only when at least that much device memory plus a 4 GiB margin is free; without them
+// the batched path reads the caller's row-major matrices.
+hipError_t make_tiled_copies(first_ctx* c) {
+  const first_model_desc& d = c->d;
+  auto tiled_elems = [](int N, int K) { return (size_t)((N + 15) / 16) * ((K + 31) / 32) * 512; };
+  const int nqkv = c->nq + 2 * c->nkv;
+  const size_t per_layer = tiled_elems(nqkv, d.d_model) + tiled_elems(d.d_model, c->nq) + 2 * tiled_elems(d.d_ffn, d.d_model) +
+                           tiled_elems(d.d_model, d.d_ffn);
+  const size_t total = (per_layer * d.n_layers + tiled_elems(d.vocab, d.d_model)) * sizeof(bf16);
+  size_t free_b = 0, total_b = 0;
+  if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < total + ((size_t)4 << 30)) return hipSuccess;
+  auto conv = [&](const void* src, bf16* dst, int N, int K) {
+    const size_t items = tiled_elems(N, K) / 8;
+    hipLaunchKernelGGL(k_tile_weights, dim3((unsigned)std::min<size_t>((items + WG - 1) / WG, 65535)), dim3(WG), 0, c->stream,
+                       reinterpret_cast<const bf16*>(src), dst, N, K);
+  };
+  for (int i = 0; i < d.n_layers; ++i) {
+    LayerPtrs& l = c->layers[i];
+    if (dev_alloc(c, &l.t_qkv, tiled_elems(nqkv, d.d_model)) || dev_alloc(c, &l.t_o, tiled_elems(d.d_model, c->nq)) ||
+        dev_alloc(c, &l.t_g, tiled_elems(d.d_ffn, d.d_model)) || dev_alloc(c, &l.t_u, tiled_elems(d.d_ffn, d.d_model)) ||
+        dev_alloc(c, &l.t_d, tiled_elems(d.d_model, d.d_ffn)))
+      return hipErrorOutOfMemory;
+    // q, k and v stacked: nq and nkv are multiples of 64, so no tile straddles two matrices
+    conv(l.wq, l.t_qkv, c->nq, d.d_model);
+    conv(l.wk, l.t_qkv + tiled_elems(c->nq, d.d_model), c->nkv, d.d_model);
+    conv(l.wv, l.t_qkv + tiled_elems(c->nq + c->nkv, d.d_model), c->nkv, d.d_model);
+    conv(l.wo, l.t_o, d.d_model, c->nq);
+    conv(l.wg, l.t_g, d.d_ffn, d.d_model);
+    conv(l.wu, l.t_u, d.d_ffn, d.d_model);
+    conv(l.wd, l.t_d, d.d_model, d.d_ffn);
+  }
+  if (dev_alloc(c, &c->t_head, tiled_elems(d.vocab, d.d_model))) return hipErrorOutOfMemory;
+  conv(c->lm_head, c->t_head, d.vocab, d.d_model);
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  c->tiled = e == hipSuccess;
+  return e;
 }
 
 // One decode token for every live sequence (bf16 models), layer by layer: the sequences that
@@ -258,6 +304,7 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
     P.d.tokens = tokens; P.d.token_out = token_out;
     P.xh = c->d_xh; P.xl = c->d_xl; P.zh = c->d_zh; P.zl = c->d_zl; P.rinv = c->d_rinv; P.xpitch = c->xpitch;
     P.logits_all = logits ? logits : c->d_logits_all;
+    P.t_head = c->t_head;
     SeqList all{};
     for (int b = b0; b < std::min(c->B, b0 + BATCH_SLOTS); ++b) all.id[all.n++] = b;
     P.seqs = all;
@@ -273,6 +320,7 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       if (keep.n == 0) continue;                   // skipped by every sequence: no launch, no bytes
       P.seqs = keep;
       set_layer(c, P.d, i);
+      { const LayerPtrs& l = c->layers[i]; P.t_qkv = l.t_qkv; P.t_o = l.t_o; P.t_g = l.t_g; P.t_u = l.t_u; P.t_d = l.t_d; }
       xsplit(0, d.d_model, P.d.g_attn);
       launch_bgemv<BG_QKV>(c, P, nqkv, d.d_model);
       if (tiles_attn && d.head_dim == 128)
@@ -547,6 +595,10 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     A(dev_alloc(c, &c->d_zh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_zl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_rinv, BATCH_SLOTS)); A(dev_alloc(c, &c->d_logits_all, (size_t)B * d.vocab));
   }
+  if (B > 1 && rc == FIRST_OK) {
+    (void)hipMemset(c->d_xh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_xl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
+    (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
+  }
   A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
   A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
@@ -581,6 +633,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<64>, SK_THREADS, c->step_lds);
       if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
     }
+    if (e == hipSuccess && B > 1 && d.dtype == FIRST_DTYPE_BF16 && d_batch_fits(c)) e = make_tiled_copies(c);
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
     if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
     // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
@@ -767,6 +820,10 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->decode_path = value; return FIRST_OK;
     case FIRST_OPT_STEP_TIMING:
       c->step_timing = value ? 1 : 0;
+      drop_graphs(c);
+      return FIRST_OK;
+    case FIRST_OPT_BATCH_TILED:
+      c->tiled = value != 0 && c->t_head != nullptr;
       drop_graphs(c);
       return FIRST_OK;
     case FIRST_OPT_STEP_BALANCE:

@@ -103,9 +103,10 @@ def test_shared_pass_agrees_with_one_pass_per_sequence():
     masks = _masks(desc.n_layers, 5, 71)
     steps = [[3 + s, 40 + s, 900 + s, 11 + s, 1500 + s] for s in range(8)]
     outs = {}
-    for path in (0, 1):
+    for path in (0, 1, 2):
         desc, w, router, ctx = build("mini_bf16", 71, max_batch=5, max_seq_len=128)
-        ctx.set_option(OPT_BATCH_PATH, path)
+        ctx.set_option(OPT_BATCH_PATH, min(path, 1))
+        ctx.set_option(9, 0 if path == 2 else 1)      # 2: shared pass over the caller's row-major matrices
         _prefill(ctx, desc, prompts)
         for b, m in enumerate(masks):
             ctx.set_mask(b, m)
@@ -113,6 +114,8 @@ def test_shared_pass_agrees_with_one_pass_per_sequence():
         ctx.close()
     # same arithmetic up to the 16-bit split of the activations and the order of the sums
     assert float((outs[0][0] - outs[1][0]).abs().max()) <= 3e-3
+    # tile-order copies or row-major matrices: the same products in the same order
+    assert torch.equal(outs[1][0], outs[2][0]) and torch.equal(outs[1][1], outs[2][1])
 
 
 def test_shared_pass_is_refused_for_fp32_models():
