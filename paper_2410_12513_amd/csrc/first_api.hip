@@ -294,8 +294,8 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
   const int nqkv = c->nq + 2 * c->nkv;
   // attention on register-resident key tiles when the geometry allows, one 64-key tile per
   // worker wave group and split where the longest sequence permits
-  const bool tiles_attn = (d.head_dim == 64 || d.head_dim == 128) && c->G <= SK_SWAVES && d.kv_page_tokens == 16;
-  const int nkg = std::max(1, SK_SWAVES / c->G);
+  const bool tiles_attn = (d.head_dim == 64 || d.head_dim == 128) && c->G <= SK_WAVES && d.kv_page_tokens == 16;
+  const int nkg = std::max(1, SK_WAVES / c->G);
   const int nsplit = std::max(1, std::min(S_MAX, (2 * S + nkg - 1) / nkg));
   const size_t attn_tiles_lds = sk_lds_floats(0, 0, 0, c->G, d.head_dim) * sizeof(float);
   for (int b0 = 0; b0 < c->B; b0 += BATCH_SLOTS) {
@@ -324,9 +324,9 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       xsplit(0, d.d_model, P.d.g_attn);
       launch_bgemv<BG_QKV>(c, P, nqkv, d.d_model);
       if (tiles_attn && d.head_dim == 128)
-        hipLaunchKernelGGL(k_attn_tiles_b<128>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(SK_THREADS), attn_tiles_lds, c->stream, P);
+        hipLaunchKernelGGL(k_attn_tiles_b<128>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
       else if (tiles_attn)
-        hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(SK_THREADS), attn_tiles_lds, c->stream, P);
+        hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
       else
         hipLaunchKernelGGL(k_attn_b, dim3(S, d.n_kv_heads, keep.n), dim3(WG), attn_lds<bf16>(c), c->stream, P);
       xsplit(1, c->nq, nullptr);

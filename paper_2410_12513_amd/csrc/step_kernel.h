@@ -632,7 +632,9 @@ __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg,
 // ---------------------------------------------------------------------------------------
 // Attention of workgroup (KV head g, split s): the waves = G query heads x (SK_WAVES/G) key groups,
 // lane = key for the scores, lane = (key subgroup, 8-dim chunk) for the weighted values.
-template <int HD>
+// NW = number of worker waves of the workgroup (the persistent kernel's streaming waves; the
+// stand-alone attention kernel of the batched path runs a full set of SK_WAVES workers).
+template <int HD, int NW = SK_SWAVES>
 __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
                                              unsigned long long* stamps) {
   const DecParams& p = P.d;
@@ -643,7 +645,7 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
   const int b = p.b, G = p.G, Pg = p.P;
   const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
   // workers: the first G * nkg streaming waves = G query heads x nkg key groups
-  const int nkg = SK_SWAVES / G;
+  const int nkg = NW / G;
   const bool worker = wave < G * nkg;
   const int hq = wave % G, kg = worker ? wave / G : nkg;       // kg == nkg: no tiles, no results
   const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
