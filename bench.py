@@ -226,7 +226,9 @@ def bench_batch(args, wl, desc):
     ev1.record(stream)
     ev1.synchronize()
     prefill_ms = ev0.elapsed_time(ev1)
-    masks = [make_skip_mask(L, k, seed * 100 + b).tolist() for b, k in enumerate(skips)]
+    # per-sequence draws for the mixed-mask workload; one common set of skipped layers otherwise
+    mixed = isinstance(wl["skip"], str)
+    masks = [make_skip_mask(L, k, seed * 100 + (b if mixed else 0)).tolist() for b, k in enumerate(skips)]
     for b, m in enumerate(masks):
         ctx.set_mask(b, m)
     for _ in range(W):

@@ -168,6 +168,11 @@ int first_kv_read(first_ctx *ctx, int32_t seq, int32_t layer, int32_t pos0, int3
 int first_kv_write(first_ctx *ctx, int32_t seq, int32_t layer, int32_t pos0, int32_t n,
                    const float *k_in, const float *v_in);
 
+/* Test tap: declares that sequence `seq` holds `len` tokens (1 <= len < max_seq_len), handing it the
+ * pages that length needs.  The KV of positions the library never computed is whatever
+ * first_kv_write put there (long-context checks on directly written KV).  Does not touch masks. */
+int first_set_seq_len(first_ctx *ctx, int32_t seq, int32_t len);
+
 /* Residual stream after the last decode step (before the final norm).  DEV fp32 [B, D]. */
 int first_get_hidden(first_ctx *ctx, float *hidden_out);
 

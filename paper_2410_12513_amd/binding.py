@@ -15,7 +15,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares"]
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len"]
 
 
 class FirstError(RuntimeError):
@@ -200,6 +200,9 @@ class FirstContext:
         _check_dev(v, torch.float32, "v", n * self.desc.n_kv_heads * self.desc.head_dim)
         self._chk(self.lib.first_kv_write(self.h, C.c_int32(seq), C.c_int32(layer), C.c_int32(pos0), C.c_int32(n),
                                           _ptr(k), _ptr(v)))
+
+    def set_seq_len(self, seq: int, length: int) -> None:
+        self._chk(self.lib.first_set_seq_len(self.h, C.c_int32(seq), C.c_int32(length)))
 
     def get_hidden(self) -> torch.Tensor:
         out = torch.empty((self.batch(), self.desc.d_model), dtype=torch.float32, device="cuda")

@@ -903,6 +903,24 @@ int first_kv_write(first_ctx* c, int32_t seq, int32_t layer, int32_t pos0, int32
   return kv_tap(c, seq, layer, pos0, n, const_cast<float*>(k_in), const_cast<float*>(v_in), true);
 }
 
+int first_set_seq_len(first_ctx* c, int32_t seq, int32_t len) {
+  if (!c) return FIRST_ERR_ARG;
+  if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_set_seq_len: no such live sequence");
+  if (len < 1 || len + 1 > c->d.max_seq_len) return fail(c, FIRST_ERR_CAPACITY, "first_set_seq_len: length out of range");
+  const int P = c->d.kv_page_tokens;
+  while (c->seq_npages[seq] * P < len) {
+    const int slot = alloc_page(c, seq);
+    if (slot < 0) return fail(c, FIRST_ERR_CAPACITY, "first_set_seq_len: out of KV pages");
+    hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, c->stream, c->d_page_table + (size_t)seq * c->max_pages + slot,
+                       c->h_page_table[(size_t)seq * c->max_pages + slot]);
+  }
+  hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, c->stream, c->d_len + seq, len);
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->hlen[seq] = len;
+  return FIRST_OK;
+}
+
 int first_get_hidden(first_ctx* c, float* hidden_out) {
   if (!c) return FIRST_ERR_ARG;
   if (!hidden_out) return fail(c, FIRST_ERR_ARG, "first_get_hidden: null output");
