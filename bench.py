@@ -43,6 +43,7 @@ def main():
     ap.add_argument("--workload", default="cfg3_8b",
                     choices=["cfg3_8b", "cfg2_1b", "cfg1_tiny", "cfg4_8b_b16", "cfg5_8b_16k"])
     ap.add_argument("--prompt", type=int, default=0, help="override the prompt length of a batch workload")
+    ap.add_argument("--skips", default="", help="comma-separated numbers of skipped layers to sweep instead of the workload's own")
     ap.add_argument("--headline-skip", type=float, default=0.25)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -64,7 +65,7 @@ def main():
     seed = wl["seed"]
     n_prompt, L = wl["prompt"], desc.n_layers
     K, W = args.steps, args.warmup
-    skips = sorted(set(wl["skip"]))
+    skips = sorted(set(int(x) for x in args.skips.split(","))) if args.skips else sorted(set(wl["skip"]))
     torch.cuda.set_device(0)
     stream = torch.cuda.Stream()
     t0 = time.time()
