@@ -126,18 +126,21 @@ def main():
     gu_bytes = 2 * desc.d_ffn * desc.d_model * desc.bytes_per_elem       # both matrices, once
     per_op = {"kernel": "k_gateup (RMSNorm + gate/up mat-vec + SiLU*up of one layer, per-op path)",
               "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3, "GB/s": gu_bytes / (gu_ms * 1e-3) / 1e9}
-    traffic = None
+    # HBM bytes per launch from the committed counter runs (profiles/): valid for the headline mask only
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("k_step" if persistent else "k_gateup")
+            traffic_detail = json.load(open(tpath)).get("k_step" if persistent else "k_gateup")
+            if traffic_detail and traffic_detail.get("kept_layers") == head["kept_layers"]:
+                traffic = traffic_detail["bytes_per_launch"]
         except Exception:
-            traffic = None
+            traffic, traffic_detail = None, None
     if persistent:
         achieved = head["step_bytes"] / (head["ms_per_step"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_step (whole decode step of the kept layers + LM head as one persistent kernel)",
                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": traffic, "bytes_per_launch": head["step_bytes"],
+                    "traffic": traffic, "traffic_detail": traffic_detail, "bytes_per_launch": head["step_bytes"],
                     "avg_launch_us": head["ms_per_step"] * 1e3, "launches_timed": K, "per_op_gateup": per_op}
     else:
         roofline = {"bound": "hbm", "kernel": per_op["kernel"], "achieved": per_op["GB/s"], "peak": HBM_PEAK_GBS,
