@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="cfg3_8b",
-                    choices=["cfg3_8b", "cfg2_1b", "cfg1_tiny", "cfg4_8b_b16", "cfg5_8b_16k"])
+                    choices=["cfg3_8b", "cfg3_3b", "cfg2_1b", "cfg1_tiny", "cfg4_8b_b16", "cfg5_8b_16k"])
     ap.add_argument("--prompt", type=int, default=0, help="override the prompt length of a batch workload")
     ap.add_argument("--skips", default="", help="comma-separated numbers of skipped layers to sweep instead of the workload's own")
     ap.add_argument("--headline-skip", type=float, default=0.25)

@@ -365,13 +365,13 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
 bool step_kernel_fits(const first_ctx* c) {
   const first_model_desc& d = c->d;
   if (d.dtype != FIRST_DTYPE_BF16) return false;
-  if (d.d_model % SK_SEG || c->nq % SK_SEG || d.d_ffn % SK_SEG) return false;
+  if (d.d_model % 256 || c->nq % 256 || d.d_ffn % 256) return false;           // row segments may be partial, rows stay 512-byte aligned
   if (c->G > SK_SWAVES || d.kv_page_tokens != 16) return false;               // one streaming wave per query head of a KV group
   if (d.n_kv_heads > c->num_cu || d.d_ffn > 16384 || d.d_model > 16384 || c->nq > 16384) return false;
   const int ncu = c->num_cu;
   if ((long long)std::max({d.vocab, 2 * d.d_ffn, c->nq + 2 * c->nkv}) * (ncu + 1) >= (1LL << 31)) return false;
   // (rows per workgroup: up to 15 % above an even share, see k_rebalance)
-  auto units = [&](long long rows, int K) { return (int)(((rows + ncu - 1) / ncu) * 6 / 5 + 4) * (K / SK_SEG); };
+  auto units = [&](long long rows, int K) { return (int)(((rows + ncu - 1) / ncu) * 6 / 5 + 4) * ((K + SK_SEG - 1) / SK_SEG); };
   const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), units(d.d_model, c->nq),
                               units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});
   if (worst > SK_PSUM) return false;

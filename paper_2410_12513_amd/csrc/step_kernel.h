@@ -157,16 +157,17 @@ struct SkLds {
 };
 
 __host__ __device__ inline size_t sk_lds_floats(int D, int nq, int F, int G, int hd) {
-  const int xs = D > nq ? D : nq;
+  const int xs = (D > nq ? D : nq) == 0 ? 0 : ((D > nq ? D : nq) + 2047) / 2048 * 2048;     // staged vectors are padded to whole segments
+  F = (F + 2047) / 2048 * 2048;
   return (size_t)xs + F + SK_PSUM + (SK_WAVES + 8) + (size_t)G * hd + 2 * hd + hd + SK_WAVES * 64 +
          (size_t)SK_WAVES * (hd + 2) + 4;
 }
 
 __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int G, int hd) {
   SkLds s;
-  const int xs = D > nq ? D : nq;
+  const int xs = ((D > nq ? D : nq) + 2047) / 2048 * 2048;
   s.xs = base; base += xs;
-  s.zs = base; base += F;
+  s.zs = base; base += (F + 2047) / 2048 * 2048;
   s.psum = base; base += SK_PSUM;
   s.red = base; base += SK_WAVES + 8;
   s.qs = base; base += G * hd;
@@ -338,6 +339,24 @@ __device__ __forceinline__ int grid_sync(SkBar& B, unsigned epoch, int cu, int n
   }
 }
 
+// A staged vector of K elements occupies K rounded up to whole 2048-element segments: the
+// second plane starts at sk_plane(K), and the padding of both planes is zero (a row segment
+// that reaches past the end of its weight row reads zeros there, and 0 * 0 must not meet a
+// stale NaN).
+__host__ __device__ __forceinline__ int sk_pad(int K) { return (K + SK_SEG - 1) / SK_SEG * SK_SEG; }
+__host__ __device__ __forceinline__ int sk_plane(int K) { return sk_pad(K) >> 1; }
+
+// Zeroes the padding of both planes (nothing to do when K is a whole number of segments).
+__device__ __forceinline__ void sk_zero_pad(float* xs, int K) {
+  const int ngroups = K >> 3, gpad = sk_pad(K) >> 3, plane = sk_plane(K);
+  if (gpad == ngroups) return;
+  const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+  for (int g = ngroups + (int)(threadIdx.x & 63); g < gpad; g += 64) {
+    *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = zero;
+    *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = zero;
+  }
+}
+
 // RMSNorm gains of a vector of at most 4096 elements, 8 groups of 8 per lane.  They are
 // constants, so the service wave fetches them before it waits at the grid barrier.
 struct SkGains { f32x4_t a[8], b[8]; };
@@ -373,14 +392,16 @@ __device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, in
     }
   }
   const float r = 1.0f / sqrtf(wave_sum(ss) / (float)K + eps);
+  const int plane = sk_plane(K);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int g = i * 64 + lane;
     if (g < ngroups) {
       *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i] * G.a[i] * r;
-      *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = b[i] * G.b[i] * r;
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b[i] * G.b[i] * r;
     }
   }
+  sk_zero_pad(xs, K);
 }
 
 // xs <- x or RMSNorm(x; gain), in the two-plane layout the 8-wide weight vectors read.
@@ -390,7 +411,7 @@ __device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, in
 __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps) {
   constexpr int NB = 8;
   const int lane = threadIdx.x & 63;
-  const int ngroups = K >> 3;
+  const int ngroups = K >> 3, plane = sk_plane(K);
   float ss = 0.f;
   for (int g0 = 0; g0 < ngroups; g0 += NB * 64) {
     f32x4_t a[NB], b[NB];
@@ -414,15 +435,16 @@ __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, 
           u *= g0v; v *= g1v;
         }
         *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = u;
-        *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = v;
+        *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = v;
       }
     }
   }
+  sk_zero_pad(xs, K);
   if (gain) {
     const float r = 1.0f / sqrtf(wave_sum(ss) / (float)K + eps);
     for (int g = lane; g < ngroups; g += 64) {                      // each lane rescales what it wrote
       f32x4_t* u = reinterpret_cast<f32x4_t*>(xs + (g << 2));
-      f32x4_t* v = reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2));
+      f32x4_t* v = reinterpret_cast<f32x4_t*>(xs + plane + (g << 2));
       *u = *u * r; *v = *v * r;
     }
   }
@@ -432,7 +454,7 @@ __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, 
 // norm: one batch of coherent loads.  Executed by the service wave.
 __device__ __forceinline__ void sk_stage_segments(float* xs, const float* x, int K, int c0, int c1) {
   const int lane = threadIdx.x & 63;
-  const int g_begin = c0 * (SK_SEG / 8), g_end = min(c1 * (SK_SEG / 8), K >> 3);
+  const int g_begin = c0 * (SK_SEG / 8), g_pad = c1 * (SK_SEG / 8), g_end = min(g_pad, K >> 3), plane = sk_plane(K);
   f32x4_t a[8], b[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -447,9 +469,10 @@ __device__ __forceinline__ void sk_stage_segments(float* xs, const float* x, int
     const int g = g_begin + i * 64 + lane;
     if (g < g_end) {
       *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i];
-      *reinterpret_cast<f32x4_t*>(xs + (K >> 1) + (g << 2)) = b[i];
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b[i];
     }
   }
+  if (g_pad > g_end) sk_zero_pad(xs, K);
 }
 
 // A segment is one mat-vec phase of the step (QKV, O, gate/up, down of a kept layer, or the
@@ -461,6 +484,7 @@ enum { SEG_QKV = 0, SEG_O = 1, SEG_GU = 2, SEG_DN = 3, SEG_HEAD = 4, SEG_NONE = 
 struct SegDesc {
   const bf16 *m0, *m1, *m2;     // up to three stacked matrices (or two interleaved ones)
   int n0, n1, K, inter;
+  int xplane;                   // offset of the second plane of the staged input vector (sk_plane(K))
   int row0, nrows, nseg, nunits, nr_pad;
   unsigned inv_nrows;           // ceil(2^32 / nrows): unit / nrows = umulhi(unit, inv_nrows) for the small units here
   int kind;
@@ -476,11 +500,12 @@ struct SkShare { int w0, w1, ncu; };
 __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, const SkShare& sh, int pair) {
   const int n = N / pair;
   d.K = K;
+  d.xplane = sk_plane(K);
   // 64-bit product, 32-bit division (n * w >> 10 < 2^31 is checked on the host): 64-bit
   // division is emulated and costs dozens of registers
   d.row0 = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w0) >> 10) / (unsigned)sh.ncu) * pair;
   d.nrows = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w1) >> 10) / (unsigned)sh.ncu) * pair - d.row0;
-  d.nseg = K / SK_SEG;
+  d.nseg = (K + SK_SEG - 1) / SK_SEG;               // the last segment of a row may be partial (reads past the row end return zeros)
   d.inv_nrows = d.nrows <= 1 ? 0u : (unsigned)((0x100000000ull + d.nrows - 1) / d.nrows);   // (nrows <= 1 handled at use)
   d.nunits = d.nrows * d.nseg;
   const int nr = (d.nunits + SK_SWAVES - 1) / SK_SWAVES;
@@ -489,7 +514,7 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, const SkShar
 
 __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   d.m0 = uni(d.m0); d.m1 = uni(d.m1); d.m2 = uni(d.m2); d.gain = uni(d.gain); d.kv = uni(d.kv);
-  d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
+  d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.xplane = uni(d.xplane); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
   d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.inv_nrows = (unsigned)uni((int)d.inv_nrows); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
   return d;
 }
@@ -602,7 +627,7 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
     } while (seen <= sg && ++spins < SK_SPIN_LIMIT);      // bounded; the service wave always gets there
   }
   const float* x0p = xs + ((sg * SK_SEG + lane * 8) >> 1);
-  const float* x1p = x0p + (K >> 1);
+  const float* x1p = x0p + uni(d.xplane);
   float4 x0[4], x1[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {

@@ -54,6 +54,7 @@ CONFIGS: Dict[str, ModelDesc] = {
     "tiny": ModelDesc(4, 256, 4, 4, 64, 688, 1024, dtype="fp32"),
     "1b": ModelDesc(16, 2048, 32, 8, 64, 8192, 32000, dtype="bf16"),
     "8b": ModelDesc(32, 4096, 32, 8, 128, 14336, 128256, dtype="bf16"),
+    "3b": ModelDesc(28, 3072, 24, 8, 128, 8192, 128256, dtype="bf16"),        # geometry of the paper's second model
     # reduced shapes for fast parity tests: ragged FFN / vocab sizes, GQA group 4
     "mini_bf16": ModelDesc(4, 512, 8, 2, 64, 1416, 2003, dtype="bf16"),
     "mini_fp32": ModelDesc(3, 256, 4, 2, 64, 696, 1001, dtype="fp32"),
@@ -63,6 +64,7 @@ CONFIGS: Dict[str, ModelDesc] = {
     "step_hd64": ModelDesc(2, 2048, 32, 8, 64, 2048, 3001, dtype="bf16"),
     "step_g2": ModelDesc(2, 2048, 16, 8, 128, 2048, 2999, dtype="bf16"),
     "step_mha": ModelDesc(2, 2048, 16, 16, 128, 2048, 2999, dtype="bf16"),
+    "step_3k": ModelDesc(2, 1536, 12, 4, 128, 2560, 3001, dtype="bf16"),          # widths that are not multiples of 2048
 }
 
 # Workloads: (model, batch, prompt length(s), decode steps, skipped-layer count(s)).
@@ -70,6 +72,7 @@ WORKLOADS: Dict[str, dict] = {
     "cfg1_tiny": dict(model="tiny", batch=1, prompt=32, decode=16, skip=[2, 0, 4], seed=1),
     "cfg2_1b": dict(model="1b", batch=1, prompt=512, decode=128, skip=[4], seed=2),
     "cfg3_8b": dict(model="8b", batch=1, prompt=1024, decode=256, skip=[0, 8, 16], seed=3),
+    "cfg3_3b": dict(model="3b", batch=1, prompt=1024, decode=256, skip=[0, 7, 14], seed=6),
     "cfg4_8b_b16": dict(model="8b", batch=16, prompt=(256, 2048), decode=128, skip="U[0,0.5]", seed=4),
     "cfg5_8b_16k": dict(model="8b", batch=4, prompt=16384, decode=256, skip=[12], seed=5),
 }

@@ -18,7 +18,7 @@ OPT_STEP_BALANCE = 8
 
 
 @pytest.mark.parametrize("model,n_prompt", [("step_hd128", 150), ("step_hd64", 70), ("step_g2", 200),
-                                            ("step_mha", 65), ("step_hd128", 700)])
+                                            ("step_mha", 65), ("step_hd128", 700), ("step_3k", 90)])
 @pytest.mark.parametrize("mask_kind", ["interior", "all_keep", "all_skip"])
 def test_step_kernel_matches_oracle(model, n_prompt, mask_kind):
     desc = CONFIGS[model]
