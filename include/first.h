@@ -48,7 +48,7 @@ extern "C" {
 #define FIRST_OPT_USE_GRAPH     1  /* 1 (default): replay a cached hipGraph per mask; 0: eager launches */
 #define FIRST_OPT_ATTN_SPLITS   2  /* KV splits per (sequence, KV head) in decode attention; 0 = auto   */
 #define FIRST_OPT_DECODE_PATH   3  /* -1 (default): persistent whole-step kernel when the model fits it
-                                      (bf16, widths multiples of 2048, one live sequence), else per-op
+                                      (bf16, widths multiples of 256, one live sequence), else per-op
                                       kernels; 0: always per-op kernels; 1: persistent kernel or error */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */

@@ -766,7 +766,7 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   const bool persistent = c->step_ok && c->B == 1 && c->decode_path != 0;
   if (c->decode_path == 1 && !persistent)
     return fail(c, FIRST_ERR_STATE, "first_decode_step: the persistent kernel needs a bf16 model whose widths are "
-                                    "multiples of 2048 and exactly one live sequence");
+                                    "multiples of 256, 16-token pages and exactly one live sequence");
   const bool batch_ok = bf && c->B > 1 && c->d_xh && d_batch_fits(c);
   const bool batched = !persistent && batch_ok && c->batch_path != 0;
   if (c->batch_path == 1 && !persistent && !batched)
