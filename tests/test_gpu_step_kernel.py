@@ -120,3 +120,28 @@ def test_step_kernel_is_refused_when_the_model_does_not_fit():
     ctx.decode_step(tin, None, tin)          # automatic choice falls back to the per-op kernels
     ctx.sync()
     ctx.close()
+
+
+def test_step_kernel_long_run_is_reproducible_and_never_gives_up():
+    """1500 free-running steps twice (each step feeds its own token): identical token streams,
+    finite logits, and first_sync reports no barrier that gave up."""
+    desc = CONFIGS["step_hd128"]
+    prompt = make_prompt(desc.vocab, 33, 51)
+    streams = []
+    for run in range(2):
+        desc, w, router, ctx = build("step_hd128", 51, max_seq_len=33 + 1500 + 8)
+        ctx.set_option(OPT_DECODE_PATH, 1)
+        got = _prefill(ctx, desc, [prompt])
+        ctx.set_mask(0, [1, 0, 1])
+        tok = got["token"].to(torch.int32).cuda()
+        hist = torch.zeros(1500, dtype=torch.int32, device="cuda")
+        lg = torch.zeros(1, desc.vocab, device="cuda")
+        for s in range(1500):
+            ctx.decode_step(tok, lg, tok)
+            ctx.sync()                           # raises if a grid barrier gave up
+            hist[s:s + 1].copy_(tok)
+        assert bool(torch.isfinite(lg).all())
+        assert ctx.seq_len(0) == 33 + 1500
+        streams.append(hist.cpu())
+        ctx.close()
+    assert torch.equal(streams[0], streams[1])
