@@ -65,9 +65,12 @@ extern "C" {
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
                                       keep it share one pass over its weights (bf16 models, widths multiples of 8),
                                       else one pass per sequence; 0: always one pass per sequence; 1: shared pass or error */
-#define FIRST_OPT_STEP_BARRIER  5  /* grid barrier of the persistent kernel.  1 (default): workgroups of one XCD
-                                      count arrivals in their shared L2 and the last one publishes one flag per
-                                      XCD; 0: every workgroup publishes a flag and polls all of them */
+#define FIRST_OPT_STEP_BARRIER  5  /* how the workgroups of the persistent kernel hand activations on between
+                                      phases.  2 (default): no grid barrier; every exchanged 32-bit word carries an
+                                      alternating tag in its lowest mantissa bit and consumers re-read until all
+                                      words are current.  1: grid barrier, workgroups of one XCD count arrivals in
+                                      their shared L2 and the last one publishes one flag per XCD; 0: grid barrier,
+                                      every workgroup publishes a flag and polls all of them */
 
 typedef struct first_ctx first_ctx;
 

@@ -84,6 +84,9 @@ struct first_ctx {
   unsigned* d_share_time = nullptr;
   int step_balance = 0;                   // FIRST_OPT_STEP_BALANCE
   int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
+  int step_tagged = 1;                    // persistent kernel exchanges activations as tagged words instead of using grid barriers
+  float *x_h = nullptr, *x_qkv = nullptr, *x_attn = nullptr, *x_z = nullptr;   // tagged exchange vectors (written by k_step only)
+  int* d_tagstate = nullptr;              // [B][4] tags of their latest writes
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
   int step_timing = 0;
@@ -139,6 +142,17 @@ hipError_t reset_shares(first_ctx* c) {
   const int eq[8] = {1024, 1024, 1024, 1024, 1024, 1024, 1024, 1024};
   hipError_t e = hipMemcpy(c->d_shares, eq, sizeof(eq), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemset(c->d_share_time, 0, (size_t)c->num_cu * sizeof(unsigned));
+  return e;
+}
+
+// Tagged exchange of the persistent kernel: all-zero vectors and "latest tag 0" are a consistent start.
+hipError_t reset_tagged_exchange(first_ctx* c) {
+  const size_t Bm = (size_t)c->d.max_batch;
+  hipError_t e = hipMemset(c->x_h, 0, Bm * c->d.d_model * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(c->x_qkv, 0, Bm * (c->nq + 2 * c->nkv) * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(c->x_attn, 0, Bm * c->nq * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(c->x_z, 0, Bm * c->d.d_ffn * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(c->d_tagstate, 0, Bm * 4 * sizeof(int));
   return e;
 }
 
@@ -350,13 +364,22 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
   P.bar = c->d_bar; P.err = c->d_err; P.two_level = c->step_two_level;
+  const bool tagged = c->step_tagged && c->d.d_model <= 64 * c->num_cu;       // (one residual row per service-wave lane)
+  if (tagged) {
+    P.tagged = 1; P.tagstate = c->d_tagstate; P.h_out = c->d_h;
+    P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
+  }
   P.shares = c->d_shares; P.share_time = c->step_balance ? c->d_share_time : nullptr;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
   hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)sk_bar_words(c->num_cu));
-  if (c->d.head_dim == 128)
-    hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  if (c->d.head_dim == 128 && tagged)
+    hipLaunchKernelGGL((k_step<128, true>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  else if (c->d.head_dim == 128)
+    hipLaunchKernelGGL((k_step<128, false>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  else if (tagged)
+    hipLaunchKernelGGL((k_step<64, true>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
   else
-    hipLaunchKernelGGL(k_step<64>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+    hipLaunchKernelGGL((k_step<64, false>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
   if (c->step_balance)
     hipLaunchKernelGGL(k_rebalance, dim3(1), dim3(256), 0, c->stream, c->d_share_time, c->d_shares, c->num_cu);
 }
@@ -600,6 +623,9 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
   }
   A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
+  A(dev_alloc(c, &c->x_h, (size_t)B * d.d_model)); A(dev_alloc(c, &c->x_qkv, (size_t)B * (c->nq + 2 * c->nkv)));
+  A(dev_alloc(c, &c->x_attn, (size_t)B * c->nq)); A(dev_alloc(c, &c->x_z, (size_t)B * d.d_ffn));
+  A(dev_alloc(c, &c->d_tagstate, (size_t)B * 4));
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
   A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
   if (rc == FIRST_OK) {
@@ -611,6 +637,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
     if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
     if (e == hipSuccess) e = reset_shares(c);
+    if (e == hipSuccess) e = reset_tagged_exchange(c);
     if (e == hipSuccess) e = hipMemset(c->d_bar, 0, (size_t)sk_bar_words(c->num_cu) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
@@ -623,15 +650,16 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
       }
       e = hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
       c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
-      const void* fn = d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>)
-                                         : reinterpret_cast<const void*>(&k_step<64>);
-      if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
-      int per_cu = 0;
-      if (e == hipSuccess)
-        e = d.head_dim == 128
-                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<128>, SK_THREADS, c->step_lds)
-                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_step<64>, SK_THREADS, c->step_lds);
-      if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
+      const void* fns[2] = {d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128, true>)
+                                              : reinterpret_cast<const void*>(&k_step<64, true>),
+                            d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128, false>)
+                                              : reinterpret_cast<const void*>(&k_step<64, false>)};
+      for (const void* fn : fns) {
+        if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
+        int per_cu = 0;
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, SK_THREADS, c->step_lds);
+        if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
+      }
     }
     if (e == hipSuccess && B > 1 && d.dtype == FIRST_DTYPE_BF16 && d_batch_fits(c)) e = make_tiled_copies(c);
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
@@ -838,8 +866,9 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
       c->batch_path = value; return FIRST_OK;
     case FIRST_OPT_STEP_BARRIER:
-      if (value < 0 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
-      c->step_two_level = value;
+      if (value < 0 || value > 2) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
+      c->step_tagged = value == 2;
+      if (value < 2) c->step_two_level = value;
       drop_graphs(c);
       return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
@@ -851,7 +880,12 @@ int first_sync(first_ctx* c) {
   HIPCHK(c, hipStreamSynchronize(c->stream));
   int err = 0;
   HIPCHK(c, hipMemcpy(&err, c->d_err, sizeof(int), hipMemcpyDeviceToHost));
-  if (err) return fail(c, FIRST_ERR_HIP, "first_sync: a grid barrier of the persistent decode kernel gave up waiting");
+  if (err) {
+    // the exchange state is undefined after a wait that gave up: start it afresh
+    (void)hipMemset(c->d_err, 0, 4 * sizeof(int));
+    (void)reset_tagged_exchange(c);
+    return fail(c, FIRST_ERR_HIP, "first_sync: a wait between workgroups of the persistent decode kernel gave up");
+  }
   return FIRST_OK;
 }
 

@@ -82,6 +82,45 @@ __device__ __forceinline__ void coh_wait() { asm volatile("s_waitcnt vmcnt(0)" :
 template <typename T>
 __device__ __forceinline__ void coh_use(T& v) { asm volatile("" : "+v"(v)); }
 
+// ---------------------------------------------------------------------------------------
+// Tagged exchange.  A vector that one phase produces and the next one consumes can carry its
+// own "ready" signal: every 32-bit word holds the value in its upper 31 bits and, in the lowest
+// mantissa bit, a tag that alternates between consecutive writes of that vector.  A consumer
+// that expects tag t re-reads until every word shows t; a word is written by one aligned
+// 32-bit store, so it is either the previous or the current value, never a mixture.  This
+// replaces "store, wait for the store, arrive at a grid barrier, wait, load" by "store" and
+// "load until current", one memory round trip instead of three or four.
+//
+// Why one bit is enough: a workgroup can be at most one phase ahead of the slowest one (to
+// finish staging a phase's input it needs every workgroup's output of the phase before), and
+// each vector is written at most once per phase, so a reader only ever meets the write it
+// waits for or the one before it.  Relative error of dropping the last mantissa bit: 2^-23.
+__device__ __forceinline__ float sk_tagged(float v, unsigned bit) {
+  return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
+}
+__device__ __forceinline__ float sk_untag(float v) { return __uint_as_float(__float_as_uint(v) & ~1u); }
+__device__ __forceinline__ f32x4_t sk_untag(f32x4_t v) {
+  v.x = sk_untag(v.x); v.y = sk_untag(v.y); v.z = sk_untag(v.z); v.w = sk_untag(v.w);
+  return v;
+}
+// Collects the tags of the words seen so far: good(bit) iff all of them equal bit.
+struct SkTags {
+  unsigned any = 0u, all = ~0u;
+  __device__ __forceinline__ void add(float v) { const unsigned u = __float_as_uint(v); any |= u; all &= u; }
+  __device__ __forceinline__ void add(const f32x4_t& v) { add(v.x); add(v.y); add(v.z); add(v.w); }
+  __device__ __forceinline__ bool good(unsigned bit) const { return bit ? (all & 1u) != 0u : (any & 1u) == 0u; }
+};
+// One more failed poll: gives up (and says so in *err) after SK_SPIN_LIMIT polls or when
+// another wave of the grid has given up; e is *err as read together with the poll.
+__device__ __forceinline__ bool sk_poll_give_up(unsigned& spins, int e, int* err) {
+  if (++spins <= SK_SPIN_LIMIT && e == 0) { __builtin_amdgcn_s_sleep(2); return false; }
+  __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return true;
+}
+__device__ __forceinline__ void coh_issue4(int& v, const int* p) {
+  asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
+}
+
 // Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait
 // for outstanding global loads, so weight prefetches stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -138,6 +177,9 @@ struct StepParams {
   const int* shares;           // [8] per-XCD share of the rows (1024 = equal), or null: even split
   unsigned* share_time;        // [grid] out: this workgroup's gate/up streaming time (100 MHz ticks), its XCD in the top byte
   int* err;                    // set to 1 if a barrier wait gives up
+  int tagged;                  // 1: activations are exchanged as self-validating words (see "Tagged exchange"), no grid barrier between phases
+  int* tagstate;               // [B][4] tag of the latest write to the h, qkv, attn and z vectors of each slot (tagged exchange)
+  float* h_out;                // tagged exchange: [B][D] plain copy of the final hidden state (d.h then holds tagged words)
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
 
@@ -372,20 +414,38 @@ __device__ __forceinline__ void sk_load_gains(SkGains& G, const float* gain, int
 
 // xs <- RMSNorm(x; gains) for K <= 4096 in one pass: one batch of coherent loads, the sum of
 // squares over the wave, one write of the scaled values.  Executed by the service wave.
-__device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, int K, const SkGains& G, float eps) {
+// TAG: x holds tagged words; the batch is re-read until every word carries tag `bit`
+// (returns false if that wait gives up).
+template <bool TAG>
+__device__ __forceinline__ bool sk_stage_norm_wave(float* xs, const float* x, int K, const SkGains& G, float eps,
+                                                   unsigned bit, int* err) {
   const int lane = threadIdx.x & 63, ngroups = K >> 3;
   f32x4_t a[8], b[8];
+  unsigned spins = 0;
+  for (;;) {
+    int e = 0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int k = min(i * 64 + lane, ngroups - 1) << 3;
-    coh_issue16(a[i], x + k);
-    coh_issue16(b[i], x + k + 4);
+    for (int i = 0; i < 8; ++i) {
+      const int k = min(i * 64 + lane, ngroups - 1) << 3;
+      coh_issue16(a[i], x + k);
+      coh_issue16(b[i], x + k + 4);
+    }
+    if (TAG) coh_issue4(e, err);
+    coh_wait();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { coh_use(a[i]); coh_use(b[i]); }
+    if (!TAG) break;
+    coh_use(e);
+    SkTags t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { t.add(a[i]); t.add(b[i]); }
+    if (__all(t.good(bit))) break;
+    if (sk_poll_give_up(spins, uni(e), err)) return false;
   }
-  coh_wait();
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    coh_use(a[i]); coh_use(b[i]);
+    if (TAG) { a[i] = sk_untag(a[i]); b[i] = sk_untag(b[i]); }
     if (i * 64 + lane < ngroups) {
       const f32x4_t u = a[i], v = b[i];
       ss += u.x * u.x + u.y * u.y + u.z * u.z + u.w * u.w + v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
@@ -402,32 +462,49 @@ __device__ __forceinline__ void sk_stage_norm_wave(float* xs, const float* x, in
     }
   }
   sk_zero_pad(xs, K);
+  return true;
 }
 
 // xs <- x or RMSNorm(x; gain), in the two-plane layout the 8-wide weight vectors read.
 // Executed by ONE wave (the service wave).  x was written by other workgroups in this
 // kernel: coherent 16-byte loads, 16 requested per lane before each wait (more in flight per
-// wave measured slower while the weight stream is running).
-__device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps) {
+// wave measured slower while the weight stream is running).  TAG as above, batch by batch.
+template <bool TAG>
+__device__ __forceinline__ bool sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps,
+                                              unsigned bit, int* err) {
   constexpr int NB = 8;
   const int lane = threadIdx.x & 63;
   const int ngroups = K >> 3, plane = sk_plane(K);
   float ss = 0.f;
+  unsigned spins = 0;
   for (int g0 = 0; g0 < ngroups; g0 += NB * 64) {
     f32x4_t a[NB], b[NB];
+    for (;;) {
+      int e = 0;
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int k = min(g0 + i * 64 + lane, ngroups - 1) << 3;      // out-of-range groups re-read the last one
-      coh_issue16(a[i], x + k);
-      coh_issue16(b[i], x + k + 4);
+      for (int i = 0; i < NB; ++i) {
+        const int k = min(g0 + i * 64 + lane, ngroups - 1) << 3;      // out-of-range groups re-read the last one
+        coh_issue16(a[i], x + k);
+        coh_issue16(b[i], x + k + 4);
+      }
+      if (TAG) coh_issue4(e, err);
+      coh_wait();
+#pragma unroll
+      for (int i = 0; i < NB; ++i) { coh_use(a[i]); coh_use(b[i]); }
+      if (!TAG) break;
+      coh_use(e);
+      SkTags t;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) { t.add(a[i]); t.add(b[i]); }
+      if (__all(t.good(bit))) break;
+      if (sk_poll_give_up(spins, uni(e), err)) return false;
     }
-    coh_wait();
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      coh_use(a[i]); coh_use(b[i]);
       const int g = g0 + i * 64 + lane;
       if (g < ngroups) {
         f32x4_t u = a[i], v = b[i];
+        if (TAG) { u = sk_untag(u); v = sk_untag(v); }
         ss += u.x * u.x + u.y * u.y + u.z * u.z + u.w * u.w + v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         if (gain) {
           const f32x4_t g0v = *as_global(reinterpret_cast<const f32x4_t*>(gain + (g << 3)));
@@ -448,31 +525,47 @@ __device__ __forceinline__ void sk_stage_wave(float* xs, const float* x, int K, 
       *u = *u * r; *v = *v * r;
     }
   }
+  return true;
 }
 
 // K-segments [c0, c1) (2048 elements each, c1 - c0 <= 2) of x into the two-plane layout, no
-// norm: one batch of coherent loads.  Executed by the service wave.
-__device__ __forceinline__ void sk_stage_segments(float* xs, const float* x, int K, int c0, int c1) {
+// norm: one batch of coherent loads.  Executed by the service wave.  TAG as above.
+template <bool TAG>
+__device__ __forceinline__ bool sk_stage_segments(float* xs, const float* x, int K, int c0, int c1, unsigned bit, int* err) {
   const int lane = threadIdx.x & 63;
   const int g_begin = c0 * (SK_SEG / 8), g_pad = c1 * (SK_SEG / 8), g_end = min(g_pad, K >> 3), plane = sk_plane(K);
   f32x4_t a[8], b[8];
+  unsigned spins = 0;
+  for (;;) {
+    int e = 0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int k = min(g_begin + i * 64 + lane, g_end - 1) << 3;
-    coh_issue16(a[i], x + k);
-    coh_issue16(b[i], x + k + 4);
+    for (int i = 0; i < 8; ++i) {
+      const int k = min(g_begin + i * 64 + lane, g_end - 1) << 3;
+      coh_issue16(a[i], x + k);
+      coh_issue16(b[i], x + k + 4);
+    }
+    if (TAG) coh_issue4(e, err);
+    coh_wait();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { coh_use(a[i]); coh_use(b[i]); }
+    if (!TAG) break;
+    coh_use(e);
+    SkTags t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { t.add(a[i]); t.add(b[i]); }
+    if (__all(t.good(bit))) break;
+    if (sk_poll_give_up(spins, uni(e), err)) return false;
   }
-  coh_wait();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    coh_use(a[i]); coh_use(b[i]);
     const int g = g_begin + i * 64 + lane;
     if (g < g_end) {
-      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i];
-      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b[i];
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = TAG ? sk_untag(a[i]) : a[i];
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = TAG ? sk_untag(b[i]) : b[i];
     }
   }
   if (g_pad > g_end) sk_zero_pad(xs, K);
+  return true;
 }
 
 // A segment is one mat-vec phase of the step (QKV, O, gate/up, down of a kept layer, or the
@@ -659,9 +752,12 @@ __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg,
 // lane = key for the scores, lane = (key subgroup, 8-dim chunk) for the weighted values.
 // NW = number of worker waves of the workgroup (the persistent kernel's streaming waves; the
 // stand-alone attention kernel of the batched path runs a full set of SK_WAVES workers).
-template <int HD, int NW = SK_SWAVES>
-__device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
-                                             unsigned long long* stamps) {
+// EXT: the queries and the new key / value are already in LDS (sk_attn_prologue_tagged, run by
+// the service wave); the function returns false if that wave reported failure.  out_tag >= 0:
+// the attention output is written as tagged words.
+template <int HD, int NW = SK_SWAVES, bool EXT = false>
+__device__ __forceinline__ bool sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
+                                             unsigned long long* stamps, int out_tag = -1) {
   const DecParams& p = P.d;
 #define SK_ASTAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
   SK_ASTAMP(6);
@@ -720,7 +816,7 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
   request(0);
 
   // this step's q (G heads), k and v of the KV head: one batch of coherent loads
-  {
+  if (!EXT) {
     float q1, q2, k1, k2, vv;
     const int iq = min(tid, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
     const int dk = min(tid, HALF - 1), dv = min(tid, HD - 1);
@@ -753,6 +849,10 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
     }
   }
   lds_barrier();
+  if (EXT) {
+    SK_ASTAMP(7);
+    if (uni(*S.flag) == 0) return false;
+  }
 
   float m = -INFINITY, l = 0.f, o[8], qv[8], kn[8], vn[8];
 #pragma unroll
@@ -903,12 +1003,98 @@ __device__ __forceinline__ void sk_attention(const StepParams& P, bf16* pool, co
       }
     }
     float* out = p.attn + (size_t)b * nq + H * HD;
-    st_coh(out + lane, a0 / den);
-    if (HD > 64) st_coh(out + lane + 64, a1 / den);
-    vm_wait_all();
+    if (out_tag >= 0) {
+      st_coh(out + lane, sk_tagged(a0 / den, (unsigned)out_tag));
+      if (HD > 64) st_coh(out + lane + 64, sk_tagged(a1 / den, (unsigned)out_tag));
+    } else {
+      st_coh(out + lane, a0 / den);
+      if (HD > 64) st_coh(out + lane + 64, a1 / den);
+      vm_wait_all();
+    }
   }
   SK_ASTAMP(11);
 #undef SK_ASTAMP
+  return true;
+}
+
+// Tagged exchange: the service wave fetches this step's q (G heads), k and v of KV head g as
+// soon as they carry tag `bit`, rotates them and leaves them in LDS for sk_attention<.., EXT>;
+// the workgroup that owns the new position also appends k and v to the cache.  The service
+// wave has no other loads in flight, so its polls are not queued behind the key tiles the
+// worker waves have already requested.  Returns false if the wait gives up.
+template <int HD>
+__device__ __forceinline__ bool sk_attn_prologue_tagged(const StepParams& P, bf16* pool, const SkLds& S, int g, int s,
+                                                        int nsplit, unsigned bit) {
+  const DecParams& p = P.d;
+  constexpr int HALF = HD / 2;
+  constexpr int NQ = (SK_SWAVES * HALF + 63) / 64;      // q pairs per lane (up to SK_SWAVES query heads per KV head)
+  constexpr int NV = (HD + 63) / 64;
+  const int b = p.b, G = p.G, Pg = p.P, lane = threadIdx.x & 63;
+  const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
+  const int tps = (tiles + nsplit - 1) / nsplit;
+  const int t_first = s * tps, t_last = min(tiles, t_first + tps);
+  const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
+  const int nq = p.Hq * HD, nkv = p.Hkv * HD;
+  const float* qkv = p.qkv + (size_t)b * (nq + 2 * nkv);
+  float q1[NQ], q2[NQ], k1, k2, vv[NV];
+  const int dk = min(lane, HALF - 1);
+  unsigned spins = 0;
+  for (;;) {
+    int e = 0;
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+      const int iq = min(j * 64 + lane, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
+      coh_issue4(q1[j], qkv + (g * G + hh) * HD + dq);
+      coh_issue4(q2[j], qkv + (g * G + hh) * HD + dq + HALF);
+    }
+    coh_issue4(k1, qkv + nq + g * HD + dk);
+    coh_issue4(k2, qkv + nq + g * HD + dk + HALF);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) coh_issue4(vv[j], qkv + nq + nkv + g * HD + min(j * 64 + lane, HD - 1));
+    coh_issue4(e, P.err);
+    coh_wait();
+    coh_use(e); coh_use(k1); coh_use(k2);
+    SkTags t;
+    t.add(k1); t.add(k2);
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) { coh_use(q1[j]); coh_use(q2[j]); t.add(q1[j]); t.add(q2[j]); }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) { coh_use(vv[j]); t.add(vv[j]); }
+    if (__all(t.good(bit))) break;
+    if (sk_poll_give_up(spins, uni(e), P.err)) return false;
+  }
+#pragma unroll
+  for (int j = 0; j < NQ; ++j) {
+    const int iq = j * 64 + lane, hh = iq / HALF, dq = iq - hh * HALF;
+    if (iq < G * HALF) {                              // rotate and pre-scale the queries
+      const float2 c = S.cs[dq];
+      const float a = sk_untag(q1[j]), bq = sk_untag(q2[j]);
+      S.qs[hh * HD + dq] = (a * c.x - bq * c.y) * p.qscale;
+      S.qs[hh * HD + dq + HALF] = (bq * c.x + a * c.y) * p.qscale;
+    }
+  }
+  if (owns_new) {                                     // append the new key / value; keep the stored values in LDS
+    const int* pt = p.page_table + (size_t)b * p.max_pages;
+    const size_t head_off = (size_t)g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
+    const size_t base = (size_t)pt[pos / Pg] * p.page_elems + head_off + (size_t)(pos % Pg) * HD;
+    if (lane < HALF) {
+      const float2 c = S.cs[dk];
+      const float a = sk_untag(k1), bk = sk_untag(k2);
+      const bf16 r1 = from_f32<bf16>(a * c.x - bk * c.y), r2 = from_f32<bf16>(bk * c.x + a * c.y);
+      stg_bf16(pool + base + dk, r1); stg_bf16(pool + base + dk + HALF, r2);
+      S.knew[dk] = to_f32(r1); S.knew[dk + HALF] = to_f32(r2);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int dv = j * 64 + lane;
+      if (dv < HD) {
+        const bf16 r = from_f32<bf16>(sk_untag(vv[j]));
+        stg_bf16(pool + base + v_off + dv, r);
+        S.vnew[dv] = to_f32(r);
+      }
+    }
+  }
+  return true;
 }
 
 // The service wave's part of the attention phase: it only keeps step with the workgroup
@@ -928,7 +1114,10 @@ __device__ __forceinline__ void sk_attention_service() {
 // phase's input vector into LDS.  It never has weight loads in flight, which matters because
 // a wave's loads return in order: a barrier poll or an input load issued behind a prefetch
 // queue would wait for all of it.
-template <int HD>
+//
+// TAG selects the tagged exchange (see above): no grid barrier between phases; the only grid
+// barrier left is the one before the final token reduction.
+template <int HD, bool TAG>
 __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   extern __shared__ __align__(16) float smem_f[];
   const DecParams& p = P.d;
@@ -952,8 +1141,16 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   }
   share.w0 = uni(share.w0); share.w1 = uni(share.w1);
   SkBar bar;
-  if (service) sk_bar_init(bar, P.bar, P.err, ncu, P.two_level);
+  if (service) sk_bar_init(bar, P.bar, P.err, ncu, TAG ? 0 : P.two_level);
   float* h = p.h + (size_t)b * D;
+  // tagged exchange: tags of the latest writes of h, qkv, attn and z (the same in every wave of
+  // the grid: each flips when the phase that writes the vector begins)
+  unsigned tag_h = 0, tag_q = 0, tag_a = 0, tag_z = 0;
+  if (TAG) {
+    const int* ts = P.tagstate + 4 * b;
+    tag_h = (unsigned)uni(ld_coh(ts)) & 1u; tag_q = (unsigned)uni(ld_coh(ts + 1)) & 1u;
+    tag_a = (unsigned)uni(ld_coh(ts + 2)) & 1u; tag_z = (unsigned)uni(ld_coh(ts + 3)) & 1u;
+  }
   const int nk = uni(P.n_kept[b]);
   const int* kept = P.kept + (size_t)b * P.L;
   const int pos = uni(p.len[b]);
@@ -988,18 +1185,30 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   } while (0)
 
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
+  float h_own = 0.f;                               // tagged exchange: service-wave lane r keeps residual row row0 + r of this workgroup
   {
     int tok = uni(p.tokens[b]);
     tok = min(max(tok, 0), p.V - 1);
     const bf16* row = reinterpret_cast<const bf16*>(p.embed) + (size_t)tok * D;
-    const int r0 = (int)((unsigned)(D * cu) / (unsigned)ncu), r1 = (int)((unsigned)(D * (cu + 1)) / (unsigned)ncu);
-    for (int k = r0 + tid; k < r1; k += SK_THREADS) st_coh(h + k, to_f32(row[k]));
+    if (TAG) {
+      // the rows this workgroup owns in every phase that writes h (at most 64, checked on the host)
+      SegDesc e{};
+      seg_split(e, D, D, share, 1);
+      tag_h ^= 1u;
+      if (service && lane < e.nrows) {
+        h_own = sk_untag(to_f32(row[e.row0 + lane]));
+        st_coh(h + e.row0 + lane, sk_tagged(h_own, tag_h));
+      }
+    } else {
+      const int r0 = (int)((unsigned)(D * cu) / (unsigned)ncu), r1 = (int)((unsigned)(D * (cu + 1)) / (unsigned)ncu);
+      for (int k = r0 + tid; k < r1; k += SK_THREADS) st_coh(h + k, to_f32(row[k]));
+    }
     for (int i = tid; i < HD / 2; i += SK_THREADS) {
       const double a = (double)pos * p.theta[i];
       S.cs[i] = make_float2((float)cos(a), (float)sin(a));
     }
   }
-  vm_wait_all();                                   // this wave's h rows are out
+  if (!TAG) vm_wait_all();                         // this wave's h rows are out
 
   const int nsegs = 4 * nk + 1;
   const bool attn_wg = cu < p.Hkv * nsplit;
@@ -1007,7 +1216,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   // The two roles run separate loops (so that the service wave carries no ring registers and
   // the streaming waves no staging registers) with the same sequence of workgroup barriers.
   if (service) {
-    lds_barrier();                                 // every wave's stores of the embedding are complete
+    lds_barrier();                                 // every wave's stores of the embedding are complete (and the rotation table)
     unsigned gu_ticks = 0;
     for (int s = 0; s < nsegs; ++s) {
       const SegDesc cur = seg_desc(P, s, nk, kept, share);
@@ -1015,39 +1224,55 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       SkGains gains;
       const bool fast_norm = cur.gain != nullptr && D <= 4096;
       if (fast_norm) sk_load_gains(gains, cur.gain, D);
-      SK_GRID_SYNC_TRACED();                       // everything the segment reads has been written
+      if (!TAG) SK_GRID_SYNC_TRACED();             // everything the segment reads has been written
       SK_STAMP(1);
+      bool staged_ok = true;
       if (cur.kind == SEG_O) {
-        lds_barrier();
-        if (uni(*S.flag) == 0) return;
-        if (attn_wg) sk_attention_service();
-        lds_barrier();                             // the attention output of this workgroup is out
-        SK_GRID_SYNC();
-        SK_STAMP(2);
-        sk_stage_wave(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f);
+        if (TAG) {
+          tag_a ^= 1u;
+          // q, k, v of this workgroup's KV head into LDS as soon as they are current
+          bool ok = true;
+          if (attn_wg) ok = sk_attn_prologue_tagged<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, tag_q);
+          if (lane == 0) *S.flag = ok ? 1 : 0;
+          lds_barrier();
+          if (uni(*S.flag) == 0) return;
+          if (attn_wg) { lds_barrier(); lds_barrier(); lds_barrier(); }
+          SK_STAMP(2);
+          staged_ok = sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err);
+        } else {
+          lds_barrier();
+          if (uni(*S.flag) == 0) return;
+          if (attn_wg) sk_attention_service();
+          lds_barrier();                           // the attention output of this workgroup is out
+          SK_GRID_SYNC();
+          SK_STAMP(2);
+          sk_stage_wave<false>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, 0u, nullptr);
+        }
       } else if (cur.kind == SEG_DN) {
         // the down projection starts on the first K-segment of its input; the rest is staged
         // while it streams (after the workgroup barrier below)
-        sk_stage_segments(S.zs, p.z + (size_t)b * F, F, 0, 1);
+        staged_ok = sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err);
         __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       } else if (fast_norm) {
-        sk_stage_norm_wave(S.xs, h, D, gains, p.eps);
+        staged_ok = sk_stage_norm_wave<TAG>(S.xs, h, D, gains, p.eps, tag_h, P.err);
       } else {
-        sk_stage_wave(S.xs, h, D, cur.gain, p.eps);
+        staged_ok = sk_stage_wave<TAG>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err);
       }
+      if (TAG && lane == 0) *S.flag = staged_ok ? 1 : 0;
       SK_STAMP(3);
-      lds_barrier();                               // input vector staged; barrier verdict visible
+      lds_barrier();                               // input vector staged; verdict of the wait visible
       if (uni(*S.flag) == 0) return;
       // residual rows this workgroup will update: final since the barrier above, so they are
-      // fetched while the weights stream
-      float h_prev = 0.f;
-      if ((cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
+      // fetched while the weights stream (tagged exchange: kept in a register instead)
+      float h_prev = h_own;
+      if (!TAG && (cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
       const bool timed = cur.kind == SEG_GU && P.share_time != nullptr;   // the longest phase measures this XCD's stream rate
       const unsigned long long t_stream = timed ? wall_clock64() : 0ull;
       if (cur.kind == SEG_DN) {
         for (int c = 1; c < cur.nseg; c += 2) {
           const int c1 = min(c + 2, cur.nseg);
-          sk_stage_segments(S.zs, p.z + (size_t)b * F, F, c, c1);
+          // (a wait that gives up has said so in *P.err: the next phase's wait ends the workgroup)
+          sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, c, c1, tag_z, P.err);
           __hip_atomic_store(S.flag + 2, c1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
       }
@@ -1057,18 +1282,38 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // results of the segment
       if (cur.kind == SEG_QKV) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
-        for (int r = lane; r < cur.nrows; r += 64) st_coh(out + cur.row0 + r, sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
+        tag_q ^= 1u;
+        for (int r = lane; r < cur.nrows; r += 64) {
+          const float v = sk_row_sum(S.psum, r, cur.nseg, cur.nrows);
+          st_coh(out + cur.row0 + r, TAG ? sk_tagged(v, tag_q) : v);
+        }
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
-        if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
-        for (int r = 64 + lane; r < cur.nrows; r += 64)
-          st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
+        if (TAG) {
+          tag_h ^= 1u;
+          if (lane < cur.nrows) {
+            h_own = sk_untag(h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
+            st_coh(h + cur.row0 + lane, sk_tagged(h_own, tag_h));
+          }
+        } else {
+          if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
+          for (int r = 64 + lane; r < cur.nrows; r += 64)
+            st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
+        }
       } else if (cur.kind == SEG_GU) {
         float* z = p.z + (size_t)b * F;
+        tag_z ^= 1u;
         for (int r = lane; r < cur.nrows / 2; r += 64) {
           const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg, cur.nrows), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg, cur.nrows);
-          st_coh(z + cur.row0 / 2 + r, siluf(gt) * up);
+          const float v = siluf(gt) * up;
+          st_coh(z + cur.row0 / 2 + r, TAG ? sk_tagged(v, tag_z) : v);
         }
       } else {
+        // (tagged exchange: the residual rows of this workgroup also go out as plain values)
+        if (TAG && P.h_out != nullptr) {
+          SegDesc e{};
+          seg_split(e, D, D, share, 1);
+          if (lane < e.nrows) P.h_out[(size_t)b * D + e.row0 + lane] = h_own;
+        }
         float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
@@ -1087,7 +1332,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           st_coh(&dst->v, best.v); st_coh(&dst->i, best.i);
         }
       }
-      vm_wait_all();                               // the stores are complete before this workgroup arrives
+      if (!TAG || s == nsegs - 1) vm_wait_all();   // the stores are complete before this workgroup arrives at a barrier
       SK_STAMP(5);
     }
     if (P.share_time != nullptr && lane == 0) P.share_time[cu] = min(gu_ticks, 0xffffffu) | (bar.x << 24);
@@ -1105,6 +1350,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       if (lane == 0) {
         if (p.token_out) p.token_out[b] = bb.i;
         if (p.advance_len) p.len[b] = pos + 1;
+        if (TAG) {
+          int* ts = P.tagstate + 4 * b;
+          st_coh(ts, (int)tag_h); st_coh(ts + 1, (int)tag_q); st_coh(ts + 2, (int)tag_a); st_coh(ts + 3, (int)tag_z);
+        }
       }
     }
   } else {
@@ -1120,19 +1369,31 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       const SegDesc nxt = seg_desc(P, s + 1, nk, kept, share);
       const float* xsrc = cur.kind == SEG_DN ? S.zs : S.xs;
       if (cur.kind == SEG_O) {
-        lds_barrier();
-        if (uni(*S.flag) == 0) return;
+        if (!TAG) {
+          lds_barrier();
+          if (uni(*S.flag) == 0) return;
+        }
         // only the SK_PD_EARLY lower ring slots stay in flight across attention (it needs the
         // registers); the upper slots hold nothing here and are refilled right after
 #pragma unroll
         for (int j = SK_PD_EARLY; j < SK_PD; ++j)
 #pragma unroll
           for (int i = 0; i < 4; ++i) buf[j][i] = make_uint4(0, 0, 0, 0);
-        if (attn_wg) sk_attention<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit,
-                                      (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr);
+        unsigned long long* stamps = (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr;
+        if (TAG) {
+          tag_a ^= 1u;
+          if (attn_wg) {
+            if (!sk_attention<HD, SK_SWAVES, true>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, stamps, (int)tag_a)) return;
+          } else {
+            lds_barrier();
+            if (uni(*S.flag) == 0) return;
+          }
+        } else if (attn_wg) {
+          sk_attention<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, stamps);
+        }
 #pragma unroll
         for (int j = SK_PD_EARLY; j < SK_PD; ++j) sk_issue(cur, j, true, wave, buf[j]);
-        lds_barrier();
+        if (!TAG) lds_barrier();
       }
       lds_barrier();                               // input vector staged
       if (uni(*S.flag) == 0) return;
