@@ -366,7 +366,7 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.bar = c->d_bar; P.err = c->d_err; P.two_level = c->step_two_level;
   const bool tagged = c->step_tagged && c->d.d_model <= 64 * c->num_cu;       // (one residual row per service-wave lane)
   if (tagged) {
-    P.tagged = 1; P.tagstate = c->d_tagstate; P.h_out = c->d_h;
+    P.tagged = c->step_tagged; P.tagstate = c->d_tagstate; P.h_out = c->d_h;
     P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
   }
   P.shares = c->d_shares; P.share_time = c->step_balance ? c->d_share_time : nullptr;
@@ -866,9 +866,10 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
       c->batch_path = value; return FIRST_OK;
     case FIRST_OPT_STEP_BARRIER:
-      if (value < 0 || value > 2) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
-      c->step_tagged = value == 2;
+      if (value < 0 || value > 3) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
+      c->step_tagged = value == 2 ? 1 : value == 3 ? 2 : 0;
       if (value < 2) c->step_two_level = value;
+      if (value == 3) c->step_two_level = 1;
       drop_graphs(c);
       return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");

@@ -177,7 +177,9 @@ struct StepParams {
   const int* shares;           // [8] per-XCD share of the rows (1024 = equal), or null: even split
   unsigned* share_time;        // [grid] out: this workgroup's gate/up streaming time (100 MHz ticks), its XCD in the top byte
   int* err;                    // set to 1 if a barrier wait gives up
-  int tagged;                  // 1: activations are exchanged as self-validating words (see "Tagged exchange"), no grid barrier between phases
+  int tagged;                  // activations are exchanged as self-validating words (see "Tagged exchange"): 1: consumers poll
+                               // the words themselves, no grid barrier between phases; 2: a grid barrier tells them when to
+                               // read, and the arrival travels together with the stores instead of after them
   int* tagstate;               // [B][4] tag of the latest write to the h, qkv, attn and z vectors of each slot (tagged exchange)
   float* h_out;                // tagged exchange: [B][D] plain copy of the final hidden state (d.h then holds tagged words)
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
@@ -188,6 +190,7 @@ struct SkLds {
   float* xs;      // [max(D, Hq*hd)] activation vector of the running phase
   float* zs;      // [F] MLP activation for the down projection
   float* psum;    // [SK_PSUM]
+  float* gs;      // [min(pad(D), 4096)] RMSNorm gains of the next phase that has a norm, two-plane layout like xs
   float* red;     // [SK_WAVES + 8]
   float* qs;      // [G*hd] rotated, pre-scaled queries of this workgroup's KV head
   float* knew;    // [hd]
@@ -201,7 +204,8 @@ struct SkLds {
 __host__ __device__ inline size_t sk_lds_floats(int D, int nq, int F, int G, int hd) {
   const int xs = (D > nq ? D : nq) == 0 ? 0 : ((D > nq ? D : nq) + 2047) / 2048 * 2048;     // staged vectors are padded to whole segments
   F = (F + 2047) / 2048 * 2048;
-  return (size_t)xs + F + SK_PSUM + (SK_WAVES + 8) + (size_t)G * hd + 2 * hd + hd + SK_WAVES * 64 +
+  const int gs = ((D + 2047) / 2048 * 2048) < 4096 ? ((D + 2047) / 2048 * 2048) : 4096;
+  return (size_t)xs + F + SK_PSUM + gs + (SK_WAVES + 8) + (size_t)G * hd + 2 * hd + hd + SK_WAVES * 64 +
          (size_t)SK_WAVES * (hd + 2) + 4;
 }
 
@@ -211,6 +215,7 @@ __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int
   s.xs = base; base += xs;
   s.zs = base; base += (F + 2047) / 2048 * 2048;
   s.psum = base; base += SK_PSUM;
+  s.gs = base; base += ((D + 2047) / 2048 * 2048) < 4096 ? ((D + 2047) / 2048 * 2048) : 4096;
   s.red = base; base += SK_WAVES + 8;
   s.qs = base; base += G * hd;
   s.knew = base; base += hd;
@@ -336,6 +341,9 @@ __device__ __forceinline__ void sk_bar_init(SkBar& B, unsigned* bar, int* err, i
   }
 }
 
+__device__ __forceinline__ void grid_arrive(SkBar& B, unsigned& old);
+__device__ __forceinline__ int grid_wait(SkBar& B, unsigned epoch, unsigned& old);
+
 __device__ __forceinline__ int grid_sync(SkBar& B, unsigned epoch, int cu, int ncu) {
   const int lane = threadIdx.x & 63;
   if (!B.two_level || epoch == 1) {
@@ -346,13 +354,31 @@ __device__ __forceinline__ int grid_sync(SkBar& B, unsigned epoch, int cu, int n
     }
     return ok;
   }
-  const unsigned k = epoch - 1;
+  unsigned old = 0;
+  grid_arrive(B, old);
+  return grid_wait(B, epoch, old);
+}
+
+// The two halves of the two-level barrier (epoch > 1).  grid_arrive only requests the count
+// of this workgroup's arrival; `old` is defined after grid_wait has waited for it.  Stores
+// issued between the two travel concurrently with the arrival (useful only when readers can
+// tell on their own whether what they read is current, as with tagged words).
+__device__ __forceinline__ void grid_arrive(SkBar& B, unsigned& old) {
   unsigned* cnt = B.xbase + (SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
+  // Only lane 0 adds, selected inside the statement: for the compiler every lane's `old` is
+  // defined here, so it has no reason to copy the register before the value has landed.
+  unsigned long long exec_save;
+  asm volatile("s_mov_b64 %1, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add %0, %2, %3, off sc0\n\ts_mov_b64 exec, %1"
+               : "=v"(old), "=&s"(exec_save) : "v"(cnt), "v"(1u) : "memory");
+}
+
+__device__ __forceinline__ int grid_wait(SkBar& B, unsigned epoch, unsigned& old) {
+  const int lane = threadIdx.x & 63;
+  const unsigned k = epoch - 1;
   unsigned* pub = B.xbase + (2 * SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
-  if (lane == 0) {
-    const unsigned old = sk_l2_add_ret(cnt, 1u);
-    if (old + 1u == B.my_n * k) __hip_atomic_store(pub, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  coh_wait();
+  coh_use(old);
+  if (lane == 0 && old + 1u == B.my_n * k) __hip_atomic_store(pub, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const unsigned* f = B.xbase + (2 * SK_XCD_SLOTS + (lane & (SK_XCD_SLOTS - 1))) * SK_XCD_STRIDE;
   const bool need = B.n_lane != 0;
   coh_wait();
@@ -399,16 +425,34 @@ __device__ __forceinline__ void sk_zero_pad(float* xs, int K) {
   }
 }
 
-// RMSNorm gains of a vector of at most 4096 elements, 8 groups of 8 per lane.  They are
-// constants, so the service wave fetches them before it waits at the grid barrier.
-struct SkGains { f32x4_t a[8], b[8]; };
-__device__ __forceinline__ void sk_load_gains(SkGains& G, const float* gain, int K) {
-  const int lane = threadIdx.x & 63, ngroups = K >> 3;
+// A lane index the compiler cannot prove loop-invariant: address arithmetic that depends on it
+// is redone (a few ALU operations) where it is used, instead of being computed once before the
+// phase loop and then spilled to scratch memory for lack of registers.
+__device__ __forceinline__ int sk_lane_opaque() {
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));
+  return lane;
+}
+
+// RMSNorm gains of a vector of at most 4096 elements into LDS, in the two-plane layout of the
+// staged vectors.  They are constants: the service wave fetches them while the phase before
+// streams, so that nothing stands between the arrival of a phase's input and its staging.
+__device__ __forceinline__ void sk_gains_to_lds(float* gs, const float* gain, int K) {
+  const int lane = sk_lane_opaque(), ngroups = K >> 3, plane = sk_plane(K);
+  f32x4_t a[8], b[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int k = min(i * 64 + lane, ngroups - 1) << 3;
-    G.a[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k));
-    G.b[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k + 4));
+    a[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k));
+    b[i] = *as_global(reinterpret_cast<const f32x4_t*>(gain + k + 4));
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int g = i * 64 + lane;
+    if (g < ngroups) {
+      *reinterpret_cast<f32x4_t*>(gs + (g << 2)) = a[i];
+      *reinterpret_cast<f32x4_t*>(gs + plane + (g << 2)) = b[i];
+    }
   }
 }
 
@@ -417,9 +461,9 @@ __device__ __forceinline__ void sk_load_gains(SkGains& G, const float* gain, int
 // TAG: x holds tagged words; the batch is re-read until every word carries tag `bit`
 // (returns false if that wait gives up).
 template <bool TAG>
-__device__ __forceinline__ bool sk_stage_norm_wave(float* xs, const float* x, int K, const SkGains& G, float eps,
+__device__ __forceinline__ bool sk_stage_norm_wave(float* xs, const float* x, int K, const float* gs, float eps,
                                                    unsigned bit, int* err) {
-  const int lane = threadIdx.x & 63, ngroups = K >> 3;
+  const int lane = sk_lane_opaque(), ngroups = K >> 3;
   f32x4_t a[8], b[8];
   unsigned spins = 0;
   for (;;) {
@@ -457,8 +501,10 @@ __device__ __forceinline__ bool sk_stage_norm_wave(float* xs, const float* x, in
   for (int i = 0; i < 8; ++i) {
     const int g = i * 64 + lane;
     if (g < ngroups) {
-      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i] * G.a[i] * r;
-      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b[i] * G.b[i] * r;
+      const f32x4_t ga = *reinterpret_cast<const f32x4_t*>(gs + (g << 2));
+      const f32x4_t gb = *reinterpret_cast<const f32x4_t*>(gs + plane + (g << 2));
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a[i] * ga * r;
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b[i] * gb * r;
     }
   }
   sk_zero_pad(xs, K);
@@ -473,7 +519,7 @@ template <bool TAG>
 __device__ __forceinline__ bool sk_stage_wave(float* xs, const float* x, int K, const float* gain, float eps,
                                               unsigned bit, int* err) {
   constexpr int NB = 8;
-  const int lane = threadIdx.x & 63;
+  const int lane = sk_lane_opaque();
   const int ngroups = K >> 3, plane = sk_plane(K);
   float ss = 0.f;
   unsigned spins = 0;
@@ -532,7 +578,7 @@ __device__ __forceinline__ bool sk_stage_wave(float* xs, const float* x, int K, 
 // norm: one batch of coherent loads.  Executed by the service wave.  TAG as above.
 template <bool TAG>
 __device__ __forceinline__ bool sk_stage_segments(float* xs, const float* x, int K, int c0, int c1, unsigned bit, int* err) {
-  const int lane = threadIdx.x & 63;
+  const int lane = sk_lane_opaque();
   const int g_begin = c0 * (SK_SEG / 8), g_pad = c1 * (SK_SEG / 8), g_end = min(g_pad, K >> 3), plane = sk_plane(K);
   f32x4_t a[8], b[8];
   unsigned spins = 0;
@@ -1029,7 +1075,7 @@ __device__ __forceinline__ bool sk_attn_prologue_tagged(const StepParams& P, bf1
   constexpr int HALF = HD / 2;
   constexpr int NQ = (SK_SWAVES * HALF + 63) / 64;      // q pairs per lane (up to SK_SWAVES query heads per KV head)
   constexpr int NV = (HD + 63) / 64;
-  const int b = p.b, G = p.G, Pg = p.P, lane = threadIdx.x & 63;
+  const int b = p.b, G = p.G, Pg = p.P, lane = sk_lane_opaque();
   const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps);
@@ -1141,7 +1187,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   }
   share.w0 = uni(share.w0); share.w1 = uni(share.w1);
   SkBar bar;
-  if (service) sk_bar_init(bar, P.bar, P.err, ncu, TAG ? 0 : P.two_level);
+  const bool detect = TAG && P.tagged == 2;       // tagged words plus a grid barrier as the "ready" signal
+  if (service) sk_bar_init(bar, P.bar, P.err, ncu, TAG && !detect ? 0 : P.two_level);
   float* h = p.h + (size_t)b * D;
   // tagged exchange: tags of the latest writes of h, qkv, attn and z (the same in every wave of
   // the grid: each flips when the phase that writes the vector begins)
@@ -1216,29 +1263,39 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   // The two roles run separate loops (so that the service wave carries no ring registers and
   // the streaming waves no staging registers) with the same sequence of workgroup barriers.
   if (service) {
+#ifdef SK_SERVICE_PRIO
+    __builtin_amdgcn_s_setprio(SK_SERVICE_PRIO);
+#endif
     lds_barrier();                                 // every wave's stores of the embedding are complete (and the rotation table)
     unsigned gu_ticks = 0;
+    bool sync_ok = true;                           // tagged exchange with barrier: verdict of the latest grid barrier
+    // RMSNorm gains of the next phase that has a norm: constants, fetched while the phase before
+    // streams so that they are not in the way when the phase's input arrives
+    {
+      const SegDesc first = seg_desc(P, 0, nk, kept, share);
+      if (first.gain != nullptr && D <= 4096) sk_gains_to_lds(S.gs, first.gain, D);
+    }
     for (int s = 0; s < nsegs; ++s) {
       const SegDesc cur = seg_desc(P, s, nk, kept, share);
       SK_STAMP(0);
-      SkGains gains;
       const bool fast_norm = cur.gain != nullptr && D <= 4096;
-      if (fast_norm) sk_load_gains(gains, cur.gain, D);
       if (!TAG) SK_GRID_SYNC_TRACED();             // everything the segment reads has been written
+      else if (detect && s == 0) sync_ok = grid_sync(bar, ++epoch, cu, ncu) != 0;
       SK_STAMP(1);
-      bool staged_ok = true;
+      bool staged_ok = sync_ok;
       if (cur.kind == SEG_O) {
         if (TAG) {
           tag_a ^= 1u;
           // q, k, v of this workgroup's KV head into LDS as soon as they are current
           bool ok = true;
           if (attn_wg) ok = sk_attn_prologue_tagged<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, tag_q);
-          if (lane == 0) *S.flag = ok ? 1 : 0;
+          if (lane == 0) *S.flag = ok && sync_ok ? 1 : 0;
           lds_barrier();
           if (uni(*S.flag) == 0) return;
           if (attn_wg) { lds_barrier(); lds_barrier(); lds_barrier(); }
+          if (detect) sync_ok = grid_sync(bar, ++epoch, cu, ncu) != 0;     // (the merging waves did not wait for their stores)
           SK_STAMP(2);
-          staged_ok = sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err);
+          staged_ok = sync_ok && sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err);
         } else {
           lds_barrier();
           if (uni(*S.flag) == 0) return;
@@ -1251,12 +1308,12 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       } else if (cur.kind == SEG_DN) {
         // the down projection starts on the first K-segment of its input; the rest is staged
         // while it streams (after the workgroup barrier below)
-        staged_ok = sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err);
+        staged_ok = sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err) && staged_ok;
         __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       } else if (fast_norm) {
-        staged_ok = sk_stage_norm_wave<TAG>(S.xs, h, D, gains, p.eps, tag_h, P.err);
+        staged_ok = sk_stage_norm_wave<TAG>(S.xs, h, D, S.gs, p.eps, tag_h, P.err) && staged_ok;
       } else {
-        staged_ok = sk_stage_wave<TAG>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err);
+        staged_ok = sk_stage_wave<TAG>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err) && staged_ok;
       }
       if (TAG && lane == 0) *S.flag = staged_ok ? 1 : 0;
       SK_STAMP(3);
@@ -1276,9 +1333,18 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           __hip_atomic_store(S.flag + 2, c1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
       }
+      if (s + 1 < nsegs && D <= 4096) {            // (this phase's staging has read S.gs already)
+        const float* next_gain = seg_desc(P, s + 1, nk, kept, share).gain;
+        if (next_gain != nullptr) sk_gains_to_lds(S.gs, next_gain, D);
+      }
       lds_barrier();                               // partial sums complete
       if (timed) gu_ticks += (unsigned)(wall_clock64() - t_stream);
       SK_STAMP(4);
+      // tagged exchange with barrier: the arrival is requested before the results are stored
+      // and awaited after, so the two travel together
+      const bool arrive = detect && s + 1 < nsegs;
+      unsigned arrived = 0;
+      if (arrive && bar.two_level) grid_arrive(bar, arrived);
       // results of the segment
       if (cur.kind == SEG_QKV) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
@@ -1333,6 +1399,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
       }
       if (!TAG || s == nsegs - 1) vm_wait_all();   // the stores are complete before this workgroup arrives at a barrier
+      if (arrive) sync_ok = (bar.two_level ? grid_wait(bar, ++epoch, arrived) : grid_sync(bar, ++epoch, cu, ncu)) != 0;
       SK_STAMP(5);
     }
     if (P.share_time != nullptr && lane == 0) P.share_time[cu] = min(gu_ticks, 0xffffffu) | (bar.x << 24);
