@@ -68,9 +68,10 @@ extern "C" {
 #define FIRST_OPT_STEP_BARRIER  5  /* how the workgroups of the persistent kernel hand activations on between
                                       phases.  2 (default): no grid barrier; every exchanged 32-bit word carries an
                                       alternating tag in its lowest mantissa bit and consumers re-read until all
-                                      words are current.  1: grid barrier, workgroups of one XCD count arrivals in
-                                      their shared L2 and the last one publishes one flag per XCD; 0: grid barrier,
-                                      every workgroup publishes a flag and polls all of them */
+                                      words are current.  3: tagged words as in 2, plus the grid barrier of 1 as
+                                      the signal to read them.  1: grid barrier, workgroups of one XCD count arrivals
+                                      in their shared L2 and the last one publishes one flag per XCD; 0: grid
+                                      barrier, every workgroup publishes a flag and polls all of them */
 
 typedef struct first_ctx first_ctx;
 

@@ -60,9 +60,12 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
     mask = make_skip_mask(desc.n_layers, 1 if desc.n_layers > 2 else 0, 43).tolist()
     inputs = [[int(t)] for t in make_prompt(desc.vocab, 24, 44)]
     runs = {}
-    for name, path, graph, barrier, balance in (("ops", 0, 1, 1, 1), ("step", 1, 1, 1, 1), ("step_again", 1, 1, 1, 1),
-                                                ("step_eager", 1, 0, 1, 1), ("step_flat_barrier", 1, 1, 0, 1),
-                                                ("step_even_split", 1, 1, 1, 0)):
+    # exchange kinds (option STEP_BARRIER): 2 tagged words (default), 3 tagged words + grid barrier,
+    # 1 two-level grid barrier, 0 flat grid barrier
+    for name, path, graph, barrier, balance in (("ops", 0, 1, 2, 0), ("step", 1, 1, 2, 0), ("step_again", 1, 1, 2, 0),
+                                                ("step_eager", 1, 0, 2, 0), ("step_shares", 1, 1, 2, 1),
+                                                ("tagged_barrier", 1, 1, 3, 0), ("two_level", 1, 1, 1, 0),
+                                                ("flat", 1, 1, 0, 0), ("two_level_shares", 1, 1, 1, 1)):
         desc, w, router, ctx = build(model, 43, max_seq_len=200)
         ctx.set_option(OPT_DECODE_PATH, path)
         ctx.set_option(1, graph)
@@ -74,15 +77,49 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
         h = ctx.get_hidden().cpu()
         runs[name] = (lg, tk, h)
         ctx.close()
-    assert torch.equal(runs["step"][0], runs["step_again"][0]) and torch.equal(runs["step"][1], runs["step_again"][1])
-    assert torch.equal(runs["step"][0], runs["step_eager"][0])
+
+    def same(a, b):
+        return torch.equal(runs[a][0], runs[b][0]) and torch.equal(runs[a][1], runs[b][1]) and torch.equal(runs[a][2], runs[b][2])
+
+    assert same("step", "step_again") and same("step", "step_eager")
     # who owns which weight rows (the shares move with the measured streaming times) changes no arithmetic
-    assert torch.equal(runs["step"][0], runs["step_even_split"][0]) and torch.equal(runs["step"][1], runs["step_even_split"][1])
-    # the kind of grid barrier changes no arithmetic
-    assert torch.equal(runs["step"][0], runs["step_flat_barrier"][0]) and torch.equal(runs["step"][1], runs["step_flat_barrier"][1])
+    assert same("step", "step_shares") and same("two_level", "two_level_shares")
+    # how readiness is detected changes no arithmetic: the two tagged kinds agree, and so do the two barriers
+    assert same("step", "tagged_barrier") and same("two_level", "flat")
+    # tagged words drop the last mantissa bit of the exchanged activations (relative 2^-23)
+    scale = float(runs["two_level"][0].abs().max())
+    assert float((runs["step"][0] - runs["two_level"][0]).abs().max()) <= 2e-5 * scale
     # same arithmetic up to fp32 summation order
     assert float((runs["step"][0] - runs["ops"][0]).abs().max()) <= 3e-3   # a new K/V may round to the neighbouring bf16
     assert float((runs["step"][2] - runs["ops"][2]).abs().max()) <= 3e-3 * float(runs["ops"][2].abs().max())
+
+
+def test_step_kernel_alternating_with_the_per_op_kernels_and_new_sequences():
+    """The tagged exchange keeps state from launch to launch (the tags of the latest writes).  Steps of
+    the per-op kernels in between, a new prefill and a different mask must not disturb it."""
+    model = "step_hd128"
+    desc = CONFIGS[model]
+    prompt = make_prompt(desc.vocab, 90, 61)
+    inputs = [[int(t)] for t in make_prompt(desc.vocab, 18, 62)]
+    masks = [make_skip_mask(desc.n_layers, 1, 61).tolist(), [1] * desc.n_layers]
+
+    def run(paths):
+        desc_, w, router, ctx = build(model, 61, max_seq_len=160)
+        out = []
+        for mask in masks:                              # second round: new sequence in the same context
+            _prefill(ctx, desc_, [prompt])
+            ctx.set_mask(0, mask)
+            for i, tok in enumerate(inputs):
+                ctx.set_option(OPT_DECODE_PATH, paths[i % len(paths)])
+                lg, tk = _decode(ctx, desc_, [tok])
+                out.append(lg[0, 0].clone())
+        ctx.close()
+        return torch.stack(out)
+
+    mixed, only_step, only_ops = run([1, 1, 0, 1, 0, 0, 1]), run([1]), run([0])
+    assert float((only_step - only_ops).abs().max()) <= 3e-3
+    assert float((mixed - only_ops).abs().max()) <= 3e-3
+    assert float((mixed - only_step).abs().max()) <= 3e-3
 
 
 def test_step_kernel_all_skip_leaves_hidden_bit_identical_and_kv_untouched():
