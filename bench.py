@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--per-op", action="store_true", help="one kernel per fused op instead of the persistent kernel")
+    ap.add_argument("--sample", action="store_true",
+                    help="also time the headline mask with the paper's decoding rule (temperature 0.8, top-k 10) instead of greedy")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -108,6 +110,27 @@ def main():
                       "ms_per_step": ms, "step_bytes": by,
                       "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)})
     head = min(sweep, key=lambda r: abs(r["skip_fraction"] - args.headline_skip))
+
+    sampled = None
+    if args.sample:
+        # same mask, each step followed by first_sample_top_k on its logits; the sampled token feeds the next step
+        k = L - head["kept_layers"]
+        gen = torch.Generator(device="cpu").manual_seed(seed)
+        uni = torch.rand(W + K, generator=gen).cuda()
+        scratch = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ctx.prefill_route(prompt, [n_prompt], token=tok)
+        ctx.set_mask(0, [0] * L if k >= L else make_skip_mask(L, k, seed).tolist())
+        for i in range(W + K):
+            if i == W:
+                ctx.sync()
+                ev0.record(stream)
+            ctx.decode_step(tok, logits, scratch)
+            ctx.sample_top_k(logits, uni[i:i + 1], 0.8, 10, tok)
+        ev1.record(stream)
+        ev1.synchronize()
+        ms = ev0.elapsed_time(ev1) / K
+        sampled = {"temperature": 0.8, "top_k": 10, "kept_layers": head["kept_layers"], "ms_per_step": ms,
+                   "tokens_per_s": 1000.0 / ms, "greedy_ms_per_step": head["ms_per_step"]}
 
     # Dominant kernel.  With the persistent path the whole step is ONE kernel (k_step), so its
     # launch duration is the step time measured above with events on the library's stream;
@@ -171,6 +194,7 @@ def main():
                    "decode_path": "per-op kernels" if args.per_op else "persistent kernel"},
         "hbm_roofline_frac_step": head["hbm_frac"],
         "sweep": sweep,
+        "sampled_decode": sampled,
         "prefill": {"tokens": n_prompt, "ms": prefill_ms,
                     "tflops": (2.0 * n_prompt * L * desc.layer_params + 2.0 * desc.vocab * desc.d_model)
                               / (prefill_ms * 1e-3) / 1e12},

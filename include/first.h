@@ -155,6 +155,22 @@ int first_get_kept(first_ctx *ctx, int32_t seq, int32_t *kept_idx, int32_t *n_ke
 int first_decode_step(first_ctx *ctx, const int32_t *last_tokens, float *logits_out,
                       int32_t *token_out);
 
+/* The decoding rule the paper times (Appendix, "Inference settings": temperature 0.8, top-k sampling
+ * over 10 tokens) applied to the logits of the live sequences, e.g. those first_decode_step or
+ * first_prefill_route just wrote: the candidates of a sequence are its top_k largest logits (equal
+ * logits in order of token index), their weights exp((l - l_max) / temperature) are summed in
+ * descending-logit order in fp32, and the token returned is the first candidate whose cumulative
+ * weight exceeds u * total.  The draws are the caller's: the library owns no random number generator.
+ *   logits         DEV fp32  [B, V]      B = number of live sequences
+ *   uniforms       DEV fp32  [B]         one number in [0, 1) per sequence
+ *   temperature    > 0;  1 <= top_k <= 64
+ *   token_out      DEV int32 [B]         may be the buffer the next first_decode_step reads
+ *   candidates_out DEV int32 [B, top_k]  the candidates in order, -1 beyond the vocabulary (may be NULL)
+ * Enqueued on the context's stream.  FIRST_ERR_ARG on null pointers or parameters out of range,
+ * FIRST_ERR_STATE when no sequence is live; nothing is written on error. */
+int first_sample_top_k(first_ctx *ctx, const float *logits, const float *uniforms, float temperature,
+                       int32_t top_k, int32_t *token_out, int32_t *candidates_out);
+
 int first_set_option(first_ctx *ctx, int32_t option, int32_t value);
 int first_sync(first_ctx *ctx);                          /* hipStreamSynchronize of the stream */
 const char *first_last_error(const first_ctx *ctx);      /* ctx may be NULL: last create error */

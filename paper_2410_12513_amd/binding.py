@@ -14,7 +14,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
-           "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order",
+           "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
            "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len"]
 
 
@@ -203,6 +203,17 @@ class FirstContext:
 
     def set_seq_len(self, seq: int, length: int) -> None:
         self._chk(self.lib.first_set_seq_len(self.h, C.c_int32(seq), C.c_int32(length)))
+
+    def sample_top_k(self, logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, top_k: int,
+                     token_out: torch.Tensor, candidates_out: Optional[torch.Tensor] = None) -> None:
+        B = self.batch()
+        _check_dev(logits, torch.float32, "logits", B * self.desc.vocab)
+        _check_dev(uniforms, torch.float32, "uniforms", B)
+        _check_dev(token_out, torch.int32, "token_out", B)
+        if candidates_out is not None:
+            _check_dev(candidates_out, torch.int32, "candidates_out", B * top_k)
+        self._chk(self.lib.first_sample_top_k(self.h, _ptr(logits), _ptr(uniforms), C.c_float(temperature),
+                                              C.c_int32(top_k), _ptr(token_out), _ptr(candidates_out)))
 
     def get_hidden(self) -> torch.Tensor:
         out = torch.empty((self.batch(), self.desc.d_model), dtype=torch.float32, device="cuda")

@@ -14,6 +14,7 @@
 #include "prefill_kernels.h"
 #include "step_kernel.h"
 #include "decode_batch_kernels.h"
+#include "sample_kernels.h"
 
 using namespace first;
 
@@ -53,6 +54,7 @@ struct first_ctx {
   double* d_theta = nullptr;
   float *d_h = nullptr, *d_qkv = nullptr, *d_attn = nullptr, *d_z = nullptr, *d_part_o = nullptr, *d_part_ml = nullptr;
   unsigned *d_attn_cnt = nullptr, *d_head_cnt = nullptr;
+  Cand* d_topk_part = nullptr;            // [max_batch][chunks][SMP_KMAX] per-chunk candidates of first_sample_top_k
   float2* d_rope_cs = nullptr;
   Best* d_arg_part = nullptr;
   // prefill workspace
@@ -623,6 +625,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
   }
   A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
+  A(dev_alloc(c, &c->d_topk_part, (size_t)B * ((d.vocab + SMP_CHUNK - 1) / SMP_CHUNK) * SMP_KMAX));
   A(dev_alloc(c, &c->x_h, (size_t)B * d.d_model)); A(dev_alloc(c, &c->x_qkv, (size_t)B * (c->nq + 2 * c->nkv)));
   A(dev_alloc(c, &c->x_attn, (size_t)B * c->nq)); A(dev_alloc(c, &c->x_z, (size_t)B * d.d_ffn));
   A(dev_alloc(c, &c->d_tagstate, (size_t)B * 4));
@@ -833,6 +836,21 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
     HIPCHK(c, hipGraphLaunch(it->second, c->stream));
   }
   for (int b = 0; b < c->B; ++b) { c->hlen[b] += 1; c->decoded[b] = 1; }
+  return FIRST_OK;
+}
+
+int first_sample_top_k(first_ctx* c, const float* logits, const float* uniforms, float temperature, int32_t top_k,
+                       int32_t* token_out, int32_t* candidates_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!logits || !uniforms || !token_out) return fail(c, FIRST_ERR_ARG, "first_sample_top_k: null pointer");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(c, FIRST_ERR_ARG, "first_sample_top_k: temperature must be positive");
+  if (top_k < 1 || top_k > SMP_KMAX) return fail(c, FIRST_ERR_ARG, "first_sample_top_k: top_k must be in 1..64");
+  if (c->B < 1) return fail(c, FIRST_ERR_STATE, "first_sample_top_k: no live sequence");
+  const int chunks = (c->d.vocab + SMP_CHUNK - 1) / SMP_CHUNK;
+  hipLaunchKernelGGL(k_topk_part, dim3(chunks, c->B), dim3(SMP_THREADS), 0, c->stream, logits, c->d.vocab, top_k, c->d_topk_part);
+  hipLaunchKernelGGL(k_topk_sample, dim3(c->B), dim3(SMP_THREADS), 0, c->stream, c->d_topk_part, chunks * top_k, top_k,
+                     temperature, uniforms, token_out, candidates_out);
+  HIPCHK(c, hipGetLastError());
   return FIRST_OK;
 }
 
