@@ -89,26 +89,31 @@ __global__ void __launch_bounds__(WG) k_attn_b(BatchParams P) {
 
 // Decode attention of (split, KV head, slot) with the persistent kernel's attention phase
 // (register-resident 64-key tiles, page lookups batched per tile): SK_WAVES worker waves (query
-// heads x key groups) + one wave that only keeps step with the workgroup barriers.  Needs
-// 16-token pages and G <= SK_WAVES.
-constexpr int AT_THREADS = (SK_WAVES + 1) * 64;
+// heads x key groups).  A workgroup's life is a chain of memory round trips (q/k/v, key tile,
+// value tile, partial, count, merge), so two workgroups share a compute unit (at most 128
+// registers per lane).  Needs 16-token pages and G <= SK_WAVES.
+constexpr int AT_THREADS = SK_WAVES * 64;
 template <int HD>
-__global__ void __launch_bounds__(AT_THREADS) k_attn_tiles_b(BatchParams P) {
+__global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
   extern __shared__ __align__(16) float smem_f[];
   StepParams SP{};
   SP.d = P.d;
   SP.d.b = P.seqs.id[blockIdx.z];
   const DecParams& p = SP.d;
   const SkLds S = sk_carve(smem_f, 0, 0, 0, p.G, HD);
-  const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6));
+  const int tid = threadIdx.x;
   const int pos = uni(p.len[p.b]);
+  // The grid is sized for the longest sequence; a shorter one uses only as many splits as give
+  // every worker wave a 64-key tile, and the workgroups of its other splits leave at once.
+  const int tiles = (pos + 64) >> 6, nkg = max(1, SK_WAVES / p.G);
+  const int nsplit = max(1, min((int)gridDim.x, (tiles + nkg - 1) / nkg));
+  if ((int)blockIdx.x >= nsplit) return;
   for (int i = tid; i < HD / 2; i += AT_THREADS) {
     const double a = (double)pos * p.theta[i];
     S.cs[i] = make_float2((float)cos(a), (float)sin(a));
   }
   lds_barrier();
-  if (wave == SK_WAVES) sk_attention_service();
-  else sk_attention<HD, SK_WAVES>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, gridDim.x, nullptr);
+  sk_attention<HD, SK_WAVES>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
 }
 
 // Re-lays a row-major bf16 matrix W[N][K] into MFMA tile order: block (t, s) = rows 16 t .. +16,
