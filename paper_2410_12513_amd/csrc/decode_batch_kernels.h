@@ -26,9 +26,9 @@ struct SeqList {
 struct BatchParams {
   DecParams d;          // geometry, per-sequence state, layer pointers (d.b unused)
   SeqList seqs;         // sequences of this pass; slot j <-> sequence seqs.id[j]
-  bf16* xh;             // [BATCH_SLOTS][xpitch] high halves of the op's input vectors
-  bf16* xl;             // [BATCH_SLOTS][xpitch] low halves
-  bf16* zh;             // [BATCH_SLOTS][xpitch] MLP activation (written by gate/up, read by down), high halves
+  bf16* xh;             // [BATCH_SLOTS * xpitch] high halves of the op's input vectors, A-operand order (bg_aidx)
+  bf16* xl;             // low halves
+  bf16* zh;             // MLP activation (written by gate/up, read by down), high halves, same order
   bf16* zl;             //                       low halves
   float* rinv;          // [BATCH_SLOTS] 1/rms of the vector that was split last (norm ops)
   int xpitch;
@@ -36,6 +36,14 @@ struct BatchParams {
   // optional copies of the layer's matrices (and of the LM head) in MFMA tile order, see k_tile_weights
   const bf16 *t_qkv, *t_o, *t_g, *t_u, *t_d, *t_head;
 };
+
+// The split activation vectors of the (up to) 16 sequences of a pass are kept in the order the
+// MFMA A operand wants them: block s = elements 32 s .. 32 s + 31 of all 16 slots is 1 KB, lane
+// l = slot + 16 g of a wave owns its 16 bytes l (slot's elements 32 s + 8 g .. + 8).  One A load
+// of a wave is then 1 KB contiguous instead of sixteen 64-byte pieces one vector pitch apart.
+__host__ __device__ __forceinline__ size_t bg_aidx(int slot, int k) {
+  return ((size_t)(k >> 5) << 9) + (size_t)((((k >> 3) & 3) << 4) + slot) * 8 + (k & 7);
+}
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v_t;
@@ -54,8 +62,8 @@ __global__ void __launch_bounds__(WG) k_xsplit(BatchParams P, int src, int K, in
   const DecParams& p = P.d;
   const int j = blockIdx.x, b = P.seqs.id[j];
   const float* x = src == 0 ? p.h + (size_t)b * p.D : p.attn + (size_t)b * p.Hq * p.hd;
-  bf16* xh = P.xh + (size_t)j * P.xpitch;
-  bf16* xl = P.xl + (size_t)j * P.xpitch;
+  bf16* xh = P.xh;
+  bf16* xl = P.xl;
   if (gain && blockIdx.y == 0) {
     float ss = 0.f;
     for (int k = threadIdx.x; k < K; k += WG) { const float v = x[k]; ss = fmaf(v, v, ss); }
@@ -67,8 +75,8 @@ __global__ void __launch_bounds__(WG) k_xsplit(BatchParams P, int src, int K, in
     float v = x[k];
     if (gain) v *= gain[k];
     const bf16 hi = from_f32<bf16>(v);
-    xh[k] = hi;
-    xl[k] = from_f32<bf16>(v - to_f32(hi));
+    xh[bg_aidx(j, k)] = hi;
+    xl[bg_aidx(j, k)] = from_f32<bf16>(v - to_f32(hi));
   }
 }
 
@@ -194,8 +202,8 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
       else w[t] = bg_row_ptr<MODE>(p, rowc, K, 0);
     }
   }
-  const bf16* xh = (MODE == BG_DN ? P.zh : P.xh) + (size_t)n * P.xpitch;
-  const bf16* xl = (MODE == BG_DN ? P.zl : P.xl) + (size_t)n * P.xpitch;
+  const bf16* xh = (MODE == BG_DN ? P.zh : P.xh) + lane * 8;       // this lane's 16 bytes of block 0 (bg_aidx)
+  const bf16* xl = (MODE == BG_DN ? P.zl : P.xl) + lane * 8;
 
   f32x4v_t acc[NS];
 #pragma unroll
@@ -216,8 +224,8 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
       const int k = ((sc + u) << 5) + (g << 3);
 #pragma unroll
       for (int i = 0; i < NS; ++i) c.wv[u][i] = ld_stream16(TILED ? w[i] + (size_t)(sc + u) * 512 : w[i] + k);
-      c.a_h[u] = *reinterpret_cast<const uint4*>(xh + k);
-      c.a_l[u] = *reinterpret_cast<const uint4*>(xl + k);
+      c.a_h[u] = *reinterpret_cast<const uint4*>(xh + ((size_t)(sc + u) << 9));
+      c.a_l[u] = *reinterpret_cast<const uint4*>(xl + ((size_t)(sc + u) << 9));
     }
   };
   auto mma = [&](const Chunk& c) {
@@ -251,8 +259,8 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
 #pragma unroll
     for (int i = 0; i < NS; ++i) wv[i] = ah4;
     if (k < K) {
-      ah4 = *reinterpret_cast<const uint4*>(xh + k);
-      al4 = *reinterpret_cast<const uint4*>(xl + k);
+      ah4 = *reinterpret_cast<const uint4*>(xh + ((size_t)s << 9));
+      al4 = *reinterpret_cast<const uint4*>(xl + ((size_t)s << 9));
 #pragma unroll
       for (int i = 0; i < NS; ++i) wv[i] = *reinterpret_cast<const uint4*>(TILED ? w[i] + (size_t)s * 512 : w[i] + k);
     }
@@ -296,8 +304,8 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
         const float r = P.rinv[slot];
         const float z = siluf(acc[2 * t][j] * r) * (acc[2 * t + 1][j] * r);
         const bf16 hi = from_f32<bf16>(z);
-        P.zh[(size_t)slot * P.xpitch + row] = hi;              // input of the down projection, already split
-        P.zl[(size_t)slot * P.xpitch + row] = from_f32<bf16>(z - to_f32(hi));
+        P.zh[bg_aidx(slot, row)] = hi;                         // input of the down projection, already split
+        P.zl[bg_aidx(slot, row)] = from_f32<bf16>(z - to_f32(hi));
       } else {
         P.logits_all[(size_t)b * N + row] = acc[t][j] * P.rinv[slot];
       }
