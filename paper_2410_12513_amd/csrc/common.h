@@ -78,4 +78,13 @@ __device__ __forceinline__ bool better(const Best& a, const Best& b) {
   return a.v > b.v || (a.v == b.v && a.i < b.i);
 }
 
+// The split activation vectors of the (up to) 16 sequences of a pass are kept in the order the
+// MFMA A operand wants them: block s = elements 32 s .. 32 s + 31 of all 16 slots is 1 KB, lane
+// l = slot + 16 g of a wave owns its 16 bytes l (slot's elements 32 s + 8 g .. + 8).  One A load
+// of a wave is then 1 KB contiguous instead of sixteen 64-byte pieces one vector pitch apart.
+__host__ __device__ __forceinline__ size_t bg_aidx(int slot, int k) {
+  return ((size_t)(k >> 5) << 9) + (size_t)((((k >> 3) & 3) << 4) + slot) * 8 + (k & 7);
+}
+
+
 }  // namespace first

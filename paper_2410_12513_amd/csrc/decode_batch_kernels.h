@@ -37,14 +37,6 @@ struct BatchParams {
   const bf16 *t_qkv, *t_o, *t_g, *t_u, *t_d, *t_head;
 };
 
-// The split activation vectors of the (up to) 16 sequences of a pass are kept in the order the
-// MFMA A operand wants them: block s = elements 32 s .. 32 s + 31 of all 16 slots is 1 KB, lane
-// l = slot + 16 g of a wave owns its 16 bytes l (slot's elements 32 s + 8 g .. + 8).  One A load
-// of a wave is then 1 KB contiguous instead of sixteen 64-byte pieces one vector pitch apart.
-__host__ __device__ __forceinline__ size_t bg_aidx(int slot, int k) {
-  return ((size_t)(k >> 5) << 9) + (size_t)((((k >> 3) & 3) << 4) + slot) * 8 + (k & 7);
-}
-
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4v_t;
 
@@ -121,7 +113,10 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
     S.cs[i] = make_float2((float)cos(a), (float)sin(a));
   }
   lds_barrier();
-  sk_attention<HD, SK_WAVES>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
+  // the merged output goes out split into bf16 high and low halves, in the order the output
+  // projection's A operand reads (slot = position of the sequence in this pass)
+  SP.xh_out = P.xh; SP.xl_out = P.xl; SP.out_slot = blockIdx.z;
+  sk_attention<HD, SK_WAVES, false, true>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
 }
 
 // Re-lays a row-major bf16 matrix W[N][K] into MFMA tile order: block (t, s) = rows 16 t .. +16,

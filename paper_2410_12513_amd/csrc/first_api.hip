@@ -345,7 +345,7 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
         hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
       else
         hipLaunchKernelGGL(k_attn_b, dim3(S, d.n_kv_heads, keep.n), dim3(WG), attn_lds<bf16>(c), c->stream, P);
-      xsplit(1, c->nq, nullptr);
+      if (!tiles_attn) xsplit(1, c->nq, nullptr);        // (k_attn_tiles_b writes its output already split)
       launch_bgemv<BG_O>(c, P, d.d_model, c->nq);
       xsplit(0, d.d_model, P.d.g_mlp);
       launch_bgemv<BG_GU>(c, P, d.d_ffn, d.d_model);

@@ -185,6 +185,8 @@ struct StepParams {
                                // read, and the arrival travels together with the stores instead of after them
   int* tagstate;               // [B][4] tag of the latest write to the h, qkv, attn and z vectors of each slot (tagged exchange)
   float* h_out;                // tagged exchange: [B][D] plain copy of the final hidden state (d.h then holds tagged words)
+  bf16 *xh_out, *xl_out;       // sk_attention<.., SPLIT_OUT>: the attention output as bf16 high / low halves in
+  int out_slot;                //   A-operand order (bg_aidx) for slot out_slot, instead of fp32 in d.attn
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
 
@@ -804,7 +806,7 @@ __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg,
 // EXT: the queries and the new key / value are already in LDS (sk_attn_prologue_tagged, run by
 // the service wave); the function returns false if that wave reported failure.  out_tag >= 0:
 // the attention output is written as tagged words.
-template <int HD, int NW = SK_SWAVES, bool EXT = false>
+template <int HD, int NW = SK_SWAVES, bool EXT = false, bool SPLIT_OUT = false>
 __device__ __forceinline__ bool sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
                                              unsigned long long* stamps, int out_tag = -1) {
   const DecParams& p = P.d;
@@ -1077,8 +1079,23 @@ __device__ __forceinline__ bool sk_attention(const StepParams& P, bf16* pool, co
       const unsigned tb = (unsigned)out_tag;
       r.x = sk_tagged(r.x, tb); r.y = sk_tagged(r.y, tb); r.z = sk_tagged(r.z, tb); r.w = sk_tagged(r.w, tb);
     }
-    if (sl == 0) st_coh16(out, r);
-    if (out_tag < 0) vm_wait_all();
+    if (SPLIT_OUT) {
+      if (sl == 0) {
+        const float v[4] = {r.x, r.y, r.z, r.w};
+        unsigned short hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bf16 h = from_f32<bf16>(v[j]);
+          hi[j] = h.v; lo[j] = from_f32<bf16>(v[j] - to_f32(h)).v;
+        }
+        const size_t at = bg_aidx(P.out_slot, H * HD + q4);          // 4 consecutive elements: 8 bytes, aligned
+        *reinterpret_cast<uint2*>(P.xh_out + at) = make_uint2(hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16));
+        *reinterpret_cast<uint2*>(P.xl_out + at) = make_uint2(lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16));
+      }
+    } else {
+      if (sl == 0) st_coh16(out, r);
+      if (out_tag < 0) vm_wait_all();
+    }
   }
   SK_ASTAMP(11);
 #undef SK_ASTAMP
