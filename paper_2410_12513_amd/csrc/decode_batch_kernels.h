@@ -108,10 +108,7 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
   const int tiles = (pos + 64) >> 6, nkg = max(1, SK_WAVES / p.G);
   const int nsplit = max(1, min((int)gridDim.x, (tiles + nkg - 1) / nkg));
   if ((int)blockIdx.x >= nsplit) return;
-  for (int i = tid; i < HD / 2; i += AT_THREADS) {
-    const double a = (double)pos * p.theta[i];
-    S.cs[i] = make_float2((float)cos(a), (float)sin(a));
-  }
+  for (int i = tid; i < HD / 2; i += AT_THREADS) S.cs[i] = p.rope_cs[(size_t)p.b * (HD / 2) + i];   // made by k_embed_b
   lds_barrier();
   // the merged output goes out split into bf16 high and low halves, in the order the output
   // projection's A operand reads (slot = position of the sequence in this pass)
