@@ -244,7 +244,7 @@ void launch_bgemv_rt(first_ctx* c, const BatchParams& P, int N, int K) {
   const bool tiled = c->tiled;
   const int groups = ((N + 15) / 16 + RT - 1) / RT;
   int ks = 1;
-  while (ks < BG_WAVES && groups * ks < 12 * c->num_cu) ks *= 2;
+  while (ks < BG_WAVES && groups * ks < 6 * c->num_cu) ks *= 2;       // (6 waves per CU measured best of 3 / 6 / 12 / 24)
   const int groups_per_wg = BG_WAVES / ks;
   const int grid = (groups + groups_per_wg - 1) / groups_per_wg;
   if (tiled) hipLaunchKernelGGL((k_bgemv<MODE, RT, true>), dim3(grid), dim3(BG_THREADS), 0, c->stream, P, N, K, ks);
