@@ -116,6 +116,347 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
   sk_attention<HD, SK_WAVES, false, true>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
 }
 
+// Decode attention of (split, KV head, slot) for models with G = Hq / Hkv query heads per KV
+// head (G = 4 instantiated): k_attn_tiles_b lets every head wave fetch its own copy of each
+// 64-key tile and form scores and weighted values with scalar FMAs, which at long context is
+// bound by the vector ALUs and by G-fold traffic through the compute unit's memory pipeline.
+// Here the workgroup fetches every tile ONCE, cooperatively, into LDS (double-buffered: the
+// two tiles of the next iteration are in flight while these are worked on); a wave takes 16
+// keys of a tile for ALL G heads: scores = Q K^T on the matrix cores (16x16x32 bf16, Q split
+// into high + low halves so that the product with the stored bf16 keys is exact to 2^-16),
+// an online softmax per wave, weighted values with the value rows shared across the heads.
+// The 8 waves' partial results meet in LDS; partial / count / merge across splits and the
+// output format are those of sk_attention<.., SPLIT_OUT>.  One workgroup per compute unit
+// (128 KB of tiles): the host sizes the grid to about one workgroup per compute unit.
+constexpr int AS_THREADS = SK_WAVES * 64;
+constexpr int AS_NT = 2;                                // tiles per iteration
+__host__ __device__ inline size_t as_lds_bytes(int G, int hd) {
+  return (size_t)2 * AS_NT * 2 * 64 * hd * 2 +          // [2 buffers][AS_NT][K, V][64][hd] bf16
+         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8) * sizeof(float);
+}
+
+template <int HD, int G>
+__global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
+  static_assert(HD == 128 && G <= 4, "lane layouts below: 8 value dims per lane, heads in one group of 16 lanes");
+  extern __shared__ __align__(16) float smem_f[];
+  DecParams p = P.d;
+  p.b = P.seqs.id[blockIdx.z];
+  constexpr int HALF = HD / 2;
+  constexpr int TILE_E = 64 * HD;                       // elements of one key (or value) tile
+  constexpr int BPT = HD / 64;                          // 8 KB blocks (512 lanes x 16 B) per tile
+  constexpr int NB = AS_NT * 2 * BPT;                   // blocks per iteration
+  constexpr int KS = HD / 32;                           // MFMA k-steps over the head dimension
+  constexpr int DL = HD / 16;                           // value dims per lane: lane (sub, dc), dc = lane % 16
+  const int b = p.b, Pg = p.P, g = blockIdx.y;
+  const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
+  const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
+  const int nsplit = max(1, min((int)gridDim.x, (tiles + AS_NT - 1) / AS_NT));
+  const int s = blockIdx.x;
+  if (s >= nsplit) return;
+  // LDS carve-up
+  bf16* tile_lds = reinterpret_cast<bf16*>(smem_f);
+  float* fb = smem_f + (size_t)2 * AS_NT * 2 * TILE_E / 2;
+  float* qs = fb; fb += G * HD;
+  float* knew = fb; fb += HD;
+  float* vnew = fb; fb += HD;
+  float2* cs = reinterpret_cast<float2*>(fb); fb += HD;
+  float* mbuf = fb; fb += SK_WAVES * G * (HD + 2);      // [wave][head][HD dims, max, sum]
+  int* flag = reinterpret_cast<int*>(fb);
+
+  const int tps = (tiles + nsplit - 1) / nsplit;
+  const int t_first = s * tps, t_last = min(tiles, t_first + tps), T = max(0, t_last - t_first);
+  const int n_it = (T + AS_NT - 1) / AS_NT;
+  const int nq = p.Hq * HD, nkv = p.Hkv * HD;
+  const float* qkv = p.qkv + (size_t)b * (nq + 2 * nkv);
+  const int* pt = p.page_table + (size_t)b * p.max_pages;
+  bf16* pool = reinterpret_cast<bf16*>(p.kv_layer);
+  const size_t head_off = (size_t)g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
+  const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
+  const int last_page = pos / Pg;
+  const int T1 = max(T, 1);                             // (a split without tiles still issues its requests, on a valid page)
+
+  // cooperative fetch of the AS_NT key tiles and value tiles of iteration `it` into registers
+  struct Stage { u32x4_t v[NB]; };
+  Stage stage, stage2;                                  // iterations it and it + 1: a request has two iterations to land
+  auto issue = [&](Stage& st, int it) __attribute__((always_inline)) {
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) {
+      const int ti = jb / (2 * BPT), rem = jb % (2 * BPT), is_v = rem / BPT, part = rem % BPT;
+      const int tt = max(0, min(it * AS_NT + ti, T1 - 1));                     // past the split: a harmless reload
+      const int t = t_first + tt;
+      const int e = part * 4096 + tid * 8, row = e / HD, col = e % HD;
+      const int key = (t << 6) + row;
+      const int pg = pt[min(key >> 4, last_page)];                             // pages past the last one: clamped, weight 0
+      const bf16* src = pool + (size_t)pg * p.page_elems + head_off + (is_v ? v_off : 0) + (size_t)(key & 15) * HD + col;
+      st.v[jb] = *reinterpret_cast<const u32x4_t*>(src);
+    }
+  };
+  // (blocks are stored in fetch order: block jb = (tile, key or value, part) lands at jb * 4096 elements,
+  //  which is exactly [tile][K, V][64][HD]; constant register indices keep the staging array out of memory)
+  auto stash = [&](const Stage& st, int it) __attribute__((always_inline)) {
+    bf16* buf = tile_lds + (size_t)(it & 1) * AS_NT * 2 * TILE_E + tid * 8;
+    static_assert(NB == 8, "written out for 8 blocks");
+    *reinterpret_cast<u32x4_t*>(buf + 0 * 4096) = st.v[0]; *reinterpret_cast<u32x4_t*>(buf + 1 * 4096) = st.v[1];
+    *reinterpret_cast<u32x4_t*>(buf + 2 * 4096) = st.v[2]; *reinterpret_cast<u32x4_t*>(buf + 3 * 4096) = st.v[3];
+    *reinterpret_cast<u32x4_t*>(buf + 4 * 4096) = st.v[4]; *reinterpret_cast<u32x4_t*>(buf + 5 * 4096) = st.v[5];
+    *reinterpret_cast<u32x4_t*>(buf + 6 * 4096) = st.v[6]; *reinterpret_cast<u32x4_t*>(buf + 7 * 4096) = st.v[7];
+  };
+
+  // this step's q (G heads), k and v of the KV head (requested before the tiles: loads return in order)
+  {
+    const int iq = min(tid, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
+    const int dk = min(tid, HALF - 1), dv = min(tid, HD - 1);
+    const float q1 = qkv[(g * G + hh) * HD + dq], q2 = qkv[(g * G + hh) * HD + dq + HALF];
+    const float k1 = qkv[nq + g * HD + dk], k2 = qkv[nq + g * HD + dk + HALF];
+    const float vv = qkv[nq + nkv + g * HD + dv];
+    const float2 c_own = p.rope_cs[(size_t)b * HALF + min(tid, HALF - 1)];               // made by k_embed_b
+    issue(stage, 0);                                    // (a split without tiles reloads a valid one and ignores it)
+    issue(stage2, min(1, max(n_it - 1, 0)));
+    if (tid < HALF) cs[tid] = c_own;
+    lds_barrier();
+    if (tid < G * HALF) {                              // rotate and pre-scale the queries
+      const float2 c = cs[dq];
+      qs[hh * HD + dq] = (q1 * c.x - q2 * c.y) * p.qscale;
+      qs[hh * HD + dq + HALF] = (q2 * c.x + q1 * c.y) * p.qscale;
+    }
+    if (owns_new) {                                    // append the new key / value; the rounded values also go to LDS
+      const size_t base = (size_t)pt[pos / Pg] * p.page_elems + head_off + (size_t)(pos % Pg) * HD;
+      if (tid < HALF) {
+        const float2 c = cs[dk];
+        const bf16 r1 = from_f32<bf16>(k1 * c.x - k2 * c.y), r2 = from_f32<bf16>(k2 * c.x + k1 * c.y);
+        pool[base + dk] = r1; pool[base + dk + HALF] = r2;
+        knew[dk] = __uint_as_float((unsigned)r1.v); knew[dk + HALF] = __uint_as_float((unsigned)r2.v);   // raw bf16 bits
+      }
+      if (tid < HD) {
+        const bf16 r = from_f32<bf16>(vv);
+        pool[base + v_off + dv] = r;
+        vnew[dv] = __uint_as_float((unsigned)r.v);
+      }
+    }
+  }
+  lds_barrier();
+
+  // A operand of the score MFMA: row m = lane % 16 = query head (rows >= G are zero), k = dims
+  bf16x8_t qh[KS], ql[KS];
+  {
+    const int hm = lane & 15;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      union { unsigned short u[8]; bf16x8_t v; } H, L;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = hm < G ? qs[hm * HD + ks * 32 + ((lane >> 4) << 3) + e] : 0.f;
+        const bf16 h = from_f32<bf16>(x);
+        H.u[e] = h.v; L.u[e] = from_f32<bf16>(x - to_f32(h)).v;
+      }
+      qh[ks] = H.v; ql[ks] = L.v;
+    }
+  }
+
+  // per wave: running maximum, sum and weighted values of its 16-key slices, for all G heads;
+  // lane (sub = lane / 16, dc = lane % 16) accumulates dims dc*DL .. +DL over keys 4 i + sub
+  float m[G], l[G], o[G][DL];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    m[h] = -INFINITY; l[h] = 0.f;
+#pragma unroll
+    for (int e = 0; e < DL; ++e) o[h][e] = 0.f;
+  }
+  const int ti = wave >> 2, quarter = wave & 3, sub = lane >> 4, dc = lane & 15;
+
+  auto iteration = [&](Stage& st, int it) __attribute__((always_inline)) {
+    stash(st, it);                                     // (waits for the loads of this iteration)
+    issue(st, min(it + 2, n_it - 1));                  // (the last iterations reload their own tiles: branch-free, ignored)
+    lds_barrier();                                     // tiles of `it` are in LDS; everyone has left the buffer of `it - 1`
+    bf16* tk = tile_lds + (size_t)(it & 1) * AS_NT * 2 * TILE_E + (size_t)(ti * 2) * TILE_E;
+    bf16* tv = tk + TILE_E;
+    const int t = t_first + it * AS_NT + ti;
+    if (owns_new && t == (pos >> 6)) {                 // the new position's row comes from this step, not from the cache
+      const int r = pos & 63;
+      if (quarter == 0) {
+        for (int d = lane; d < HD; d += 64) {
+          tk[r * HD + d].v = (uint16_t)__float_as_uint(knew[d]);
+          tv[r * HD + d].v = (uint16_t)__float_as_uint(vnew[d]);
+        }
+      }
+    }
+    if (owns_new) lds_barrier();                       // (the row is written by one wave of the tile and read by all four)
+    if (t >= t_last) return;
+    const int k0 = (t << 6) + quarter * 16;            // first key of this wave's slice
+    // scores: C[row = head][col = key]
+    f32x4v_t sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t kb = *reinterpret_cast<const bf16x8_t*>(tk + (quarter * 16 + (lane & 15)) * HD + ks * 32 + ((lane >> 4) << 3));
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[ks], kb, sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[ks], kb, sc, 0, 0, 0);
+    }
+    // lane (key = lane % 16, head group = lane / 16) holds heads 4 (lane / 16) + j: G <= 4 lives in lanes 0..15
+    float pj[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      // head h sits in register h % 4 of lanes 16 (h / 4) + key
+      float sv = __shfl(sc[h & 3], ((h >> 2) << 4) + (lane & 15), 64);
+      if (k0 + (lane & 15) >= nkeys) sv = -INFINITY;
+      float mt = sv;
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off, 64));
+      const float mn = fmaxf(m[h], mt);
+      const float corr = mn == -INFINITY ? 1.f : expf(m[h] - mn);      // (a slice past the last key, nothing seen yet)
+      const float pv = (k0 + (lane & 15) < nkeys) ? expf(sv - mn) : 0.f;
+      float ls = pv;
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) ls += __shfl_xor(ls, off, 64);
+      l[h] = l[h] * corr + ls;
+      m[h] = mn;
+#pragma unroll
+      for (int e = 0; e < DL; ++e) o[h][e] *= corr;
+      pj[h] = pv;                                      // every lane: weight of key lane % 16 for head h
+    }
+    // weighted values: 4 rows per lane group, each value row shared by the G heads
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kr = 4 * i + sub;                      // key of this lane within the slice
+      const int key = k0 + kr;
+      float vf[DL];
+#pragma unroll
+      for (int c8 = 0; c8 < DL / 8; ++c8) {
+        const uint4 w = *reinterpret_cast<const uint4*>(tv + (quarter * 16 + kr) * HD + dc * DL + c8 * 8);
+        vf[c8 * 8 + 0] = __uint_as_float(w.x << 16); vf[c8 * 8 + 1] = __uint_as_float(w.x & 0xffff0000u);
+        vf[c8 * 8 + 2] = __uint_as_float(w.y << 16); vf[c8 * 8 + 3] = __uint_as_float(w.y & 0xffff0000u);
+        vf[c8 * 8 + 4] = __uint_as_float(w.z << 16); vf[c8 * 8 + 5] = __uint_as_float(w.z & 0xffff0000u);
+        vf[c8 * 8 + 6] = __uint_as_float(w.w << 16); vf[c8 * 8 + 7] = __uint_as_float(w.w & 0xffff0000u);
+      }
+#pragma unroll
+      for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];          // never-written slots: no NaN patterns
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float w = __shfl(pj[h], kr, 64);         // weight of key kr for head h (held by lane kr)
+#pragma unroll
+        for (int e = 0; e < DL; ++e) o[h][e] = fmaf(w, vf[e], o[h][e]);
+      }
+    }
+  };
+  for (int it = 0; it < n_it; it += 2) {
+    iteration(stage, it);
+    if (it + 1 < n_it) iteration(stage2, it + 1);
+  }
+
+  // fold the key subgroups (lanes sub = 0..3), then every wave leaves its partial per head in LDS
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < DL; ++e) {
+      o[h][e] += __shfl_xor(o[h][e], 16, 64);
+      o[h][e] += __shfl_xor(o[h][e], 32, 64);
+    }
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    float* mb = mbuf + (size_t)(wave * G + h) * (HD + 2);
+    if (lane < 16) {
+#pragma unroll
+      for (int e = 0; e < DL; ++e) mb[dc * DL + e] = o[h][e];
+    }
+    if (lane == 0) { mb[HD] = m[h]; mb[HD + 1] = l[h]; }
+  }
+  __syncthreads();
+  // wave h merges head h over the 8 waves (fixed order) and writes the split's partial
+  if (wave < G) {
+    const int hq = wave;
+    float M = -INFINITY;
+    for (int w2 = 0; w2 < SK_WAVES; ++w2) M = fmaxf(M, mbuf[(size_t)(w2 * G + hq) * (HD + 2) + HD]);
+    float den = 0.f, a0 = 0.f, a1 = 0.f;
+    for (int w2 = 0; w2 < SK_WAVES; ++w2) {
+      const float* src = mbuf + (size_t)(w2 * G + hq) * (HD + 2);
+      const float lt = src[HD + 1];
+      if (lt > 0.f) {
+        const float w = expf(src[HD] - M);
+        den = fmaf(lt, w, den);
+        a0 = fmaf(src[lane], w, a0);
+        if (HD > 64) a1 = fmaf(src[lane + 64 < HD ? lane + 64 : lane], w, a1);
+      }
+    }
+    const int H = g * G + hq;
+    float* po = p.part_o + (((size_t)b * p.Hq + H) * S_MAX + s) * HD;
+    st_coh(po + lane, a0);
+    if (HD > 64) st_coh(po + lane + 64, a1);
+    if (lane == 0) {
+      float* pml = p.part_ml + (((size_t)b * p.Hq + H) * S_MAX + s) * 2;
+      st_coh(pml, M); st_coh(pml + 1, den);
+    }
+  }
+  // the last split of this KV head to finish merges all splits (fixed order) and writes the output
+  vm_wait_all();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned old = __hip_atomic_fetch_add(p.attn_cnt + b * p.Hkv + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (old == (unsigned)(nsplit - 1));
+    if (last) __hip_atomic_store(p.attn_cnt + b * p.Hkv + g, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    flag[1] = last;
+  }
+  __syncthreads();
+  if (uni(flag[1]) && wave < G) {
+    constexpr int LPS = HD / 4, SPI = 64 / LPS, NI = 16;
+    const int H = g * G + wave, q4 = (lane % LPS) * 4, sl = lane / LPS;
+    const float* pml = p.part_ml + ((size_t)b * p.Hq + H) * S_MAX * 2;
+    const float* po = p.part_o + ((size_t)b * p.Hq + H) * S_MAX * HD;
+    float den = 0.f, M = -INFINITY;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int b0 = 0; b0 < nsplit; b0 += NI * SPI) {
+      f32x4_t o4[NI];
+      float m_own, l_own;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) coh_issue16(o4[i], po + min(b0 + i * SPI + sl, nsplit - 1) * HD + q4);
+      coh_issue4(m_own, pml + 2 * min(lane, nsplit - 1));
+      coh_issue4(l_own, pml + 2 * min(lane, nsplit - 1) + 1);
+      coh_wait();
+#pragma unroll
+      for (int i = 0; i < NI; ++i) coh_use(o4[i]);
+      coh_use(m_own); coh_use(l_own);
+      float mv[NI], lv[NI];
+      float Mb = M;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int ts = min(b0 + i * SPI + sl, nsplit - 1);
+        mv[i] = __shfl(m_own, ts, 64); lv[i] = __shfl(l_own, ts, 64);
+        if (b0 + i * SPI + sl < nsplit) Mb = fmaxf(Mb, mv[i]);
+      }
+#pragma unroll
+      for (int off = LPS; off < 64; off <<= 1) Mb = fmaxf(Mb, __shfl_xor(Mb, off, 64));
+      const float resc = expf(M - Mb);
+      den *= resc; acc *= resc;
+      M = Mb;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        if (b0 + i * SPI + sl < nsplit && lv[i] > 0.f) {
+          const float w = expf(mv[i] - M);
+          den = fmaf(lv[i], w, den);
+          acc.x = fmaf(o4[i].x, w, acc.x); acc.y = fmaf(o4[i].y, w, acc.y);
+          acc.z = fmaf(o4[i].z, w, acc.z); acc.w = fmaf(o4[i].w, w, acc.w);
+        }
+      }
+    }
+#pragma unroll
+    for (int off = LPS; off < 64; off <<= 1) {
+      den += __shfl_xor(den, off, 64);
+      acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
+      acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
+    }
+    if (sl == 0) {
+      const float v[4] = {acc.x / den, acc.y / den, acc.z / den, acc.w / den};
+      unsigned short hi[4], lo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bf16 h = from_f32<bf16>(v[j]);
+        hi[j] = h.v; lo[j] = from_f32<bf16>(v[j] - to_f32(h)).v;
+      }
+      const size_t at = bg_aidx(blockIdx.z, H * HD + q4);
+      *reinterpret_cast<uint2*>(P.xh + at) = make_uint2(hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16));
+      *reinterpret_cast<uint2*>(P.xl + at) = make_uint2(lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16));
+    }
+  }
+}
+
 // Re-lays a row-major bf16 matrix W[N][K] into MFMA tile order: block (t, s) = rows 16 t .. +16,
 // columns 32 s .. +32 is 1 KB, lane l of a wave owns its 16 bytes l (row 16 t + l % 16, columns
 // 32 s + 8 (l / 16) .. +8), blocks of a tile are consecutive in s.  A wave then streams a tile

@@ -314,6 +314,8 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
   const int nkg = std::max(1, SK_WAVES / c->G);
   const int nsplit = std::max(1, std::min(S_MAX, (2 * S + nkg - 1) / nkg));
   const size_t attn_tiles_lds = sk_lds_floats(0, 0, 0, c->G, d.head_dim) * sizeof(float);
+  // models with 4 query heads per KV head and head dimension 128: tiles fetched once per workgroup, scores on the matrix cores
+  const bool shared_attn = c->G == 4 && d.head_dim == 128;
   for (int b0 = 0; b0 < c->B; b0 += BATCH_SLOTS) {
     BatchParams P{};
     P.d = base_params(c, 0, S);
@@ -339,7 +341,12 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       { const LayerPtrs& l = c->layers[i]; P.t_qkv = l.t_qkv; P.t_o = l.t_o; P.t_g = l.t_g; P.t_u = l.t_u; P.t_d = l.t_d; }
       xsplit(0, d.d_model, P.d.g_attn);
       launch_bgemv<BG_QKV>(c, P, nqkv, d.d_model);
-      if (tiles_attn && d.head_dim == 128)
+      // shared key / value tiles: about one workgroup per compute unit, long loops
+      int ns_shared = std::max(1, std::min(S_MAX, c->num_cu / std::max(1, d.n_kv_heads * keep.n)));
+      if (c->attn_splits > 0) ns_shared = std::min(ns_shared, c->attn_splits);
+      if (tiles_attn && shared_attn)
+        hipLaunchKernelGGL((k_attn_mfma_b<128, 4>), dim3(ns_shared, d.n_kv_heads, keep.n), dim3(AS_THREADS), as_lds_bytes(4, 128), c->stream, P);
+      else if (tiles_attn && d.head_dim == 128)
         hipLaunchKernelGGL(k_attn_tiles_b<128>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
       else if (tiles_attn)
         hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
@@ -668,6 +675,8 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
     if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
     // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_mfma_b<128, 4>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, bf16>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, float>),
