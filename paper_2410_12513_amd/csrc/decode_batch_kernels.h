@@ -130,14 +130,32 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
 // (128 KB of tiles): the host sizes the grid to about one workgroup per compute unit.
 constexpr int AS_THREADS = SK_WAVES * 64;
 constexpr int AS_NT = 2;                                // tiles per iteration
+constexpr int AS_PT = 1024;                             // page ids of a split kept in LDS: the host gives a split at most AS_PT / 4 tiles
 __host__ __device__ inline size_t as_lds_bytes(int G, int hd) {
   return (size_t)2 * AS_NT * 2 * 64 * hd * 2 +          // [2 buffers][AS_NT][K, V][64][hd] bf16
-         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8) * sizeof(float);
+         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8 + AS_PT + SK_WAVES * 16 * 4) * sizeof(float);
+}
+
+// Reductions over the 16 lanes of a DPP row (quads, half rows, rows): every lane ends up with
+// the row's result, without LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_row_perm(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_row_perm<0xB1>(v)); v = fmaxf(v, dpp_row_perm<0x4E>(v));
+  v = fmaxf(v, dpp_row_perm<0x141>(v)); v = fmaxf(v, dpp_row_perm<0x140>(v));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_row_perm<0xB1>(v); v += dpp_row_perm<0x4E>(v);
+  v += dpp_row_perm<0x141>(v); v += dpp_row_perm<0x140>(v);
+  return v;
 }
 
 template <int HD, int G>
 __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
-  static_assert(HD == 128 && G <= 4, "lane layouts below: 8 value dims per lane, heads in one group of 16 lanes");
+  static_assert(HD == 128 && G == 4, "lane layouts below: 8 value dims per lane, the 4 heads repeat down the 16 score rows");
   extern __shared__ __align__(16) float smem_f[];
   DecParams p = P.d;
   p.b = P.seqs.id[blockIdx.z];
@@ -161,8 +179,10 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   float* vnew = fb; fb += HD;
   float2* cs = reinterpret_cast<float2*>(fb); fb += HD;
   float* mbuf = fb; fb += SK_WAVES * G * (HD + 2);      // [wave][head][HD dims, max, sum]
-  int* flag = reinterpret_cast<int*>(fb);
-
+  int* flag = reinterpret_cast<int*>(fb); fb += 8;
+  int* pt_lds = reinterpret_cast<int*>(fb); fb += AS_PT;   // page ids of this split's tiles: a lookup in global memory before every
+                                                        // tile request would put a second, dependent round trip into each iteration
+  float* wbuf = fb + (size_t)wave * 16 * 4;             // [16 keys][4 heads] softmax weights of this wave's slice
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps), T = max(0, t_last - t_first);
   const int n_it = (T + AS_NT - 1) / AS_NT;
@@ -174,6 +194,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
   const int last_page = pos / Pg;
   const int T1 = max(T, 1);                             // (a split without tiles still issues its requests, on a valid page)
+  for (int i = tid; i < min(T1 * 4, AS_PT); i += AS_THREADS) pt_lds[i] = pt[min(t_first * 4 + i, last_page)];
+  lds_barrier();
 
   // cooperative fetch of the AS_NT key tiles and value tiles of iteration `it` into registers
   struct Stage { u32x4_t v[NB]; };
@@ -186,7 +208,7 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
       const int t = t_first + tt;
       const int e = part * 4096 + tid * 8, row = e / HD, col = e % HD;
       const int key = (t << 6) + row;
-      const int pg = pt[min(key >> 4, last_page)];                             // pages past the last one: clamped, weight 0
+      const int pg = pt_lds[min(tt * 4 + (row >> 4), AS_PT - 1)];            // (pages past the last one were clamped: weight 0)
       const bf16* src = pool + (size_t)pg * p.page_elems + head_off + (is_v ? v_off : 0) + (size_t)(key & 15) * HD + col;
       st.v[jb] = *reinterpret_cast<const u32x4_t*>(src);
     }
@@ -236,10 +258,11 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   }
   lds_barrier();
 
-  // A operand of the score MFMA: row m = lane % 16 = query head (rows >= G are zero), k = dims
+  // A operand of the score MFMA: row m = lane % 16 holds query head m % G (the heads repeat down the
+  // 16 rows, so that every group of 16 lanes gets all G heads of its key in its own result registers), k = dims
   bf16x8_t qh[KS], ql[KS];
   {
-    const int hm = lane & 15;
+    const int hm = (lane & 15) % G;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       union { unsigned short u[8]; bf16x8_t v; } H, L;
@@ -292,27 +315,25 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
       sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[ks], kb, sc, 0, 0, 0);
     }
     // lane (key = lane % 16, head group = lane / 16) holds heads 4 (lane / 16) + j: G <= 4 lives in lanes 0..15
-    float pj[G];
+    float pj[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      // head h sits in register h % 4 of lanes 16 (h / 4) + key
-      float sv = __shfl(sc[h & 3], ((h >> 2) << 4) + (lane & 15), 64);
+      // result rows 4 (lane / 16) + j hold head j: register h of every lane is S[head h][key lane % 16]
+      float sv = sc[h];
       if (k0 + (lane & 15) >= nkeys) sv = -INFINITY;
-      float mt = sv;
-#pragma unroll
-      for (int off = 1; off < 16; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off, 64));
+      const float mt = row16_max(sv);
       const float mn = fmaxf(m[h], mt);
       const float corr = mn == -INFINITY ? 1.f : expf(m[h] - mn);      // (a slice past the last key, nothing seen yet)
       const float pv = (k0 + (lane & 15) < nkeys) ? expf(sv - mn) : 0.f;
-      float ls = pv;
-#pragma unroll
-      for (int off = 1; off < 16; off <<= 1) ls += __shfl_xor(ls, off, 64);
+      const float ls = row16_sum(pv);
       l[h] = l[h] * corr + ls;
       m[h] = mn;
 #pragma unroll
       for (int e = 0; e < DL; ++e) o[h][e] *= corr;
       pj[h] = pv;                                      // every lane: weight of key lane % 16 for head h
     }
+    // the weights go through LDS: lane (sub, dc) needs those of keys 4 i + sub
+    if (lane < 16) *reinterpret_cast<f32x4_t*>(wbuf + lane * 4) = f32x4_t{pj[0], pj[1], pj[2], pj[3]};
     // weighted values: 4 rows per lane group, each value row shared by the G heads
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -329,9 +350,10 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
       }
 #pragma unroll
       for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];          // never-written slots: no NaN patterns
+      const f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(wbuf + kr * 4);   // weights of key kr for the G heads
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        const float w = __shfl(pj[h], kr, 64);         // weight of key kr for head h (held by lane kr)
+        const float w = w4[h];
 #pragma unroll
         for (int e = 0; e < DL; ++e) o[h][e] = fmaf(w, vf[e], o[h][e]);
       }

@@ -344,6 +344,9 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       // shared key / value tiles: about one workgroup per compute unit, long loops
       int ns_shared = std::max(1, std::min(S_MAX, c->num_cu / std::max(1, d.n_kv_heads * keep.n)));
       if (c->attn_splits > 0) ns_shared = std::min(ns_shared, c->attn_splits);
+      // a split's page ids must fit the kernel's LDS table whatever length a sequence reaches (a bound that
+      // does not move with the lengths, so a captured graph stays valid)
+      ns_shared = std::max(ns_shared, ((d.max_seq_len + 64) / 64 * 4 + AS_PT - 1) / AS_PT);
       if (tiles_attn && shared_attn)
         hipLaunchKernelGGL((k_attn_mfma_b<128, 4>), dim3(ns_shared, d.n_kv_heads, keep.n), dim3(AS_THREADS), as_lds_bytes(4, 128), c->stream, P);
       else if (tiles_attn && d.head_dim == 128)
