@@ -668,6 +668,131 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
   }
 }
 
+// The small mat-vecs of a layer (QKV, O, down: few row tiles, long or medium K) decomposed the
+// other way round: a workgroup = 8 row tiles (one per wave) x ONE slice of K.  All its waves need
+// the same slice of the activation operand, so it is copied into LDS once and read from there;
+// k_bgemv's workgroup (one tile x 8 slices of K) makes every wave fetch its own slice from L2,
+// which for these matrices is twice the weight bytes and saturates the compute unit's memory
+// pipeline.  The K-slices of a tile group then live in different workgroups: each stores its
+// partial sums, and the last one to finish (a counter per tile group) adds them in slice order
+// - the result does not depend on which workgroup that is - and applies the epilogue.
+// Tile-order weights only.  Dynamic LDS: 2 * per * 1024 bytes (per = K-steps per slice).
+__host__ __device__ inline int bgg_per(int K, int ks) { return (((K + 31) >> 5) + ks - 1) / ks; }
+
+template <int MODE>
+__global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, int K, int ks, float* __restrict__ part,
+                                                        unsigned* __restrict__ cnt) {
+  static_assert(MODE == BG_QKV || MODE == BG_O || MODE == BG_DN, "gate/up measured no faster this way; the LM head has tiles enough");
+  constexpr int NS = 1;
+  extern __shared__ __align__(16) uint4 lds_a[];       // [hi, lo][per][64] 16-byte pieces in A-operand order
+  __shared__ int last_flag;
+  const DecParams& p = P.d;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, g = lane >> 4;
+  const int ksteps = (K + 31) >> 5, per = bgg_per(K, ks);
+  const int tg = blockIdx.x / ks, sl = blockIdx.x % ks;
+  const int s0 = sl * per, s1 = min(ksteps, s0 + per), ns = max(0, s1 - s0);
+  const int ntiles = (N + 15) >> 4, tile = tg * BG_WAVES + wave;
+  const bf16* w[NS];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) w[i] = bg_tiled_base<MODE>(P, i) + (size_t)min(tile, ntiles - 1) * ksteps * 512 + lane * 8;
+
+  constexpr int UN = 4;
+  struct Chunk { uint4 wv[UN][NS]; };
+  const int nchunks = ns / UN;
+  auto load = [&](Chunk& c, int ci) __attribute__((always_inline)) {
+    const int sc = s0 + min(ci, max(nchunks - 1, 0)) * UN;
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+      for (int i = 0; i < NS; ++i) c.wv[u][i] = ld_stream16(w[i] + (size_t)min(sc + u, ksteps - 1) * 512);
+  };
+  Chunk A, B;
+  load(A, 0);                                          // the weight stream starts before the activations are staged
+  {
+    const uint4* xh = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zh : P.xh) + (size_t)s0 * 512);
+    const uint4* xl = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zl : P.xl) + (size_t)s0 * 512);
+    for (int i = tid; i < ns * 64; i += BG_THREADS) {
+      lds_a[i] = xh[i];
+      lds_a[per * 64 + i] = xl[i];
+    }
+  }
+  __syncthreads();
+
+  f32x4v_t acc[NS];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) acc[i] = f32x4v_t{0.f, 0.f, 0.f, 0.f};
+  auto mma = [&](const Chunk& c, int ci) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const bf16x8_t ah = as_bf16x8(lds_a[(ci * UN + u) * 64 + lane]);
+      const bf16x8_t al = as_bf16x8(lds_a[per * 64 + (ci * UN + u) * 64 + lane]);
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        const bf16x8_t bw = as_bf16x8(c.wv[u][i]);
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bw, acc[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bw, acc[i], 0, 0, 0);
+      }
+    }
+  };
+  if (nchunks > 0) {
+    int ci = 0;
+    for (; ci + 2 <= nchunks; ci += 2) {
+      load(B, ci + 1);
+      mma(A, ci);
+      load(A, ci + 2);
+      mma(B, ci + 1);
+    }
+    if (ci < nchunks) mma(A, ci);
+  }
+  for (int s = s0 + nchunks * UN; s < s1; ++s) {       // remaining steps of the slice
+    const bf16x8_t ah = as_bf16x8(lds_a[(s - s0) * 64 + lane]), al = as_bf16x8(lds_a[per * 64 + (s - s0) * 64 + lane]);
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const bf16x8_t bw = as_bf16x8(*reinterpret_cast<const uint4*>(w[i] + (size_t)s * 512));
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bw, acc[i], 0, 0, 0);
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bw, acc[i], 0, 0, 0);
+    }
+  }
+
+  // partial sums of this slice: [workgroup][stream][slot][row within the tile group]
+  float* mine = part + (size_t)blockIdx.x * (NS * 16 * 128);
+#pragma unroll
+  for (int i = 0; i < NS; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) st_coh(mine + i * (16 * 128) + (4 * g + j) * 128 + wave * 16 + n, acc[i][j]);
+  vm_wait_all();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned old = __hip_atomic_fetch_add(cnt + tg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = old == (unsigned)(ks - 1);
+    if (last) __hip_atomic_store(cnt + tg, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last_flag = last;
+  }
+  __syncthreads();
+  if (!last_flag) return;
+  // the last slice of this tile group to finish adds the slices in order and applies the epilogue
+  const float* grp = part + (size_t)tg * ks * (NS * 16 * 128);
+  for (int e = tid; e < 16 * 128; e += BG_THREADS) {
+    const int slot = e >> 7, r = e & 127, row = tg * 128 + r;
+    float sum[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) coh_issue4(v[q], grp + (size_t)min(q, ks - 1) * (NS * 16 * 128) + i * (16 * 128) + e);
+      coh_wait();
+      sum[i] = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { coh_use(v[q]); if (q < ks) sum[i] += v[q]; }
+    }
+    if (slot >= P.seqs.n || row >= N) continue;
+    const int b = P.seqs.id[slot];
+    if (MODE == BG_QKV) p.qkv[(size_t)b * N + row] = sum[0] * P.rinv[slot];
+    else p.h[(size_t)b * p.D + row] += sum[0];
+  }
+}
+
 // Greedy token, stage 1: candidate of chunk blockIdx.y of slot blockIdx.x's logits row.
 constexpr int ARG_CHUNKS = 64;
 __global__ void __launch_bounds__(WG) k_argmax_part_b(BatchParams P) {

@@ -54,6 +54,9 @@ struct first_ctx {
   double* d_theta = nullptr;
   float *d_h = nullptr, *d_qkv = nullptr, *d_attn = nullptr, *d_z = nullptr, *d_part_o = nullptr, *d_part_ml = nullptr;
   unsigned *d_attn_cnt = nullptr, *d_head_cnt = nullptr;
+  float* d_bg_part = nullptr;             // k_bgemv_g: [workgroups][16 slots][128 rows] partial sums of the K-slices
+  unsigned* d_bg_cnt = nullptr;           //            arrival counters per tile group (zero between launches)
+  size_t bg_part_wgs = 0, bg_cnt_n = 0;
   Cand* d_topk_part = nullptr;            // [max_batch][chunks][SMP_KMAX] per-chunk candidates of first_sample_top_k
   float2* d_rope_cs = nullptr;
   Best* d_arg_part = nullptr;
@@ -255,8 +258,25 @@ bool d_batch_fits(const first_ctx* c) {
   return c->d.d_model % 8 == 0 && c->nq % 8 == 0 && c->d.d_ffn % 8 == 0;
 }
 
+// QKV, O and down with tile-order weights: 8 row tiles x one slice of K per workgroup (k_bgemv_g),
+// about one workgroup per compute unit, at most 8 slices.
+template <int MODE>
+bool launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
+  if (!c->tiled || c->d_bg_part == nullptr) return false;
+  const int groups = ((N + 15) / 16 + BG_WAVES - 1) / BG_WAVES;
+  int ks = std::max(1, std::min(8, (c->num_cu + groups / 2) / groups));
+  ks = std::min(ks, (K + 31) / 32);
+  const size_t lds = (size_t)2 * bgg_per(K, ks) * 1024;
+  if (lds > 150 * 1024 || (size_t)groups * ks > c->bg_part_wgs || (size_t)groups > c->bg_cnt_n) return false;
+  hipLaunchKernelGGL((k_bgemv_g<MODE>), dim3(groups * ks), dim3(BG_THREADS), lds, c->stream, P, N, K, ks, c->d_bg_part, c->d_bg_cnt);
+  return true;
+}
+
 template <int MODE>
 void launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
+  if constexpr (MODE == BG_QKV || MODE == BG_O || MODE == BG_DN) {
+    if (launch_bgemv_g<MODE>(c, P, N, K)) return;
+  }
   // two tiles per wave once that still leaves every SIMD several waves
   if ((N + 15) / 16 >= 16 * c->num_cu / 8) launch_bgemv_rt<MODE, 2>(c, P, N, K);
   else launch_bgemv_rt<MODE, 1>(c, P, N, K);
@@ -629,10 +649,17 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     A(dev_alloc(c, &c->d_xh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_xl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_zh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_zl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_rinv, BATCH_SLOTS)); A(dev_alloc(c, &c->d_logits_all, (size_t)B * d.vocab));
+    c->bg_cnt_n = (size_t)(std::max(c->nq + 2 * c->nkv, d.d_model) + 127) / 128;
+    c->bg_part_wgs = c->bg_cnt_n * 8;                   // (up to 8 slices)
+    A(dev_alloc(c, &c->d_bg_part, c->bg_part_wgs * 16 * 128)); A(dev_alloc(c, &c->d_bg_cnt, c->bg_cnt_n));
   }
   if (B > 1 && rc == FIRST_OK) {
     (void)hipMemset(c->d_xh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_xl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
     (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
+    (void)hipMemset(c->d_bg_cnt, 0, c->bg_cnt_n * sizeof(unsigned));
+    for (const void* fn : {reinterpret_cast<const void*>(&k_bgemv_g<BG_QKV>), reinterpret_cast<const void*>(&k_bgemv_g<BG_O>),
+                           reinterpret_cast<const void*>(&k_bgemv_g<BG_DN>)})
+      (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
   }
   A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
   A(dev_alloc(c, &c->d_topk_part, (size_t)B * ((d.vocab + SMP_CHUNK - 1) / SMP_CHUNK) * SMP_KMAX));
