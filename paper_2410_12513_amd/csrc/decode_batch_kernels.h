@@ -668,22 +668,24 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
   }
 }
 
-// The small mat-vecs of a layer (QKV, O, down: few row tiles, long or medium K) decomposed the
-// other way round: a workgroup = 8 row tiles (one per wave) x ONE slice of K.  All its waves need
-// the same slice of the activation operand, so it is copied into LDS once and read from there;
-// k_bgemv's workgroup (one tile x 8 slices of K) makes every wave fetch its own slice from L2,
-// which for these matrices is twice the weight bytes and saturates the compute unit's memory
-// pipeline.  The K-slices of a tile group then live in different workgroups: each stores its
-// partial sums, and the last one to finish (a counter per tile group) adds them in slice order
-// - the result does not depend on which workgroup that is - and applies the epilogue.
+// The mat-vecs of a layer decomposed the other way round: a workgroup = GW row tiles (one per wave) x
+// ONE slice of K.  All its waves need the same slice of the activation operand, so it is copied into
+// LDS once and read from there; k_bgemv's workgroup (tiles x slices of K over its waves) makes every
+// wave fetch its own slice from L2, and that traffic counts against the same per-compute-unit memory
+// pipeline as the weights (for the small matrices it is twice the weight bytes).  The K-slices of a
+// tile group then live in different workgroups: each stores its partial sums, and the last one to
+// finish (a counter per tile group) adds them in slice order - the result does not depend on which
+// workgroup that is - and applies the epilogue.  GW (5..8 waves) and the number of slices are chosen
+// on the host so that the workgroups come to a whole number of rounds over the compute units.
 // Tile-order weights only.  Dynamic LDS: 2 * per * 1024 bytes (per = K-steps per slice).
 __host__ __device__ inline int bgg_per(int K, int ks) { return (((K + 31) >> 5) + ks - 1) / ks; }
 
-template <int MODE>
-__global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, int K, int ks, float* __restrict__ part,
-                                                        unsigned* __restrict__ cnt) {
-  static_assert(MODE == BG_QKV || MODE == BG_O || MODE == BG_DN, "gate/up measured no faster this way; the LM head has tiles enough");
-  constexpr int NS = 1;
+template <int MODE, int GW>
+__global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K, int ks, float* __restrict__ part,
+                                                     unsigned* __restrict__ cnt) {
+  static_assert(MODE == BG_QKV || MODE == BG_O || MODE == BG_DN || MODE == BG_GU, "the LM head has tiles enough for k_bgemv");
+  constexpr int NS = MODE == BG_GU ? 2 : 1;            // gate/up: a wave streams the gate tile and the up tile of its rows
+  constexpr int THREADS = GW * 64, ROWS = GW * 16;     // rows of a tile group
   extern __shared__ __align__(16) uint4 lds_a[];       // [hi, lo][per][64] 16-byte pieces in A-operand order
   __shared__ int last_flag;
   const DecParams& p = P.d;
@@ -692,7 +694,7 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, in
   const int ksteps = (K + 31) >> 5, per = bgg_per(K, ks);
   const int tg = blockIdx.x / ks, sl = blockIdx.x % ks;
   const int s0 = sl * per, s1 = min(ksteps, s0 + per), ns = max(0, s1 - s0);
-  const int ntiles = (N + 15) >> 4, tile = tg * BG_WAVES + wave;
+  const int ntiles = (N + 15) >> 4, tile = tg * GW + wave;
   const bf16* w[NS];
 #pragma unroll
   for (int i = 0; i < NS; ++i) w[i] = bg_tiled_base<MODE>(P, i) + (size_t)min(tile, ntiles - 1) * ksteps * 512 + lane * 8;
@@ -712,7 +714,7 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, in
   {
     const uint4* xh = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zh : P.xh) + (size_t)s0 * 512);
     const uint4* xl = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zl : P.xl) + (size_t)s0 * 512);
-    for (int i = tid; i < ns * 64; i += BG_THREADS) {
+    for (int i = tid; i < ns * 64; i += THREADS) {
       lds_a[i] = xh[i];
       lds_a[per * 64 + i] = xl[i];
     }
@@ -756,11 +758,11 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, in
   }
 
   // partial sums of this slice: [workgroup][stream][slot][row within the tile group]
-  float* mine = part + (size_t)blockIdx.x * (NS * 16 * 128);
+  float* mine = part + (size_t)blockIdx.x * (NS * 16 * ROWS);
 #pragma unroll
   for (int i = 0; i < NS; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) st_coh(mine + i * (16 * 128) + (4 * g + j) * 128 + wave * 16 + n, acc[i][j]);
+    for (int j = 0; j < 4; ++j) st_coh(mine + i * (16 * ROWS) + (4 * g + j) * ROWS + wave * 16 + n, acc[i][j]);
   vm_wait_all();
   __syncthreads();
   if (tid == 0) {
@@ -772,15 +774,15 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, in
   __syncthreads();
   if (!last_flag) return;
   // the last slice of this tile group to finish adds the slices in order and applies the epilogue
-  const float* grp = part + (size_t)tg * ks * (NS * 16 * 128);
-  for (int e = tid; e < 16 * 128; e += BG_THREADS) {
-    const int slot = e >> 7, r = e & 127, row = tg * 128 + r;
+  const float* grp = part + (size_t)tg * ks * (NS * 16 * ROWS);
+  for (int e = tid; e < 16 * ROWS; e += THREADS) {
+    const int slot = e / ROWS, r = e % ROWS, row = tg * ROWS + r;
     float sum[NS];
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
       float v[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) coh_issue4(v[q], grp + (size_t)min(q, ks - 1) * (NS * 16 * 128) + i * (16 * 128) + e);
+      for (int q = 0; q < 8; ++q) coh_issue4(v[q], grp + (size_t)min(q, ks - 1) * (NS * 16 * ROWS) + i * (16 * ROWS) + e);
       coh_wait();
       sum[i] = 0.f;
 #pragma unroll
@@ -788,8 +790,17 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv_g(BatchParams P, int N, in
     }
     if (slot >= P.seqs.n || row >= N) continue;
     const int b = P.seqs.id[slot];
-    if (MODE == BG_QKV) p.qkv[(size_t)b * N + row] = sum[0] * P.rinv[slot];
-    else p.h[(size_t)b * p.D + row] += sum[0];
+    if (MODE == BG_QKV) {
+      p.qkv[(size_t)b * N + row] = sum[0] * P.rinv[slot];
+    } else if (MODE == BG_GU) {
+      const float rr = P.rinv[slot];
+      const float z = siluf(sum[0] * rr) * (sum[NS - 1] * rr);
+      const bf16 hi = from_f32<bf16>(z);
+      P.zh[bg_aidx(slot, row)] = hi;                           // input of the down projection, already split
+      P.zl[bg_aidx(slot, row)] = from_f32<bf16>(z - to_f32(hi));
+    } else {
+      p.h[(size_t)b * p.D + row] += sum[0];
+    }
   }
 }
 

@@ -56,7 +56,7 @@ struct first_ctx {
   unsigned *d_attn_cnt = nullptr, *d_head_cnt = nullptr;
   float* d_bg_part = nullptr;             // k_bgemv_g: [workgroups][16 slots][128 rows] partial sums of the K-slices
   unsigned* d_bg_cnt = nullptr;           //            arrival counters per tile group (zero between launches)
-  size_t bg_part_wgs = 0, bg_cnt_n = 0;
+  size_t bg_part_floats = 0, bg_cnt_n = 0;
   Cand* d_topk_part = nullptr;            // [max_batch][chunks][SMP_KMAX] per-chunk candidates of first_sample_top_k
   float2* d_rope_cs = nullptr;
   Best* d_arg_part = nullptr;
@@ -258,23 +258,46 @@ bool d_batch_fits(const first_ctx* c) {
   return c->d.d_model % 8 == 0 && c->nq % 8 == 0 && c->d.d_ffn % 8 == 0;
 }
 
-// QKV, O and down with tile-order weights: 8 row tiles x one slice of K per workgroup (k_bgemv_g),
-// about one workgroup per compute unit, at most 8 slices.
+// Mat-vecs with tile-order weights as (GW row tiles) x (one slice of K) per workgroup (k_bgemv_g): GW in
+// 5..8 and at most 8 slices, chosen so that the workgroups fill whole rounds over the compute units
+// (ties: more waves per workgroup, fewer slices).
+template <int MODE, int GW>
+void launch_bgemv_gw(first_ctx* c, const BatchParams& P, int N, int K, int groups, int ks) {
+  hipLaunchKernelGGL((k_bgemv_g<MODE, GW>), dim3(groups * ks), dim3(GW * 64), (size_t)2 * bgg_per(K, ks) * 1024, c->stream, P, N, K, ks,
+                     c->d_bg_part, c->d_bg_cnt);
+}
+
 template <int MODE>
 bool launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
   if (!c->tiled || c->d_bg_part == nullptr) return false;
-  const int groups = ((N + 15) / 16 + BG_WAVES - 1) / BG_WAVES;
-  int ks = std::max(1, std::min(8, (c->num_cu + groups / 2) / groups));
-  ks = std::min(ks, (K + 31) / 32);
-  const size_t lds = (size_t)2 * bgg_per(K, ks) * 1024;
-  if (lds > 150 * 1024 || (size_t)groups * ks > c->bg_part_wgs || (size_t)groups > c->bg_cnt_n) return false;
-  hipLaunchKernelGGL((k_bgemv_g<MODE>), dim3(groups * ks), dim3(BG_THREADS), lds, c->stream, P, N, K, ks, c->d_bg_part, c->d_bg_cnt);
+  constexpr int NS = MODE == BG_GU ? 2 : 1;
+  const int tiles = (N + 15) / 16, ksteps = (K + 31) / 32;
+  int best_gw = 0, best_ks = 0;
+  double best = 0.0;
+  for (int gw = 8; gw >= 5; --gw)
+    for (int ks = 1; ks <= std::min(8, ksteps); ++ks) {
+      const int groups = (tiles + gw - 1) / gw, wgs = groups * ks;
+      if ((size_t)2 * bgg_per(K, ks) * 1024 > 150 * 1024) continue;
+      if ((size_t)wgs * NS * 16 * gw * 16 > c->bg_part_floats || (size_t)groups > c->bg_cnt_n) continue;
+      // useful wave-slots over the wave-slots of the rounds the grid occupies
+      const int rounds = (wgs + c->num_cu - 1) / c->num_cu;
+      const double eff = (double)tiles * ks / ((double)rounds * c->num_cu * gw) / rounds;
+      if (eff > best + 1e-9) { best = eff; best_gw = gw; best_ks = ks; }
+    }
+  if (best_gw == 0) return false;
+  const int groups = (tiles + best_gw - 1) / best_gw;
+  switch (best_gw) {
+    case 8: launch_bgemv_gw<MODE, 8>(c, P, N, K, groups, best_ks); break;
+    case 7: launch_bgemv_gw<MODE, 7>(c, P, N, K, groups, best_ks); break;
+    case 6: launch_bgemv_gw<MODE, 6>(c, P, N, K, groups, best_ks); break;
+    default: launch_bgemv_gw<MODE, 5>(c, P, N, K, groups, best_ks); break;
+  }
   return true;
 }
 
 template <int MODE>
 void launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
-  if constexpr (MODE == BG_QKV || MODE == BG_O || MODE == BG_DN) {
+  if constexpr (MODE == BG_QKV || MODE == BG_O || MODE == BG_DN || MODE == BG_GU) {
     if (launch_bgemv_g<MODE>(c, P, N, K)) return;
   }
   // two tiles per wave once that still leaves every SIMD several waves
@@ -649,17 +672,23 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     A(dev_alloc(c, &c->d_xh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_xl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_zh, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_zl, (size_t)BATCH_SLOTS * c->xpitch));
     A(dev_alloc(c, &c->d_rinv, BATCH_SLOTS)); A(dev_alloc(c, &c->d_logits_all, (size_t)B * d.vocab));
-    c->bg_cnt_n = (size_t)(std::max(c->nq + 2 * c->nkv, d.d_model) + 127) / 128;
-    c->bg_part_wgs = c->bg_cnt_n * 8;                   // (up to 8 slices)
-    A(dev_alloc(c, &c->d_bg_part, c->bg_part_wgs * 16 * 128)); A(dev_alloc(c, &c->d_bg_cnt, c->bg_cnt_n));
+    {                                                   // partial sums: up to 8 slices x 16 slots x (rows padded to a tile group), gate + up
+      const size_t nmax = (size_t)std::max(std::max(c->nq + 2 * c->nkv, d.d_model), 2 * d.d_ffn);
+      c->bg_cnt_n = nmax / (5 * 16) + 2;
+      c->bg_part_floats = (size_t)8 * 16 * (nmax + 8 * 16 * 2);
+    }
+    A(dev_alloc(c, &c->d_bg_part, c->bg_part_floats)); A(dev_alloc(c, &c->d_bg_cnt, c->bg_cnt_n));
   }
   if (B > 1 && rc == FIRST_OK) {
     (void)hipMemset(c->d_xh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_xl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
     (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
     (void)hipMemset(c->d_bg_cnt, 0, c->bg_cnt_n * sizeof(unsigned));
-    for (const void* fn : {reinterpret_cast<const void*>(&k_bgemv_g<BG_QKV>), reinterpret_cast<const void*>(&k_bgemv_g<BG_O>),
-                           reinterpret_cast<const void*>(&k_bgemv_g<BG_DN>)})
-      (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+#define FIRST_BGG_ATTR(MODE)                                                                                          \
+  for (const void* fn : {reinterpret_cast<const void*>(&k_bgemv_g<MODE, 8>), reinterpret_cast<const void*>(&k_bgemv_g<MODE, 7>),      \
+                         reinterpret_cast<const void*>(&k_bgemv_g<MODE, 6>), reinterpret_cast<const void*>(&k_bgemv_g<MODE, 5>)})      \
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    FIRST_BGG_ATTR(BG_QKV) FIRST_BGG_ATTR(BG_O) FIRST_BGG_ATTR(BG_DN) FIRST_BGG_ATTR(BG_GU)
+#undef FIRST_BGG_ATTR
   }
   A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
   A(dev_alloc(c, &c->d_topk_part, (size_t)B * ((d.vocab + SMP_CHUNK - 1) / SMP_CHUNK) * SMP_KMAX));
