@@ -27,8 +27,9 @@ no biases).  The paper does not restate those; the readings taken are:
 Pins (tests/test_oracle_pins.py): independent no-cache recompute with library attention,
 all-skip closed form, pruned-model equivalence, zero-router tie, prefill independent of the
 routers, RoPE relative-position property, a scalar pure-Python twin on a toy model, and the
-paper's printed router-parameter fractions.  The paper prints no worked numeric example, so
-absolute logit values are pinned only through those.
+paper's printed router-parameter fractions; KV elision (`elide_kv`) through the same pruned
+model and a byte count done by hand.  The paper prints no worked numeric example, so absolute
+logit values are pinned only through those.
 """
 from __future__ import annotations
 
@@ -178,9 +179,15 @@ def lm_logits(desc, weights, h: torch.Tensor, cdt) -> torch.Tensor:
 # --------------------------------------------------------------------------- prefill + route
 def prefill_route(desc, weights, router: torch.Tensor, ids: torch.Tensor,
                   cdt=torch.float64, keep_router_inputs: bool = False,
-                  progress=None) -> OracleState:
+                  progress=None, elide_kv: bool = False) -> OracleState:
     """Runs every layer on the prompt (no skipping), scores router i on the stream entering
-    layer i, thresholds, and returns the first token from the full model (Section 4.3)."""
+    layer i, thresholds, and returns the first token from the full model (Section 4.3).
+
+    elide_kv: router i is evaluated on the input of layer i (Section 4.1), so mask_i is fixed
+    before layer i runs, and decode never touches the KV of a layer whose mask is 0 (Section
+    4.3: the prefill decision is reused by every later token).  With elide_kv the K/V a skipped
+    layer formed for its own prompt attention is therefore dropped once the layer is done
+    (K[i] = V[i] = None); nothing else changes."""
     n = int(ids.numel())
     pos = torch.arange(n)
     H = weights["embed"][ids.long()].to(cdt)                        # H_0
@@ -192,8 +199,9 @@ def prefill_route(desc, weights, router: torch.Tensor, ids: torch.Tensor,
         if keep_router_inputs:
             taps.append(H.clone())
         H, K, V = block(desc, weights["layers"][i], H, pos, None, None, cdt)
-        Ks.append(K)
-        Vs.append(V)
+        stored = not (elide_kv and mask[i] == 0)
+        Ks.append(K if stored else None)
+        Vs.append(V if stored else None)
         if progress is not None:
             progress(f"oracle prefill layer {i + 1}/{desc.n_layers}")
     logits = lm_logits(desc, weights, H[n - 1], cdt)
@@ -234,3 +242,18 @@ def generate(desc, weights, st: OracleState, n_steps: int, cdt=torch.float64, fo
         toks.append(nt)
         t = nt
     return torch.stack(logits_all), toks
+
+
+# --------------------------------------------------------------------------- KV elision accounting
+def kv_layers_stored(masks) -> List[int]:
+    """Layers whose prompt KV must be persisted for a set of live sequences: those kept by at
+    least one of them (a slice of the cache belongs to a layer, all sequences share it)."""
+    masks = [list(m) for m in masks]
+    return [i for i in range(len(masks[0])) if any(int(m[i]) for m in masks)]
+
+
+def kv_bytes(desc, n_layers_stored: int, n_tokens: int) -> int:
+    """Bytes of K and V for n_tokens positions in n_layers_stored layers, in the KV storage type."""
+    elem = torch.empty(0, dtype=KV_DTYPES[desc.dtype]).element_size()
+    return 2 * n_layers_stored * n_tokens * desc.n_kv_heads * desc.head_dim * elem
+

@@ -419,3 +419,64 @@ def test_skip_mask_generator_keeps_first_and_last():
         assert m[0] == 1 and m[-1] == 1 and int(m.sum()) == 16
     with pytest.raises(ValueError):
         make_skip_mask(4, 3, 0)
+
+
+def test_kv_elision_drops_exactly_the_skipped_layers_and_changes_no_result():
+    """Section 4.1 + 4.3: the decision of router i precedes layer i and is final, so the KV of a
+    skipped layer is never read again.  Pins: same rho / mask / first token with and without
+    elision; the kept layers' KV identical; decode identical; and the elided state is all a
+    model pruned to the kept layers needs."""
+    desc = CONFIGS["mini_bf16"]
+    w = make_weights(desc, 71)
+    prompt = make_prompt(desc.vocab, 23, 71)
+    for seed in range(71, 120):                       # a router draw that keeps some layers and skips some
+        router = make_router(desc, seed, std=5.0)
+        full = O.prefill_route(desc, w, router, prompt)
+        if 0 < int(full.mask.sum()) < desc.n_layers:
+            break
+    el = O.prefill_route(desc, w, router, prompt, elide_kv=True)
+    assert torch.equal(full.rho, el.rho) and torch.equal(full.mask, el.mask)
+    assert torch.equal(full.logits, el.logits) and full.token == el.token
+    for i in range(desc.n_layers):
+        if int(full.mask[i]):
+            assert torch.equal(full.K[i], el.K[i]) and torch.equal(full.V[i], el.V[i])
+        else:
+            assert el.K[i] is None and el.V[i] is None
+    kept = O.compact_kept(el.mask)
+    pd = desc.with_(n_layers=len(kept))
+    pw = dict(w)
+    pw["layers"] = [w["layers"][i] for i in kept]
+    pst = O.OracleState(K=[el.K[i].clone() for i in kept], V=[el.V[i].clone() for i in kept], rho=el.rho[kept],
+                        mask=torch.ones(len(kept), dtype=torch.uint8), n_prompt=el.n_prompt, pos=el.pos,
+                        hidden=el.hidden, logits=el.logits, token=el.token)
+    lg_f, tk_f = O.generate(desc, w, full, 5)
+    lg_e, tk_e = O.generate(desc, w, el, 5)
+    lg_p, tk_p = O.generate(pd, pw, pst, 5)
+    assert torch.equal(lg_f, lg_e) and tk_f == tk_e
+    assert torch.equal(lg_e, lg_p) and tk_e == tk_p
+    # a layer whose prompt KV was dropped cannot be switched on afterwards
+    skipped = [i for i in range(desc.n_layers) if not int(el.mask[i])]
+    m = el.mask.clone()
+    m[skipped[0]] = 1
+    el.set_mask(m)
+    with pytest.raises(ValueError):
+        O.decode_step(desc, w, el, 3)
+
+
+def test_kv_elision_accounting():
+    """Bytes by hand for the 8B shape: K and V of one token in one layer are 2 * 8 heads * 128 * 2 B =
+    4 KiB, so a 1024-token prompt holds 128 MiB over 32 layers and 96 MiB when 8 layers are skipped
+    (saving = skip fraction).  Slices are per layer: a batch stores the union of its kept layers."""
+    desc = ModelDesc(n_layers=32, d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=14336,
+                     vocab=128256, dtype="bf16")
+    assert O.kv_bytes(desc, 1, 1) == 4096
+    assert O.kv_bytes(desc, 32, 1024) == 128 << 20
+    mask = make_skip_mask(32, 8, 5)
+    stored = O.kv_layers_stored([mask])
+    assert stored == [i for i in range(32) if mask[i]] and len(stored) == 24
+    assert O.kv_bytes(desc, len(stored), 1024) == 96 << 20
+    assert O.kv_bytes(desc, len(stored), 1024) / O.kv_bytes(desc, 32, 1024) == 1 - 8 / 32
+    masks = [[1, 0, 0, 1, 0], [1, 1, 0, 0, 0], [0, 0, 0, 1, 0]]
+    assert O.kv_layers_stored(masks) == [0, 1, 3]
+    assert O.kv_layers_stored([[0, 0]]) == []
+
