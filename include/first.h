@@ -90,6 +90,8 @@ typedef struct first_model_desc {
   int32_t kv_page_tokens; /* tokens per KV page (16)                                       */
   int32_t max_batch;      /* sequences the context can hold at once                        */
   int32_t max_seq_len;    /* prompt + generated tokens per sequence                        */
+  int32_t kv_layer_slots; /* 0 (or >= n_layers): KV pages for every layer.  1..n_layers-1:
+                           * skip-aware KV elision, see first_create                         */
 } first_model_desc;
 
 /* Weights.  The struct and the per-layer pointer arrays are HOST memory (copied at create);
@@ -114,7 +116,20 @@ typedef struct first_weights {
  * (max_batch * ceil(max_seq_len / kv_page_tokens) pages per layer), page tables and
  * workspaces.  hip_stream is a hipStream_t; NULL makes the context create a private stream
  * that keeps the null stream's implicit ordering (graphs cannot be captured on the null
- * stream itself). */
+ * stream itself).
+ *
+ * Skip-aware KV elision (kv_layer_slots in 1..n_layers-1).  Router i reads the input of
+ * layer i (Section 4.1), so its decision is known before the layer stores anything, and decode
+ * never reads the KV of a layer it skips (Section 4.3 item 2).  The pool then holds
+ * kv_layer_slots layer slices plus one scratch slice instead of n_layers slices: during
+ * first_prefill_route a layer receives a slice when the first sequence's router keeps it, and
+ * the prompt pass of a layer no sequence keeps (prefill never skips) puts its K/V in the
+ * scratch slice, overwritten by the next such layer.  Slices are per layer, shared by the live
+ * sequences: the memory used is (number of layers kept by at least one sequence + 1) slices.
+ * If the routers keep more layers than there are slots first_prefill_route returns
+ * FIRST_ERR_CAPACITY and no sequence is live.  first_set_mask may then only keep layers whose
+ * KV was stored for that sequence, and first_kv_read / first_kv_write refuse the others
+ * (FIRST_ERR_STATE).  Results are bit-identical to a context without elision. */
 int first_create(const first_model_desc *desc, const first_weights *weights, void *hip_stream,
                  first_ctx **out);
 int first_destroy(first_ctx *ctx);
@@ -200,6 +215,12 @@ int first_get_hidden(first_ctx *ctx, float *hidden_out);
  * 0..n_pages-1.  Legal only while no sequence is live.  n_pages via first_num_pages. */
 int first_set_page_order(first_ctx *ctx, const int32_t *perm);
 int first_num_pages(first_ctx *ctx, int32_t *n_pages_out /*HOST*/);
+
+/* Size of the KV page pool and its layer slices (see first_create on elision).  All outputs
+ * HOST, each may be NULL: pool_bytes = bytes allocated for KV pages (slots + scratch slice),
+ * layer_slots = slices available to layers (n_layers without elision), slots_in_use = slices
+ * handed to layers by the latest first_prefill_route (n_layers without elision). */
+int first_kv_usage(first_ctx *ctx, int64_t *pool_bytes, int32_t *layer_slots, int32_t *slots_in_use);
 
 /* ---- single fused ops, exposed for unit parity tests and kernel-level rooflines ---------- */
 

@@ -15,7 +15,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len"]
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len", "first_kv_usage"]
 
 
 class FirstError(RuntimeError):
@@ -29,7 +29,7 @@ class _Desc(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
                 ("vocab", C.c_int32), ("dtype", C.c_int32), ("rope_base", C.c_float),
                 ("rms_eps", C.c_float), ("kv_page_tokens", C.c_int32), ("max_batch", C.c_int32),
-                ("max_seq_len", C.c_int32)]
+                ("max_seq_len", C.c_int32), ("kv_layer_slots", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -81,7 +81,7 @@ class FirstContext:
     the device); `router` a device fp32 [L, D] tensor."""
 
     def __init__(self, desc, weights: dict, router: torch.Tensor, max_batch: int, max_seq_len: int,
-                 kv_page_tokens: int = 16, stream: Optional[torch.cuda.Stream] = None):
+                 kv_page_tokens: int = 16, stream: Optional[torch.cuda.Stream] = None, kv_layer_slots: int = 0):
         self.lib = load_library()
         self.desc = desc
         self.stream = stream
@@ -90,7 +90,8 @@ class FirstContext:
         L = desc.n_layers
         self._keep = [weights, router]                       # keep the borrowed tensors alive
         d = _Desc(L, desc.d_model, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.d_ffn, desc.vocab,
-                  DTYPE_CODES[desc.dtype], desc.rope_base, desc.rms_eps, kv_page_tokens, max_batch, max_seq_len)
+                  DTYPE_CODES[desc.dtype], desc.rope_base, desc.rms_eps, kv_page_tokens, max_batch, max_seq_len,
+                  kv_layer_slots)
         w = _Weights()
         for name in ("embed", "lm_head"):
             _check_dev(weights[name], wdt, name, desc.vocab * desc.d_model)
@@ -244,6 +245,12 @@ class FirstContext:
         n = C.c_int32()
         self._chk(self.lib.first_num_pages(self.h, C.byref(n)))
         return n.value
+
+    def kv_usage(self):
+        """(bytes of the KV page pool, layer slices available, layer slices in use)."""
+        nbytes, slots, used = C.c_int64(), C.c_int32(), C.c_int32()
+        self._chk(self.lib.first_kv_usage(self.h, C.byref(nbytes), C.byref(slots), C.byref(used)))
+        return nbytes.value, slots.value, used.value
 
     def set_page_order(self, perm: Sequence[int]) -> None:
         arr = (C.c_int32 * len(perm))(*[int(x) for x in perm])

@@ -75,6 +75,15 @@ struct first_ctx {
   std::vector<std::vector<uint8_t>> hmask;
   std::vector<int> free_pages, page_order, h_page_table;
   std::vector<int> seq_npages;
+  // layer slices of the KV pool: layer i's pages live in slice layer_slice[i].  Without elision slice = layer.
+  // With elision (kv_layer_slots < n_layers) a layer gets a slice when the first sequence's router keeps it;
+  // the prompt pass of a layer nobody keeps uses the one scratch slice behind the slots.
+  bool kv_elide = false;
+  int kv_slots = 0, slices_used = 0;
+  std::vector<int> layer_slice;
+  std::vector<std::vector<uint8_t>> has_kv;   // [seq][layer]: the sequence's prompt KV of that layer was stored
+  uint8_t* h_keep = nullptr;                  // pinned: one router decision read back per layer while eliding
+  hipEvent_t ev_keep = nullptr;
   // persistent whole-step kernel (bf16, one live sequence)
   LayerDev* d_layers = nullptr;
   unsigned* d_bar = nullptr;
@@ -161,11 +170,40 @@ hipError_t reset_tagged_exchange(first_ctx* c) {
   return e;
 }
 
+size_t kv_slice_bytes(const first_ctx* c) { return (size_t)c->n_pages * c->page_elems * c->elem; }
+
+// Page pool of layer i: its slice, or the scratch slice when the layer has none (only while eliding).
+char* kv_base(const first_ctx* c, int i) {
+  const int s = c->layer_slice[i] >= 0 ? c->layer_slice[i] : c->kv_slots;
+  return c->kv_pool + (size_t)s * kv_slice_bytes(c);
+}
+
+void reset_layer_slices(first_ctx* c) {
+  const int L = c->d.n_layers;
+  c->layer_slice.resize(L);
+  for (int i = 0; i < L; ++i) c->layer_slice[i] = c->kv_elide ? -1 : i;
+  c->slices_used = c->kv_elide ? 0 : L;
+  for (auto& h : c->has_kv) std::fill(h.begin(), h.end(), 0);
+}
+
 void release_sequences(first_ctx* c) {
   c->B = 0;
   c->free_pages.assign(c->page_order.rbegin(), c->page_order.rend());   // pop_back hands out page_order[0] first
   std::fill(c->seq_npages.begin(), c->seq_npages.end(), 0);
   std::fill(c->decoded.begin(), c->decoded.end(), 0);
+  reset_layer_slices(c);
+}
+
+// Per-layer pointers of the persistent kernel (weights, gains, the layer's page pool).  The stream must be idle.
+hipError_t upload_layer_table(first_ctx* c) {
+  const int L = c->d.n_layers;
+  std::vector<LayerDev> ld(L);
+  for (int i = 0; i < L; ++i) {
+    const LayerPtrs& l = c->layers[i];
+    ld[i] = LayerDev{(const bf16*)l.wq, (const bf16*)l.wk, (const bf16*)l.wv, (const bf16*)l.wo, (const bf16*)l.wg,
+                     (const bf16*)l.wu, (const bf16*)l.wd, l.g_attn, l.g_mlp, (bf16*)kv_base(c, i)};
+  }
+  return hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
 }
 
 void drop_graphs(first_ctx* c) {
@@ -193,7 +231,7 @@ void set_layer(const first_ctx* c, DecParams& p, int i) {
   const LayerPtrs& l = c->layers[i];
   p.wq = l.wq; p.wk = l.wk; p.wv = l.wv; p.wo = l.wo; p.wg = l.wg; p.wu = l.wu; p.wd = l.wd;
   p.g_attn = l.g_attn; p.g_mlp = l.g_mlp;
-  p.kv_layer = c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem;
+  p.kv_layer = kv_base(c, i);
 }
 
 template <typename WT>
@@ -524,13 +562,16 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
   hipLaunchKernelGGL(k_rope_table, dim3((T * c->half + WG - 1) / WG), dim3(WG), 0, st, c->d_theta, c->p_cs, T, c->half);
   for (int i = 0; i < L; ++i) {
     const LayerPtrs& l = c->layers[i];
-    WT* pool = reinterpret_cast<WT*>(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem);
     // router i reads the stream entering layer i, in the same pass as the attention norm
     const bool hl = d.dtype == FIRST_DTYPE_BF16;   // activations leave their producers split for the matrix cores
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_attn,
                        c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
     hipLaunchKernelGGL(k_router_reduce, dim3(1), dim3(WG), 0, st, c->p_sig, T, c->d_rho + (size_t)b * L + i,
                        c->d_mask + (size_t)b * L + i);
+    if (c->kv_elide) {   // the decision is known before the layer stores anything (Section 4.1): fetch it while Q/K/V run
+      HIPCHK(c, hipMemcpyAsync(c->h_keep, c->d_mask + (size_t)b * L + i, 1, hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipEventRecord(c->ev_keep, st));
+    }
     int rc;
     auto gemm = [&](const float* A32, const bf16* Ah, const bf16* Al, const void* W, float* C, int N, int K, int acc) {
       return hl ? launch_gemm_hl(c, st, Ah, Al, W, C, T, N, K, acc) : launch_gemm(c, st, d.dtype, A32, W, C, T, N, K, acc, true);
@@ -538,6 +579,16 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wq, c->p_q, c->nq, D, 0))) return rc;
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wk, c->p_k, c->nkv, D, 0))) return rc;
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wv, c->p_v, c->nkv, D, 0))) return rc;
+    if (c->kv_elide) {
+      HIPCHK(c, hipEventSynchronize(c->ev_keep));
+      if (*c->h_keep && c->layer_slice[i] < 0) {
+        if (c->slices_used >= c->kv_slots)
+          return fail(c, FIRST_ERR_CAPACITY, "first_prefill_route: the routers keep more layers than kv_layer_slots");
+        c->layer_slice[i] = c->slices_used++;
+      }
+    }
+    c->has_kv[b][i] = c->layer_slice[i] >= 0;
+    WT* pool = reinterpret_cast<WT*>(kv_base(c, i));   // a layer without a slice lends its prompt K/V to the scratch slice
     hipLaunchKernelGGL(k_rope_kvwrite<WT>, dim3(T), dim3(WG), 0, st, c->p_q, c->p_k, c->p_v, c->p_cs, pt, pool,
                        c->page_elems, d.n_q_heads, d.n_kv_heads, hd, P, qscale);
     if (c->p_qh && c->prefill_flash) {
@@ -598,7 +649,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   if (d.n_layers < 1 || d.d_model < 8 || d.d_model % 8 || d.n_q_heads < 1 || d.n_kv_heads < 1 ||
       d.n_q_heads % d.n_kv_heads || d.n_q_heads / d.n_kv_heads > 8 || (d.head_dim != 64 && d.head_dim != 128) ||
       d.d_ffn < 8 || d.d_ffn % 8 || d.vocab < 1 || (d.dtype != FIRST_DTYPE_FP32 && d.dtype != FIRST_DTYPE_BF16) ||
-      d.kv_page_tokens < 1 || d.max_batch < 1 || d.max_seq_len < 2 || !(d.rope_base > 0.f) || !(d.rms_eps >= 0.f))
+      d.kv_page_tokens < 1 || d.kv_layer_slots < 0 || d.max_batch < 1 || d.max_seq_len < 2 || !(d.rope_base > 0.f) || !(d.rms_eps >= 0.f))
     return fail(nullptr, FIRST_ERR_ARG, "first_create: unsupported model geometry");
   if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
       !w->mlp_norm || !w->w_gate || !w->w_up || !w->w_down || !w->router)
@@ -639,7 +690,16 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   const int B = d.max_batch, L = d.n_layers, T = d.max_seq_len;
   int rc = FIRST_OK;
   auto A = [&](int r) { if (rc == FIRST_OK) rc = r; };
-  A(dev_alloc(c, &c->kv_pool, (size_t)L * c->n_pages * c->page_elems * c->elem));
+  c->kv_elide = d.kv_layer_slots > 0 && d.kv_layer_slots < L;
+  c->kv_slots = c->kv_elide ? d.kv_layer_slots : L;
+  c->has_kv.assign(B, std::vector<uint8_t>(L, 0));
+  reset_layer_slices(c);
+  A(dev_alloc(c, &c->kv_pool, (size_t)(c->kv_slots + (c->kv_elide ? 1 : 0)) * kv_slice_bytes(c)));
+  if (c->kv_elide && rc == FIRST_OK) {
+    if (hipHostMalloc(reinterpret_cast<void**>(&c->h_keep), 64, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_keep, hipEventDisableTiming) != hipSuccess)
+      rc = fail(c, FIRST_ERR_HIP, "first_create: pinned byte / event for the router decisions");
+  }
   A(dev_alloc(c, &c->d_page_table, (size_t)B * c->max_pages));
   A(dev_alloc(c, &c->d_len, B)); A(dev_alloc(c, &c->d_kept, (size_t)B * L)); A(dev_alloc(c, &c->d_nkept, B));
   A(dev_alloc(c, &c->d_mask, (size_t)B * L)); A(dev_alloc(c, &c->d_rho, (size_t)B * L));
@@ -710,14 +770,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_bar, 0, (size_t)sk_bar_words(c->num_cu) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
-      std::vector<LayerDev> ld(L);
-      for (int i = 0; i < L; ++i) {
-        const LayerPtrs& l = c->layers[i];
-        ld[i] = LayerDev{(const bf16*)l.wq, (const bf16*)l.wk, (const bf16*)l.wv, (const bf16*)l.wo, (const bf16*)l.wg,
-                         (const bf16*)l.wu, (const bf16*)l.wd, l.g_attn, l.g_mlp,
-                         (bf16*)(c->kv_pool + (size_t)i * c->n_pages * c->page_elems * c->elem)};
-      }
-      e = hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
+      e = upload_layer_table(c);
       c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
       const void* fns[2] = {d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128, true>)
                                               : reinterpret_cast<const void*>(&k_step<64, true>),
@@ -746,6 +799,8 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   }
   if (rc != FIRST_OK) {
     for (void* p : c->allocs) (void)hipFree(p);
+    if (c->h_keep) (void)hipHostFree(c->h_keep);
+    if (c->ev_keep) (void)hipEventDestroy(c->ev_keep);
     if (c->own_stream) (void)hipStreamDestroy(c->stream);
     delete c;
     return rc;
@@ -765,6 +820,8 @@ int first_destroy(first_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   drop_graphs(c);
   for (void* p : c->allocs) (void)hipFree(p);
+  if (c->h_keep) (void)hipHostFree(c->h_keep);
+  if (c->ev_keep) (void)hipEventDestroy(c->ev_keep);
   if (c->own_stream) (void)hipStreamDestroy(c->stream);
   delete c;
   return FIRST_OK;
@@ -808,6 +865,7 @@ int first_prefill_route(first_ctx* c, int32_t B, const int32_t* ids, const int32
   if (mask_out) HIPCHK(c, hipMemcpyAsync(mask_out, c->d_mask, (size_t)B * L, hipMemcpyDeviceToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   for (int b = 0; b < B; ++b) c->hmask[b].assign(hm.begin() + (size_t)b * L, hm.begin() + (size_t)(b + 1) * L);
+  if (c->kv_elide && c->step_ok) HIPCHK(c, upload_layer_table(c));   // the layers' slices are new
   return FIRST_OK;
 }
 
@@ -821,6 +879,8 @@ int first_set_mask(first_ctx* c, int32_t seq, const uint8_t* mask) {
     m[i] = mask[i] ? 1 : 0;
     if (c->decoded[seq] && m[i] && !c->hmask[seq][i])
       return fail(c, FIRST_ERR_STATE, "first_set_mask: layer was skipped by earlier decode tokens; its KV has holes");
+    if (m[i] && !c->has_kv[seq][i])
+      return fail(c, FIRST_ERR_STATE, "first_set_mask: the prompt KV of this layer was not stored (kv_layer_slots)");
   }
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(c->d_mask + (size_t)seq * L, m.data(), L, hipMemcpyHostToDevice));
@@ -1000,8 +1060,9 @@ static int kv_tap(first_ctx* c, int seq, int layer, int pos0, int n, float* k, f
   if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_kv: no such live sequence");
   if (layer < 0 || layer >= c->d.n_layers || pos0 < 0 || n < 0 || pos0 + n > c->seq_npages[seq] * c->d.kv_page_tokens)
     return fail(c, FIRST_ERR_ARG, "first_kv: range outside the sequence's pages");
+  if (!c->has_kv[seq][layer]) return fail(c, FIRST_ERR_STATE, "first_kv: the KV of this layer was not stored (kv_layer_slots)");
   if (n == 0) return FIRST_OK;
-  char* pool = c->kv_pool + (size_t)layer * c->n_pages * c->page_elems * c->elem;
+  char* pool = kv_base(c, layer);
   const int* pt = c->d_page_table + (size_t)seq * c->max_pages;
   const first_model_desc& d = c->d;
   if (d.dtype == FIRST_DTYPE_BF16) {
@@ -1071,6 +1132,14 @@ int first_num_pages(first_ctx* c, int32_t* n_pages_out) {
   if (!c) return FIRST_ERR_ARG;
   if (!n_pages_out) return fail(c, FIRST_ERR_ARG, "first_num_pages: null output");
   *n_pages_out = c->n_pages;
+  return FIRST_OK;
+}
+
+int first_kv_usage(first_ctx* c, int64_t* pool_bytes, int32_t* layer_slots, int32_t* slots_in_use) {
+  if (!c) return FIRST_ERR_ARG;
+  if (pool_bytes) *pool_bytes = (int64_t)((size_t)(c->kv_slots + (c->kv_elide ? 1 : 0)) * kv_slice_bytes(c));
+  if (layer_slots) *layer_slots = c->kv_slots;
+  if (slots_in_use) *slots_in_use = c->slices_used;
   return FIRST_OK;
 }
 
