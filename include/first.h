@@ -222,6 +222,41 @@ int first_num_pages(first_ctx *ctx, int32_t *n_pages_out /*HOST*/);
  * handed to layers by the latest first_prefill_route (n_layers without elision). */
 int first_kv_usage(first_ctx *ctx, int64_t *pool_bytes, int32_t *layer_slots, int32_t *slots_in_use);
 
+/* ---- training-side forward pieces (forward values only: no gradients, no optimiser) ------- */
+
+/* Soft-skip forward with the loss terms of router training (Section 4.1).  For each of the B
+ * sequences every layer runs on the whole sequence, and its update enters the stream scaled by
+ * the router's score of the stream that reached it: H_i = H_{i-1} + rho_i * phi_i(H_{i-1})
+ * (the skip connection of the training figure read as an expectation; rounding rho_i gives
+ * Eq. 2 of Section 3).  Then per sequence b:
+ *   terms[b][0] = L_CE  : next-token cross entropy (natural log), mean over the positions j with
+ *                         targets[j] >= 0, of the logits W_lm . RMSNorm(H_L[j]); 0 if none
+ *   terms[b][1] = L_Reg : sum_i ||R_i||^2 over all router weights
+ *   terms[b][2] = L_PP  : sum_i rho_i of this sequence
+ *   terms[b][3] = L_CE + lambda * L_Reg + alpha * L_PP
+ *   ids        DEV  int32 [sum(lens)]  sequences packed back to back
+ *   lens       HOST int32 [B]          1 <= lens[b] <= max_seq_len
+ *   targets    DEV  int32 [sum(lens)]  token to predict at each position, -1 = none
+ *   rho_out    DEV  fp32  [B, L]       (may be NULL)
+ *   terms_out  DEV  fp32  [B, 4]
+ *   hidden_out DEV  fp32  [sum(lens), D]  H_L of every position (may be NULL)
+ * Uses the context's prefill workspace and KV pages: any live sequences are dropped, and none
+ * is live afterwards.  The first call allocates its workspace (one more stream copy, the
+ * logits of 128 positions).  Synchronises the stream before returning. */
+int first_soft_forward(first_ctx *ctx, int32_t B, const int32_t *ids, const int32_t *lens,
+                       const int32_t *targets, float lambda, float alpha, float *rho_out,
+                       float *terms_out, float *hidden_out);
+
+/* LoRA merge (Section 4.2; appendix on the training set-up: rank 8, lora_alpha 32): in place
+ * W += scale * Bm A with scale = lora_alpha / r, so that the adapters cost nothing at
+ * inference.  W DEV [n, k] of dtype (row-major, as in first_weights); A DEV fp32 [r, k];
+ * Bm DEV fp32 [n, r]; k multiple of 8; 1 <= r <= 32.  The rank-r sum is formed in fp32 in
+ * index order and the result rounded once to dtype.  Asynchronous on hip_stream.  A context
+ * created from W before the merge keeps what it copied (tile-order copies of batched decode):
+ * merge first, then create. */
+int first_lora_merge(void *hip_stream, int32_t dtype, void *W, const float *A, const float *Bm,
+                     int32_t n, int32_t k, int32_t r, float scale);
+
 /* ---- single fused ops, exposed for unit parity tests and kernel-level rooflines ---------- */
 
 /* y[r] = sum_k W[r,k] * x[k]  (+ y_in[r] if accumulate).  The decode projection kernel.

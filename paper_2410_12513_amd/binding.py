@@ -15,7 +15,8 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len", "first_kv_usage"]
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len", "first_kv_usage", "first_soft_forward",
+           "first_lora_merge"]
 
 
 class FirstError(RuntimeError):
@@ -149,6 +150,21 @@ class FirstContext:
         self._chk(self.lib.first_prefill_route(self.h, C.c_int32(B), _ptr(ids), lens_a, _ptr(rho), _ptr(mask),
                                                _ptr(hidden), _ptr(logits), _ptr(token)))
 
+    def soft_forward(self, ids: torch.Tensor, lens: Sequence[int], targets: torch.Tensor, lam: float, alpha: float,
+                     terms: torch.Tensor, rho=None, hidden=None) -> None:
+        B, n = len(lens), int(sum(lens))
+        L, D = self.desc.n_layers, self.desc.d_model
+        _check_dev(ids, torch.int32, "ids", n)
+        _check_dev(targets, torch.int32, "targets", n)
+        _check_dev(terms, torch.float32, "terms", B * 4)
+        if rho is not None:
+            _check_dev(rho, torch.float32, "rho", B * L)
+        if hidden is not None:
+            _check_dev(hidden, torch.float32, "hidden", n * D)
+        lens_a = (C.c_int32 * B)(*[int(x) for x in lens])
+        self._chk(self.lib.first_soft_forward(self.h, C.c_int32(B), _ptr(ids), lens_a, _ptr(targets), C.c_float(lam),
+                                              C.c_float(alpha), _ptr(rho), _ptr(terms), _ptr(hidden)))
+
     def set_mask(self, seq: int, mask: Sequence[int]) -> None:
         L = self.desc.n_layers
         if len(mask) != L:
@@ -270,6 +286,19 @@ def op_gemv(W: torch.Tensor, x: torch.Tensor, y: torch.Tensor, accumulate: bool 
     _check_dev(W, W.dtype, "W"); _check_dev(x, torch.float32, "x", k); _check_dev(y, torch.float32, "y", n)
     rc = lib.first_op_gemv(_stream_ptr(stream), C.c_int32(code), _ptr(W), _ptr(x), _ptr(y), C.c_int32(n),
                            C.c_int32(k), C.c_int32(int(accumulate)))
+    if rc != 0:
+        raise FirstError(rc, lib.first_last_error(None).decode())
+
+
+def lora_merge(W: torch.Tensor, A: torch.Tensor, Bm: torch.Tensor, scale: float, stream=None) -> None:
+    """In place W += scale * Bm @ A on the device (W [n, k] bf16 or fp32; A [r, k], Bm [n, r] fp32)."""
+    lib = load_library()
+    code = DTYPE_CODES["bf16" if W.dtype == torch.bfloat16 else "fp32"]
+    n, k = W.shape
+    r = A.shape[0]
+    _check_dev(W, W.dtype, "W"); _check_dev(A, torch.float32, "A", r * k); _check_dev(Bm, torch.float32, "Bm", n * r)
+    rc = lib.first_lora_merge(_stream_ptr(stream), C.c_int32(code), _ptr(W), _ptr(A), _ptr(Bm), C.c_int32(n), C.c_int32(k),
+                              C.c_int32(r), C.c_float(scale))
     if rc != 0:
         raise FirstError(rc, lib.first_last_error(None).decode())
 

@@ -15,6 +15,7 @@
 #include "step_kernel.h"
 #include "decode_batch_kernels.h"
 #include "sample_kernels.h"
+#include "train_kernels.h"
 
 using namespace first;
 
@@ -68,6 +69,8 @@ struct first_ctx {
   int p_tp = 0;                           // key pitch of p_vt / rows of p_kc (max_seq_len padded to the key tile)
   int prefill_flash = 1;                  // FIRST_OPT_PREFILL_ATTN
   float2* p_cs = nullptr;
+  // soft-skip forward (first_soft_forward; allocated at its first call)
+  float *p_Hs = nullptr, *p_lg = nullptr, *p_ce = nullptr;
   // host state
   int B = 0;
   std::vector<int> hlen;
@@ -543,7 +546,8 @@ void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int
 
 // Prefill of one sequence: T prompt tokens at ids, all layers, routers scored on the way.
 template <typename WT>
-int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, float* logits_out, int* token_out) {
+int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, float* logits_out, int* token_out,
+                bool soft = false) {
   const first_model_desc& d = c->d;
   hipStream_t st = c->stream;
   const int D = d.d_model, F = d.d_ffn, L = d.n_layers, hd = d.head_dim, P = d.kv_page_tokens;
@@ -568,7 +572,9 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
                        c->router + (size_t)i * D, x, c->p_sig, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
     hipLaunchKernelGGL(k_router_reduce, dim3(1), dim3(WG), 0, st, c->p_sig, T, c->d_rho + (size_t)b * L + i,
                        c->d_mask + (size_t)b * L + i);
-    if (c->kv_elide) {   // the decision is known before the layer stores anything (Section 4.1): fetch it while Q/K/V run
+    if (soft)            // the stream entering the layer, for H = Hprev + rho (phi(Hprev))
+      HIPCHK(c, hipMemcpyAsync(c->p_Hs, c->p_H, (size_t)T * D * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (c->kv_elide && !soft) {   // the decision is known before the layer stores anything (Section 4.1): fetch it while Q/K/V run
       HIPCHK(c, hipMemcpyAsync(c->h_keep, c->d_mask + (size_t)b * L + i, 1, hipMemcpyDeviceToHost, st));
       HIPCHK(c, hipEventRecord(c->ev_keep, st));
     }
@@ -579,7 +585,7 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wq, c->p_q, c->nq, D, 0))) return rc;
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wk, c->p_k, c->nkv, D, 0))) return rc;
     if ((rc = gemm(x, c->p_xh, c->p_xl, l.wv, c->p_v, c->nkv, D, 0))) return rc;
-    if (c->kv_elide) {
+    if (c->kv_elide && !soft) {
       HIPCHK(c, hipEventSynchronize(c->ev_keep));
       if (*c->h_keep && c->layer_slice[i] < 0) {
         if (c->slices_used >= c->kv_slots)
@@ -613,6 +619,13 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     else
       hipLaunchKernelGGL(k_silu_mul<float>, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, z, (size_t)T * F);
     if ((rc = gemm(z, c->p_zh, c->p_zl, l.wd, c->p_H, D, F, 1))) return rc;
+    if (soft)
+      hipLaunchKernelGGL(k_soft_blend, dim3((unsigned)std::min<size_t>(((size_t)T * D + WG - 1) / WG, 4096)), dim3(WG), 0, st,
+                         c->p_H, c->p_Hs, c->d_rho + (size_t)b * L + i, (size_t)T * D);
+  }
+  if (soft) {
+    HIPCHK(c, hipGetLastError());
+    return FIRST_OK;
   }
   // last position -> decode residual slot of this sequence (+ optional copy out), first token
   hipLaunchKernelGGL(k_copy_f32, dim3((D + WG - 1) / WG), dim3(WG), 0, st, c->p_H + (size_t)(T - 1) * D,
@@ -1140,6 +1153,97 @@ int first_kv_usage(first_ctx* c, int64_t* pool_bytes, int32_t* layer_slots, int3
   if (pool_bytes) *pool_bytes = (int64_t)((size_t)(c->kv_slots + (c->kv_elide ? 1 : 0)) * kv_slice_bytes(c));
   if (layer_slots) *layer_slots = c->kv_slots;
   if (slots_in_use) *slots_in_use = c->slices_used;
+  return FIRST_OK;
+}
+
+constexpr int SOFT_ROWS = 128;   // positions whose logits are formed at a time in first_soft_forward
+
+int first_soft_forward(first_ctx* c, int32_t B, const int32_t* ids, const int32_t* lens, const int32_t* targets, float lambda,
+                       float alpha, float* rho_out, float* terms_out, float* hidden_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!ids || !lens || !targets || !terms_out) return fail(c, FIRST_ERR_ARG, "first_soft_forward: null ids/lens/targets/terms");
+  if (B < 1 || B > c->d.max_batch) return fail(c, FIRST_ERR_CAPACITY, "first_soft_forward: batch exceeds max_batch");
+  for (int b = 0; b < B; ++b) {
+    if (lens[b] < 1) return fail(c, FIRST_ERR_ARG, "first_soft_forward: empty sequence");
+    if (lens[b] > c->d.max_seq_len) return fail(c, FIRST_ERR_CAPACITY, "first_soft_forward: sequence longer than max_seq_len");
+  }
+  const first_model_desc& d = c->d;
+  const int L = d.n_layers, P = d.kv_page_tokens, D = d.d_model, V = d.vocab;
+  hipStream_t st = c->stream;
+  if (!c->p_Hs) {
+    int rc = dev_alloc(c, &c->p_Hs, (size_t)d.max_seq_len * D);
+    if (rc == FIRST_OK) rc = dev_alloc(c, &c->p_lg, (size_t)SOFT_ROWS * V);
+    if (rc == FIRST_OK) rc = dev_alloc(c, &c->p_ce, (size_t)d.max_seq_len);
+    if (rc != FIRST_OK) { c->p_Hs = nullptr; return rc; }
+  }
+  release_sequences(c);
+  drop_graphs(c);
+  // the layers' own attention reads K/V through the page tables: pages for every sequence, as a prefill would take them
+  for (int b = 0; b < B; ++b)
+    for (int need = (lens[b] + P - 1) / P; c->seq_npages[b] < need;)
+      if (alloc_page(c, b) < 0) return fail(c, FIRST_ERR_CAPACITY, "first_soft_forward: out of KV pages");
+  HIPCHK(c, hipMemcpyAsync(c->d_page_table, c->h_page_table.data(), c->h_page_table.size() * sizeof(int),
+                           hipMemcpyHostToDevice, st));
+  HIPCHK(c, hipStreamSynchronize(st));
+  const bool hl = d.dtype == FIRST_DTYPE_BF16;
+  size_t off = 0;
+  for (int b = 0; b < B; ++b) {
+    const int T = lens[b];
+    int rc = hl ? prefill_one<bf16>(c, b, ids + off, T, nullptr, nullptr, nullptr, true)
+                : prefill_one<float>(c, b, ids + off, T, nullptr, nullptr, nullptr, true);
+    if (rc) return rc;
+    if (hidden_out)
+      HIPCHK(c, hipMemcpyAsync(hidden_out + off * D, c->p_H, (size_t)T * D * sizeof(float), hipMemcpyDeviceToDevice, st));
+    // logits of every position = W_lm . RMSNorm(H_L; g_final), SOFT_ROWS positions at a time, then their cross entropy
+    float* x = reinterpret_cast<float*>(c->p_x);
+    hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, c->g_final,
+                       (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
+    for (int r0 = 0; r0 < T; r0 += SOFT_ROWS) {
+      const int rows = std::min(SOFT_ROWS, T - r0);
+      rc = hl ? launch_gemm_hl(c, st, c->p_xh + (size_t)r0 * D, c->p_xl + (size_t)r0 * D, c->lm_head, c->p_lg, rows, V, D, 0)
+              : launch_gemm(c, st, d.dtype, x + (size_t)r0 * D, c->lm_head, c->p_lg, rows, V, D, 0, true);
+      if (rc) return rc;
+      hipLaunchKernelGGL(k_ce_rows, dim3(rows), dim3(WG), 0, st, c->p_lg, targets + off + r0, c->p_ce + r0, V);
+    }
+    hipLaunchKernelGGL(k_loss_terms, dim3(1), dim3(WG), 0, st, c->p_ce, targets + off, T, V, c->d_rho + (size_t)b * L, L,
+                       c->router, (size_t)L * D, lambda, alpha, terms_out + (size_t)b * 4);
+    HIPCHK(c, hipGetLastError());
+    off += T;
+  }
+  if (rho_out) HIPCHK(c, hipMemcpyAsync(rho_out, c->d_rho, (size_t)B * L * sizeof(float), hipMemcpyDeviceToDevice, st));
+  HIPCHK(c, hipStreamSynchronize(st));
+  release_sequences(c);          // a training pass leaves no sequence to decode
+  return FIRST_OK;
+}
+
+int first_lora_merge(void* hip_stream, int32_t dtype, void* W, const float* A, const float* Bm, int32_t n, int32_t k, int32_t r,
+                     float scale) {
+  if (!W || !A || !Bm || n < 1 || k < 8 || k % 8 || r < 1 || r > LM_RMAX ||
+      (dtype != FIRST_DTYPE_FP32 && dtype != FIRST_DTYPE_BF16)) {
+    g_create_error = "first_lora_merge: null pointer, k not a multiple of 8, rank outside 1..32, or unknown dtype";
+    return FIRST_ERR_ARG;
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int chunks = (k + LM_COLS - 1) / LM_COLS;
+  const int want_y = std::max(1, (4 * device_cus() + chunks - 1) / chunks);          // about four workgroups per CU
+  const int rows_per_wg = std::max(2, ((n + want_y - 1) / want_y + 1) & ~1);
+  const dim3 grid(chunks, (n + rows_per_wg - 1) / rows_per_wg);
+  const size_t lds = (size_t)r * LM_COLS * sizeof(float);
+  hipError_t e;
+  if (dtype == FIRST_DTYPE_BF16) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lora_merge<bf16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+      hipLaunchKernelGGL(k_lora_merge<bf16>, grid, dim3(WG), lds, st, reinterpret_cast<bf16*>(W), A, Bm, n, k, r, scale, rows_per_wg);
+  } else {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lora_merge<float>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+      hipLaunchKernelGGL(k_lora_merge<float>, grid, dim3(WG), lds, st, reinterpret_cast<float*>(W), A, Bm, n, k, r, scale, rows_per_wg);
+  }
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_create_error = std::string("first_lora_merge: ") + hipGetErrorString(e);
+    return FIRST_ERR_HIP;
+  }
   return FIRST_OK;
 }
 
