@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--per-op", action="store_true", help="one kernel per fused op instead of the persistent kernel")
     ap.add_argument("--sample", action="store_true",
                     help="also time the headline mask with the paper's decoding rule (temperature 0.8, top-k 10) instead of greedy")
+    ap.add_argument("--train-forward", action="store_true",
+                    help="also time the training-side pieces: soft-skip forward + loss terms over the prompt, LoRA merge of the gate matrices")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -132,6 +134,37 @@ def main():
         sampled = {"temperature": 0.8, "top_k": 10, "kept_layers": head["kept_layers"], "ms_per_step": ms,
                    "tokens_per_s": 1000.0 / ms, "greedy_ms_per_step": head["ms_per_step"]}
 
+    train = None
+    if args.train_forward:
+        # soft-skip forward with all three loss terms over the workload's prompt (every layer runs on every
+        # position, plus the LM head on every position), then a rank-8 merge into each layer's gate matrix
+        targets = torch.roll(prompt, -1).to(torch.int32)
+        targets[-1] = -1
+        terms = torch.zeros(1, 4, device="cuda")
+        ctx.soft_forward(prompt, [n_prompt], targets, 0.01, 0.05, terms)          # allocates its workspace
+        ev0.record(stream)
+        ctx.soft_forward(prompt, [n_prompt], targets, 0.01, 0.05, terms)
+        ev1.record(stream)
+        ev1.synchronize()
+        sf_ms = ev0.elapsed_time(ev1)
+        flops = 2.0 * n_prompt * (L * desc.layer_params + desc.vocab * desc.d_model)
+        gen = torch.Generator(device="cpu").manual_seed(seed)
+        A = (torch.randn(8, desc.d_model, generator=gen) * 0.01).cuda()
+        Bz = torch.zeros(desc.d_ffn, 8, device="cuda")                             # B = 0: the weights stay what they are
+        with torch.cuda.stream(stream):
+            P.lora_merge(weights["layers"][0]["w_gate"], A, Bz, 4.0, stream=stream)
+            ev0.record(stream)
+            for i in range(L):
+                P.lora_merge(weights["layers"][i]["w_gate"], A, Bz, 4.0, stream=stream)
+            ev1.record(stream)
+        ev1.synchronize()
+        lm_us = ev0.elapsed_time(ev1) * 1e3 / L
+        lm_bytes = 2.0 * desc.d_ffn * desc.d_model * desc.bytes_per_elem
+        train = {"soft_forward": {"tokens": n_prompt, "ms": sf_ms, "tokens_per_s": n_prompt / (sf_ms * 1e-3),
+                                  "tflops": flops / (sf_ms * 1e-3) / 1e12, "terms": [float(x) for x in terms[0].cpu()]},
+                 "lora_merge": {"matrix": [desc.d_ffn, desc.d_model], "rank": 8, "us": lm_us, "bytes": lm_bytes,
+                                "GB/s": lm_bytes / (lm_us * 1e-6) / 1e9, "hbm_frac": lm_bytes / (lm_us * 1e-6) / (HBM_PEAK_GBS * 1e9)}}
+
     # Dominant kernel.  With the persistent path the whole step is ONE kernel (k_step), so its
     # launch duration is the step time measured above with events on the library's stream;
     # with the per-op path it is the gate/up mat-vec, timed below over all layers' weights.
@@ -195,6 +228,7 @@ def main():
         "hbm_roofline_frac_step": head["hbm_frac"],
         "sweep": sweep,
         "sampled_decode": sampled,
+        "train_forward": train,
         "prefill": {"tokens": n_prompt, "ms": prefill_ms,
                     "tflops": (2.0 * n_prompt * L * desc.layer_params + 2.0 * desc.vocab * desc.d_model)
                               / (prefill_ms * 1e-3) / 1e12},

@@ -1226,9 +1226,9 @@ int first_lora_merge(void* hip_stream, int32_t dtype, void* W, const float* A, c
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   const int chunks = (k + LM_COLS - 1) / LM_COLS;
   const int want_y = std::max(1, (4 * device_cus() + chunks - 1) / chunks);          // about four workgroups per CU
-  const int rows_per_wg = std::max(2, ((n + want_y - 1) / want_y + 1) & ~1);
+  const int rows_per_wg = std::min(64, std::max(2 * LM_RG, ((n + want_y - 1) / want_y + 2 * LM_RG - 1) / (2 * LM_RG) * (2 * LM_RG)));
   const dim3 grid(chunks, (n + rows_per_wg - 1) / rows_per_wg);
-  const size_t lds = (size_t)r * LM_COLS * sizeof(float);
+  const size_t lds = ((size_t)r * LM_COLS + (size_t)rows_per_wg * r) * sizeof(float);
   hipError_t e;
   if (dtype == FIRST_DTYPE_BF16) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lora_merge<bf16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -74,50 +74,83 @@ __global__ void __launch_bounds__(WG) k_loss_terms(const float* __restrict__ ce,
 // LoRA merge in place: W[row][col] += scale * sum_j Bm[row][j] * A[j][col]  (W [n, k] row-major in
 // its storage type, Bm [n, r] and A [r, k] fp32).  The sum over j runs in fp32 in index order, the
 // result is rounded once to the storage type.  A workgroup stages the A columns of its chunk
-// (LM_COLS columns, all r rows) in LDS once and walks its share of the rows: W is read and
-// written exactly once, A and Bm come from the caches.
-constexpr int LM_COLS = 1024;      // columns per workgroup: 128 threads x 8 columns, two rows at a time
-constexpr int LM_RMAX = 32;        // largest rank (LDS: r * LM_COLS floats)
+// (LM_COLS columns, all r rows) and the Bm rows of its row range in LDS once; a thread owns 8
+// columns and walks the rows four at a time (four 16-byte loads of W in flight, every A value read
+// from LDS serves four rows).  W is read and written exactly once.
+constexpr int LM_COLS = 1024;      // columns per workgroup: 128 threads x 8 columns, two row groups at a time
+constexpr int LM_RMAX = 32;        // largest rank (LDS: r * LM_COLS floats + the Bm rows)
+constexpr int LM_RG = 4;           // rows per thread and iteration
 
 template <typename WT>
 __global__ void __launch_bounds__(WG) k_lora_merge(WT* __restrict__ W, const float* __restrict__ A, const float* __restrict__ Bm,
                                                    int n, int k, int r, float scale, int rows_per_wg) {
-  extern __shared__ float a_lds[];                       // [r][LM_COLS]
+  extern __shared__ float lm_lds[];                      // A tile [r][LM_COLS], then Bm rows [rows_per_wg][r] (zero beyond n)
+  float* a_lds = lm_lds;
+  float* b_lds = lm_lds + r * LM_COLS;
   const int c0 = blockIdx.x * LM_COLS;
+  const int row0 = blockIdx.y * rows_per_wg, row1 = min(n, row0 + rows_per_wg);
   for (int i = threadIdx.x; i < r * LM_COLS; i += WG) {
     const int j = i / LM_COLS, c = c0 + i % LM_COLS;
     a_lds[i] = c < k ? A[(size_t)j * k + c] : 0.f;
   }
+  for (int i = threadIdx.x; i < rows_per_wg * r; i += WG)
+    b_lds[i] = (row0 + i / r) < row1 ? Bm[(size_t)row0 * r + i] : 0.f;
   __syncthreads();
   const int tc = (threadIdx.x & 127) * 8, half = threadIdx.x >> 7;
   const int col = c0 + tc;
-  const int row0 = blockIdx.y * rows_per_wg, row1 = min(n, row0 + rows_per_wg);
   if (col >= k) return;                                  // k is a multiple of 8: a thread's 8 columns are in or out together
-  for (int row = row0 + half; row < row1; row += 2) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const float* b = Bm + (size_t)row * r;
+  constexpr int NV = sizeof(WT) == 2 ? 1 : 2;            // 16-byte vectors per 8 elements
+  for (int rb = half * LM_RG; row0 + rb < row1; rb += 2 * LM_RG) {
+    uint4 raw[LM_RG][NV];
+#pragma unroll
+    for (int q = 0; q < LM_RG; ++q) {
+      const int row = min(row0 + rb + q, row1 - 1);      // rows past the end re-read the last one and are not stored
+      const uint4* w = reinterpret_cast<const uint4*>(W + (size_t)row * k + col);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) raw[q][v] = w[v];
+    }
+    float acc[LM_RG][8];
+#pragma unroll
+    for (int q = 0; q < LM_RG; ++q)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
     for (int j = 0; j < r; ++j) {
-      const float bj = b[j];
       const float4 a0 = *reinterpret_cast<const float4*>(a_lds + j * LM_COLS + tc);
       const float4 a1 = *reinterpret_cast<const float4*>(a_lds + j * LM_COLS + tc + 4);
-      acc[0] = fmaf(bj, a0.x, acc[0]); acc[1] = fmaf(bj, a0.y, acc[1]); acc[2] = fmaf(bj, a0.z, acc[2]); acc[3] = fmaf(bj, a0.w, acc[3]);
-      acc[4] = fmaf(bj, a1.x, acc[4]); acc[5] = fmaf(bj, a1.y, acc[5]); acc[6] = fmaf(bj, a1.z, acc[6]); acc[7] = fmaf(bj, a1.w, acc[7]);
-    }
-    WT* w = W + (size_t)row * k + col;
-    if constexpr (sizeof(WT) == 2) {
-      float f[8];
-      load_vec(w, f);
-      uint16_t o[8];
+      const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = f2bf(fmaf(scale, acc[e], f[e]));
-      *reinterpret_cast<uint4*>(w) = make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16),
-                                                o[4] | ((uint32_t)o[5] << 16), o[6] | ((uint32_t)o[7] << 16));
-    } else {
-      float4 w0 = *reinterpret_cast<const float4*>(w), w1 = *reinterpret_cast<const float4*>(w + 4);
-      w0.x = fmaf(scale, acc[0], w0.x); w0.y = fmaf(scale, acc[1], w0.y); w0.z = fmaf(scale, acc[2], w0.z); w0.w = fmaf(scale, acc[3], w0.w);
-      w1.x = fmaf(scale, acc[4], w1.x); w1.y = fmaf(scale, acc[5], w1.y); w1.z = fmaf(scale, acc[6], w1.z); w1.w = fmaf(scale, acc[7], w1.w);
-      *reinterpret_cast<float4*>(w) = w0;
-      *reinterpret_cast<float4*>(w + 4) = w1;
+      for (int q = 0; q < LM_RG; ++q) {
+        const float bj = b_lds[(rb + q) * r + j];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[q][e] = fmaf(bj, a[e], acc[q][e]);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < LM_RG; ++q) {
+      const int row = row0 + rb + q;
+      if (row >= row1) break;
+      uint4* w = reinterpret_cast<uint4*>(W + (size_t)row * k + col);
+      if constexpr (sizeof(WT) == 2) {
+        const uint32_t u[4] = {raw[q][0].x, raw[q][0].y, raw[q][0].z, raw[q][0].w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t lo = f2bf(fmaf(scale, acc[q][2 * e], __uint_as_float(u[e] << 16)));
+          const uint32_t hi = f2bf(fmaf(scale, acc[q][2 * e + 1], __uint_as_float(u[e] & 0xffff0000u)));
+          o[e] = lo | (hi << 16);
+        }
+        w[0] = make_uint4(o[0], o[1], o[2], o[3]);
+      } else {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+          uint4 x = raw[q][v];
+          x.x = __float_as_uint(fmaf(scale, acc[q][4 * v + 0], __uint_as_float(x.x)));
+          x.y = __float_as_uint(fmaf(scale, acc[q][4 * v + 1], __uint_as_float(x.y)));
+          x.z = __float_as_uint(fmaf(scale, acc[q][4 * v + 2], __uint_as_float(x.z)));
+          x.w = __float_as_uint(fmaf(scale, acc[q][4 * v + 3], __uint_as_float(x.w)));
+          w[v] = x;
+        }
+      }
     }
   }
 }
