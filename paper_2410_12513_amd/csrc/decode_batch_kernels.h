@@ -30,7 +30,17 @@ struct BatchParams {
   bf16* xl;             // low halves
   bf16* zh;             // MLP activation (written by gate/up, read by down), high halves, same order
   bf16* zl;             //                       low halves
+  bf16* x2h;            // attention output (read by the output projection), high halves, same order
+  bf16* x2l;            //                       low halves
   float* rinv;          // [BATCH_SLOTS] 1/rms of the vector that was split last (norm ops)
+  // The output and down projections can leave the NEXT norm op's input behind (k_bgemv_g only): with fuse_gain set
+  // their epilogue also writes the split of (updated h) * fuse_gain into xh / xl and, per tile group, the sum of
+  // squares of its rows of h for every slot into ssq_part [group][BATCH_SLOTS].  The consumer is launched with
+  // ssq_groups = that number of groups and forms 1/rms from the partial sums in a fixed order (bg_rinv_wave) instead of
+  // reading rinv.  Producer and consumer must use the same slot list.
+  const float* fuse_gain;
+  float* ssq_part;
+  int ssq_groups;
   int xpitch;
   float* logits_all;    // [B][V] logits of the step (caller's buffer or the library's)
   // optional copies of the layer's matrices (and of the LM head) in MFMA tile order, see k_tile_weights
@@ -46,6 +56,29 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) {
   return c.b;
 }
 
+// 1/rms of the norm op's input vectors (length K), one value per slot, computed by a whole wave: lane l ends up
+// with the value of slot l / 4.  Either what k_xsplit stored, or formed from the producer's per-tile-group sums of
+// squares: the four lanes of a slot take every fourth group each (eight loads in flight per lane), then the four
+// sums are added in a fixed order - the same in every workgroup and launch.
+__device__ __forceinline__ float bg_rinv_wave(const BatchParams& P, int K, int lane) {
+  const int slot = lane >> 2, q = lane & 3;
+  if (P.ssq_groups <= 0) return P.rinv[slot];
+  float s = 0.f;
+  for (int g0 = q; g0 < P.ssq_groups; g0 += 32) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int gi = g0 + 4 * u;
+      v[u] = gi < P.ssq_groups ? P.ssq_part[gi * BATCH_SLOTS + slot] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  s += __shfl_xor(s, 1, 64);
+  s += __shfl_xor(s, 2, 64);
+  return 1.0f / sqrtf(s / (float)K + P.d.eps);
+}
+
 // hi/lo split of x (times gain) for slot blockIdx.x, elements [blockIdx.y * chunk, +chunk);
 // rinv = 1/sqrt(mean(x^2) + eps) if gain (every workgroup of a slot sums the whole vector, the
 // first one stores the result).  src: 0 = residual stream h, 1 = attention output.
@@ -54,8 +87,8 @@ __global__ void __launch_bounds__(WG) k_xsplit(BatchParams P, int src, int K, in
   const DecParams& p = P.d;
   const int j = blockIdx.x, b = P.seqs.id[j];
   const float* x = src == 0 ? p.h + (size_t)b * p.D : p.attn + (size_t)b * p.Hq * p.hd;
-  bf16* xh = P.xh;
-  bf16* xl = P.xl;
+  bf16* xh = src == 0 ? P.xh : P.x2h;
+  bf16* xl = src == 0 ? P.xl : P.x2l;
   if (gain && blockIdx.y == 0) {
     float ss = 0.f;
     for (int k = threadIdx.x; k < K; k += WG) { const float v = x[k]; ss = fmaf(v, v, ss); }
@@ -112,7 +145,7 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
   lds_barrier();
   // the merged output goes out split into bf16 high and low halves, in the order the output
   // projection's A operand reads (slot = position of the sequence in this pass)
-  SP.xh_out = P.xh; SP.xl_out = P.xl; SP.out_slot = blockIdx.z;
+  SP.xh_out = P.x2h; SP.xl_out = P.x2l; SP.out_slot = blockIdx.z;
   sk_attention<HD, SK_WAVES, false, true>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
 }
 
@@ -473,8 +506,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
         hi[j] = h.v; lo[j] = from_f32<bf16>(v[j] - to_f32(h)).v;
       }
       const size_t at = bg_aidx(blockIdx.z, H * HD + q4);
-      *reinterpret_cast<uint2*>(P.xh + at) = make_uint2(hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16));
-      *reinterpret_cast<uint2*>(P.xl + at) = make_uint2(lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16));
+      *reinterpret_cast<uint2*>(P.x2h + at) = make_uint2(hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16));
+      *reinterpret_cast<uint2*>(P.x2l + at) = make_uint2(lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16));
     }
   }
 }
@@ -557,8 +590,11 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
       else w[t] = bg_row_ptr<MODE>(p, rowc, K, 0);
     }
   }
-  const bf16* xh = (MODE == BG_DN ? P.zh : P.xh) + lane * 8;       // this lane's 16 bytes of block 0 (bg_aidx)
-  const bf16* xl = (MODE == BG_DN ? P.zl : P.xl) + lane * 8;
+  const bf16* xh = (MODE == BG_DN ? P.zh : MODE == BG_O ? P.x2h : P.xh) + lane * 8;       // this lane's 16 bytes of block 0 (bg_aidx)
+  const bf16* xl = (MODE == BG_DN ? P.zl : MODE == BG_O ? P.x2l : P.xl) + lane * 8;
+
+  // norm ops: 1/rms of slot lane / 4 (requested here so that the loads overlap the weight stream)
+  const float rv = (MODE == BG_QKV || MODE == BG_GU || MODE == BG_HEAD) ? bg_rinv_wave(P, K, lane) : 0.f;
 
   f32x4v_t acc[NS];
 #pragma unroll
@@ -642,6 +678,9 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
         acc[i][j] = a;
       }
   }
+  float rinv4[4];                                    // 1/rms of this lane's four slots (4 g + j)
+#pragma unroll
+  for (int j = 0; j < 4; ++j) rinv4[j] = __shfl(rv, (4 * g + j) * 4, 64);
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
     const int row = (group * RT + t) * 16 + n;
@@ -652,17 +691,17 @@ __global__ void __launch_bounds__(BG_THREADS) k_bgemv(BatchParams P, int N, int 
       if (slot >= P.seqs.n) continue;
       const int b = P.seqs.id[slot];
       if (MODE == BG_QKV) {
-        p.qkv[(size_t)b * N + row] = acc[t][j] * P.rinv[slot];
+        p.qkv[(size_t)b * N + row] = acc[t][j] * rinv4[j];
       } else if (MODE == BG_O || MODE == BG_DN) {
         p.h[(size_t)b * p.D + row] += acc[t][j];
       } else if (MODE == BG_GU) {
-        const float r = P.rinv[slot];
+        const float r = rinv4[j];
         const float z = siluf(acc[2 * t][j] * r) * (acc[2 * t + 1][j] * r);
         const bf16 hi = from_f32<bf16>(z);
         P.zh[bg_aidx(slot, row)] = hi;                         // input of the down projection, already split
         P.zl[bg_aidx(slot, row)] = from_f32<bf16>(z - to_f32(hi));
       } else {
-        P.logits_all[(size_t)b * N + row] = acc[t][j] * P.rinv[slot];
+        P.logits_all[(size_t)b * N + row] = acc[t][j] * rinv4[j];
       }
     }
   }
@@ -688,6 +727,7 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   constexpr int THREADS = GW * 64, ROWS = GW * 16;     // rows of a tile group
   extern __shared__ __align__(16) uint4 lds_a[];       // [hi, lo][per][64] 16-byte pieces in A-operand order
   __shared__ int last_flag;
+  __shared__ float rinv_lds[BATCH_SLOTS];              // norm ops: 1/rms per slot
   const DecParams& p = P.d;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n = lane & 15, g = lane >> 4;
@@ -712,12 +752,16 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   Chunk A, B;
   load(A, 0);                                          // the weight stream starts before the activations are staged
   {
-    const uint4* xh = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zh : P.xh) + (size_t)s0 * 512);
-    const uint4* xl = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zl : P.xl) + (size_t)s0 * 512);
+    const uint4* xh = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zh : MODE == BG_O ? P.x2h : P.xh) + (size_t)s0 * 512);
+    const uint4* xl = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zl : MODE == BG_O ? P.x2l : P.xl) + (size_t)s0 * 512);
     for (int i = tid; i < ns * 64; i += THREADS) {
       lds_a[i] = xh[i];
       lds_a[per * 64 + i] = xl[i];
     }
+  }
+  if ((MODE == BG_QKV || MODE == BG_GU) && wave == 0) {
+    const float rv = bg_rinv_wave(P, K, lane);
+    if ((lane & 3) == 0) rinv_lds[lane >> 2] = rv;
   }
   __syncthreads();
 
@@ -775,6 +819,8 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   if (!last_flag) return;
   // the last slice of this tile group to finish adds the slices in order and applies the epilogue
   const float* grp = part + (size_t)tg * ks * (NS * 16 * ROWS);
+  __shared__ float ssq_lds[(MODE == BG_O || MODE == BG_DN) ? BATCH_SLOTS * ROWS : 1];   // squares of the updated h, [slot][row]
+  const bool fuse = (MODE == BG_O || MODE == BG_DN) && P.fuse_gain != nullptr;
   for (int e = tid; e < 16 * ROWS; e += THREADS) {
     const int slot = e / ROWS, r = e % ROWS, row = tg * ROWS + r;
     float sum[NS];
@@ -788,18 +834,40 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
 #pragma unroll
       for (int q = 0; q < 8; ++q) { coh_use(v[q]); if (q < ks) sum[i] += v[q]; }
     }
-    if (slot >= P.seqs.n || row >= N) continue;
+    if (slot >= P.seqs.n || row >= N) {
+      if (MODE == BG_O || MODE == BG_DN) ssq_lds[e] = 0.f;
+      continue;
+    }
     const int b = P.seqs.id[slot];
     if (MODE == BG_QKV) {
-      p.qkv[(size_t)b * N + row] = sum[0] * P.rinv[slot];
+      p.qkv[(size_t)b * N + row] = sum[0] * rinv_lds[slot];
     } else if (MODE == BG_GU) {
-      const float rr = P.rinv[slot];
+      const float rr = rinv_lds[slot];
       const float z = siluf(sum[0] * rr) * (sum[NS - 1] * rr);
       const bf16 hi = from_f32<bf16>(z);
       P.zh[bg_aidx(slot, row)] = hi;                           // input of the down projection, already split
       P.zl[bg_aidx(slot, row)] = from_f32<bf16>(z - to_f32(hi));
     } else {
-      p.h[(size_t)b * p.D + row] += sum[0];
+      const float hn = p.h[(size_t)b * p.D + row] + sum[0];
+      p.h[(size_t)b * p.D + row] = hn;
+      ssq_lds[e] = hn * hn;
+      if (fuse) {                                              // the next norm op's input, split as k_xsplit would
+        const float v = hn * P.fuse_gain[row];
+        const bf16 hi = from_f32<bf16>(v);
+        P.xh[bg_aidx(slot, row)] = hi;
+        P.xl[bg_aidx(slot, row)] = from_f32<bf16>(v - to_f32(hi));
+      }
+    }
+  }
+  if ((MODE == BG_O || MODE == BG_DN) && fuse) {
+    __syncthreads();
+    if (tid < 64) {                                            // four lanes per slot, a quarter of the group's rows each, fixed order
+      const int sl2 = tid >> 2, qd = tid & 3;
+      float q = 0.f;
+      for (int r = qd * (ROWS / 4); r < (qd + 1) * (ROWS / 4); ++r) q += ssq_lds[sl2 * ROWS + r];
+      q += __shfl_xor(q, 1, 64);
+      q += __shfl_xor(q, 2, 64);
+      if (qd == 0) P.ssq_part[tg * BATCH_SLOTS + sl2] = q;
     }
   }
 }

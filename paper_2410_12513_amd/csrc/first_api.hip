@@ -91,7 +91,8 @@ struct first_ctx {
   LayerDev* d_layers = nullptr;
   unsigned* d_bar = nullptr;
   // batched decode (several live sequences): split activations, 1/rms per slot, logits when the caller wants none
-  bf16 *d_xh = nullptr, *d_xl = nullptr, *d_zh = nullptr, *d_zl = nullptr;
+  bf16 *d_xh = nullptr, *d_xl = nullptr, *d_zh = nullptr, *d_zl = nullptr, *d_x2h = nullptr, *d_x2l = nullptr;
+  float* d_ssq = nullptr;                 // [SSQ_GROUPS][16] per-tile-group sums of squares (fused split of the O / down epilogues)
   float *d_rinv = nullptr, *d_logits_all = nullptr;
   int xpitch = 0;
   int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
@@ -308,9 +309,10 @@ void launch_bgemv_gw(first_ctx* c, const BatchParams& P, int N, int K, int group
                      c->d_bg_part, c->d_bg_cnt);
 }
 
+// Returns the number of tile groups launched (0: this decomposition is not available, nothing was launched).
 template <int MODE>
-bool launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
-  if (!c->tiled || c->d_bg_part == nullptr) return false;
+int launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
+  if (!c->tiled || c->d_bg_part == nullptr) return 0;
   constexpr int NS = MODE == BG_GU ? 2 : 1;
   const int tiles = (N + 15) / 16, ksteps = (K + 31) / 32;
   int best_gw = 0, best_ks = 0;
@@ -325,7 +327,7 @@ bool launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
       const double eff = (double)tiles * ks / ((double)rounds * c->num_cu * gw) / rounds;
       if (eff > best + 1e-9) { best = eff; best_gw = gw; best_ks = ks; }
     }
-  if (best_gw == 0) return false;
+  if (best_gw == 0) return 0;
   const int groups = (tiles + best_gw - 1) / best_gw;
   switch (best_gw) {
     case 8: launch_bgemv_gw<MODE, 8>(c, P, N, K, groups, best_ks); break;
@@ -333,17 +335,20 @@ bool launch_bgemv_g(first_ctx* c, const BatchParams& P, int N, int K) {
     case 6: launch_bgemv_gw<MODE, 6>(c, P, N, K, groups, best_ks); break;
     default: launch_bgemv_gw<MODE, 5>(c, P, N, K, groups, best_ks); break;
   }
-  return true;
+  return groups;
 }
 
+// Returns the number of tile groups whose epilogues honoured P.fuse_gain (0: the kernel used does not fuse).
 template <int MODE>
-void launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
+int launch_bgemv(first_ctx* c, const BatchParams& P, int N, int K) {
   if constexpr (MODE == BG_QKV || MODE == BG_O || MODE == BG_DN || MODE == BG_GU) {
-    if (launch_bgemv_g<MODE>(c, P, N, K)) return;
+    const int groups = launch_bgemv_g<MODE>(c, P, N, K);
+    if (groups) return groups;
   }
   // two tiles per wave once that still leaves every SIMD several waves
   if ((N + 15) / 16 >= 16 * c->num_cu / 8) launch_bgemv_rt<MODE, 2>(c, P, N, K);
   else launch_bgemv_rt<MODE, 1>(c, P, N, K);
+  return 0;
 }
 
 // Tile-order copies of every matrix for the batched mat-vecs (as much again as the weights),
@@ -405,6 +410,7 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
     P.d = base_params(c, 0, S);
     P.d.tokens = tokens; P.d.token_out = token_out;
     P.xh = c->d_xh; P.xl = c->d_xl; P.zh = c->d_zh; P.zl = c->d_zl; P.rinv = c->d_rinv; P.xpitch = c->xpitch;
+    P.x2h = c->d_x2h; P.x2l = c->d_x2l; P.ssq_part = c->d_ssq; P.fuse_gain = nullptr; P.ssq_groups = 0;
     P.logits_all = logits ? logits : c->d_logits_all;
     P.t_head = c->t_head;
     SeqList all{};
@@ -415,16 +421,31 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       const int chunk = 1024;
       hipLaunchKernelGGL(k_xsplit, dim3(P.seqs.n, (K + chunk - 1) / chunk), dim3(WG), 0, c->stream, P, src, K, chunk, gain);
     };
-    for (int i = 0; i < d.n_layers; ++i) {
-      SeqList keep{};
+    // slot lists per layer (a layer nobody keeps has none); the list after the last layer is everybody (final norm)
+    std::vector<SeqList> keeps(d.n_layers + 1);
+    for (int i = 0; i < d.n_layers; ++i)
       for (int j = 0; j < all.n; ++j)
-        if (c->hmask[all.id[j]][i]) keep.id[keep.n++] = all.id[j];
+        if (c->hmask[all.id[j]][i]) keeps[i].id[keeps[i].n++] = all.id[j];
+    keeps[d.n_layers] = all;
+    auto same_list = [](const SeqList& a, const SeqList& b) {
+      if (a.n != b.n) return false;
+      for (int j = 0; j < a.n; ++j)
+        if (a.id[j] != b.id[j]) return false;
+      return true;
+    };
+    // x_groups > 0: xh / xl already hold the split input of the coming norm op for its slot list, left there by the
+    // previous down projection's epilogue together with that many partial sums of squares
+    int x_groups = 0;
+    for (int i = 0; i < d.n_layers; ++i) {
+      const SeqList& keep = keeps[i];
       if (keep.n == 0) continue;                   // skipped by every sequence: no launch, no bytes
       P.seqs = keep;
       set_layer(c, P.d, i);
       { const LayerPtrs& l = c->layers[i]; P.t_qkv = l.t_qkv; P.t_o = l.t_o; P.t_g = l.t_g; P.t_u = l.t_u; P.t_d = l.t_d; }
-      xsplit(0, d.d_model, P.d.g_attn);
+      if (x_groups == 0) xsplit(0, d.d_model, P.d.g_attn);
+      P.ssq_groups = x_groups;
       launch_bgemv<BG_QKV>(c, P, nqkv, d.d_model);
+      P.ssq_groups = 0;
       // shared key / value tiles: about one workgroup per compute unit, long loops
       int ns_shared = std::max(1, std::min(S_MAX, c->num_cu / std::max(1, d.n_kv_heads * keep.n)));
       if (c->attn_splits > 0) ns_shared = std::min(ns_shared, c->attn_splits);
@@ -439,15 +460,30 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
         hipLaunchKernelGGL(k_attn_tiles_b<64>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
       else
         hipLaunchKernelGGL(k_attn_b, dim3(S, d.n_kv_heads, keep.n), dim3(WG), attn_lds<bf16>(c), c->stream, P);
-      if (!tiles_attn) xsplit(1, c->nq, nullptr);        // (k_attn_tiles_b writes its output already split)
-      launch_bgemv<BG_O>(c, P, d.d_model, c->nq);
-      xsplit(0, d.d_model, P.d.g_mlp);
+      if (!tiles_attn) xsplit(1, c->nq, nullptr);        // (the tile kernels write their output already split)
+      // output projection; its epilogue leaves the MLP norm's input behind when it can
+      P.fuse_gain = P.d.g_mlp;
+      int groups = launch_bgemv<BG_O>(c, P, d.d_model, c->nq);
+      P.fuse_gain = nullptr;
+      if (groups == 0) xsplit(0, d.d_model, P.d.g_mlp);
+      P.ssq_groups = groups;
       launch_bgemv<BG_GU>(c, P, d.d_ffn, d.d_model);
-      launch_bgemv<BG_DN>(c, P, d.d_model, d.d_ffn);
+      P.ssq_groups = 0;
+      // down projection; the next norm op (the next layer somebody keeps, or the final norm) can take its input
+      // from the epilogue if it runs on the same slot list
+      int nx = i + 1;
+      while (nx < d.n_layers && keeps[nx].n == 0) ++nx;
+      const bool next_same = same_list(keeps[nx], keep);
+      P.fuse_gain = !next_same ? nullptr : nx < d.n_layers ? c->layers[nx].g_attn : c->g_final;
+      groups = launch_bgemv<BG_DN>(c, P, d.d_model, d.d_ffn);
+      P.fuse_gain = nullptr;
+      x_groups = next_same ? groups : 0;
     }
     P.seqs = all;
-    xsplit(0, d.d_model, c->g_final);
+    if (x_groups == 0) xsplit(0, d.d_model, c->g_final);
+    P.ssq_groups = x_groups;
     launch_bgemv<BG_HEAD>(c, P, d.vocab, d.d_model);
+    P.ssq_groups = 0;
     hipLaunchKernelGGL(k_argmax_part_b, dim3(all.n, ARG_CHUNKS), dim3(WG), 0, c->stream, P);
     hipLaunchKernelGGL(k_argmax_final_b, dim3(all.n), dim3(64), 0, c->stream, P, 1);
   }
@@ -751,11 +787,14 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
       c->bg_part_floats = (size_t)8 * 16 * (nmax + 8 * 16 * 2);
     }
     A(dev_alloc(c, &c->d_bg_part, c->bg_part_floats)); A(dev_alloc(c, &c->d_bg_cnt, c->bg_cnt_n));
+    A(dev_alloc(c, &c->d_x2h, (size_t)BATCH_SLOTS * c->xpitch)); A(dev_alloc(c, &c->d_x2l, (size_t)BATCH_SLOTS * c->xpitch));
+    A(dev_alloc(c, &c->d_ssq, c->bg_cnt_n * BATCH_SLOTS));
   }
   if (B > 1 && rc == FIRST_OK) {
     (void)hipMemset(c->d_xh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_xl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
     (void)hipMemset(c->d_zh, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_zl, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
     (void)hipMemset(c->d_bg_cnt, 0, c->bg_cnt_n * sizeof(unsigned));
+    (void)hipMemset(c->d_x2h, 0, (size_t)BATCH_SLOTS * c->xpitch * 2); (void)hipMemset(c->d_x2l, 0, (size_t)BATCH_SLOTS * c->xpitch * 2);
 #define FIRST_BGG_ATTR(MODE)                                                                                          \
   for (const void* fn : {reinterpret_cast<const void*>(&k_bgemv_g<MODE, 8>), reinterpret_cast<const void*>(&k_bgemv_g<MODE, 7>),      \
                          reinterpret_cast<const void*>(&k_bgemv_g<MODE, 6>), reinterpret_cast<const void*>(&k_bgemv_g<MODE, 5>)})      \

@@ -114,8 +114,10 @@ def test_shared_pass_agrees_with_one_pass_per_sequence():
         ctx.close()
     # same arithmetic up to the 16-bit split of the activations and the order of the sums
     assert float((outs[0][0] - outs[1][0]).abs().max()) <= 3e-3
-    # tile-order copies or row-major matrices: the same products in the same order
-    assert torch.equal(outs[1][0], outs[2][0]) and torch.equal(outs[1][1], outs[2][1])
+    # tile-order copies or row-major matrices: the same products in the same order; with the tile-order kernels the
+    # sum of squares behind 1/rms comes from the projections' epilogues, added in another order (2^-23 relative)
+    scale = float(outs[2][0].abs().max())
+    assert float((outs[1][0] - outs[2][0]).abs().max()) <= 2e-5 * scale and torch.equal(outs[1][1], outs[2][1])
 
 
 def test_shared_pass_is_refused_for_fp32_models():
