@@ -84,3 +84,69 @@ def test_cfg2_1b_full_size():
 
 def test_cfg3_8b_full_size_quarter_skipped():
     _run("cfg3_8b", 8, 3)
+
+
+def test_cfg4_8b_b16_full_size_sampled_sequences():
+    """The batch-16 workload exactly as bench.py builds it (8B-class decoder, ragged prompts, one skip fraction
+    per sequence, shared pass over the weights, graph replay).  The oracle cannot afford sixteen full-length
+    prompt passes, so two sequences are checked one by one - the shortest prompt and the most skipped layers -
+    each against its own oracle prefill and teacher-forced decode steps; the other sequences decode alongside
+    on their own greedy tokens."""
+    import numpy as np
+    import paper_2410_12513_amd as P
+    wl = WORKLOADS["cfg4_8b_b16"]
+    desc = CONFIGS[wl["model"]]
+    seed, B, L = wl["seed"], wl["batch"], desc.n_layers
+    rng = np.random.Generator(np.random.PCG64(seed))
+    lens = [int(x) for x in rng.integers(wl["prompt"][0], wl["prompt"][1] + 1, size=B)]
+    skips = [min(L - 2, int(round(float(f) * L))) for f in rng.uniform(0.0, 0.5, size=B)]
+    masks = [make_skip_mask(L, k, seed * 100 + b).tolist() for b, k in enumerate(skips)]
+    n_steps = 3
+    wg = make_weights(desc, seed, device="cuda")
+    rg = make_router(desc, seed, device="cuda")
+    w, router = to_device(wg, "cpu"), rg.cpu()
+    prompts = [make_prompt(desc.vocab, n, seed * 100 + b) for b, n in enumerate(lens)]
+    stream = torch.cuda.Stream()
+    ctx = P.FirstContext(desc, wg, rg, max_batch=B, max_seq_len=max(lens) + n_steps + 16, stream=stream)
+    ctx.set_option(6, 1)                                  # shared pass or error
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    logits = torch.zeros(B, desc.vocab, device="cuda")
+    rho = torch.zeros(B, L, device="cuda")
+    ctx.prefill_route(torch.cat(prompts).to(torch.int32).cuda(), lens, rho=rho, logits=logits, token=tok)
+    first = logits.cpu().clone()
+    for b, m in enumerate(masks):
+        ctx.set_mask(b, m)
+    by_len = sorted(range(B), key=lambda b: lens[b])
+    picked = [by_len[0]]
+    picked.append(max((b for b in by_len[:8] if b != picked[0]), key=lambda b: skips[b]))   # most skipped among the shorter half
+    progress(f"cfg4: lens {lens}, skips {skips}, checking sequences {picked}")
+    states = {}
+    for b in picked:
+        st = O.prefill_route(desc, w, router, prompts[b], progress=progress)
+        assert float((rho.cpu()[b] - st.rho).abs().max()) <= 1e-3
+        ok, ma, rel = logits_close(first[b], st.logits, desc.dtype)
+        progress(f"cfg4: sequence {b} (prompt {lens[b]}, {skips[b]} skipped) prefill logits max|d|={ma:.2e} rel={rel:.2e}")
+        assert ok, (b, ma, rel)
+        st.set_mask(masks[b])
+        states[b] = st
+    tin = tok.clone()
+    for b in picked:
+        tin[b] = states[b].token
+    for s in range(n_steps):
+        ctx.decode_step(tin, logits, tok)
+        ctx.sync()
+        nxt = tok.clone()                                 # the unchecked sequences follow their own greedy tokens
+        for b in picked:
+            ref, ref_tok = O.decode_step(desc, w, states[b], int(tin[b]))
+            ok, ma, rel = logits_close(logits[b], ref, desc.dtype)
+            progress(f"cfg4: sequence {b} decode step {s} max|d|={ma:.2e} rel={rel:.2e}")
+            assert ok, (b, s, ma, rel)
+            assert int(tok[b]) == int(torch.argmax(logits[b]))
+            if top2_gap(ref) > 2 * ma:
+                assert int(tok[b]) == ref_tok
+            nxt[b] = ref_tok
+        tin = nxt
+    for b in range(B):
+        assert ctx.seq_len(b) == lens[b] + n_steps
+        assert ctx.get_kept(b) == O.compact_kept(masks[b])
+    ctx.close()
