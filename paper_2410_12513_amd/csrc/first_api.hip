@@ -562,6 +562,22 @@ int launch_gemm_hl(first_ctx* c, hipStream_t st, const bf16* Ah, const bf16* Al,
   return FIRST_OK;
 }
 
+// Up to three projections of the same split activations in one launch.
+int launch_gemm_hl_seg(first_ctx* c, hipStream_t st, const bf16* Ah, const bf16* Al, int M, int K, int acc,
+                       std::initializer_list<GemmSeg> list) {
+  GemmSegs segs{};
+  int blocks = 0;
+  for (const GemmSeg& g : list) {
+    GemmSeg s = g;
+    s.blocks = (g.N + GB_N - 1) / GB_N;
+    blocks += s.blocks;
+    segs.s[segs.n++] = s;
+  }
+  hipLaunchKernelGGL(k_gemm_nt_bf16_hl_seg, dim3(blocks, (M + GB_M - 1) / GB_M), dim3(WG), 0, st, Ah, Al, segs, M, K, acc);
+  HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
 // Prompt attention on the matrix cores: operand preparation (query split, key gather, value
 // transpose out of the cache pages) and the tiled kernel.
 void launch_attn_flash(first_ctx* c, hipStream_t st, const bf16* pool, const int* pt, int T) {
@@ -618,9 +634,16 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     auto gemm = [&](const float* A32, const bf16* Ah, const bf16* Al, const void* W, float* C, int N, int K, int acc) {
       return hl ? launch_gemm_hl(c, st, Ah, Al, W, C, T, N, K, acc) : launch_gemm(c, st, d.dtype, A32, W, C, T, N, K, acc, true);
     };
-    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wq, c->p_q, c->nq, D, 0))) return rc;
-    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wk, c->p_k, c->nkv, D, 0))) return rc;
-    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wv, c->p_v, c->nkv, D, 0))) return rc;
+    if (hl) {
+      if ((rc = launch_gemm_hl_seg(c, st, c->p_xh, c->p_xl, T, D, 0,
+                                   {GemmSeg{(const bf16*)l.wq, c->p_q, c->nq, 0}, GemmSeg{(const bf16*)l.wk, c->p_k, c->nkv, 0},
+                                    GemmSeg{(const bf16*)l.wv, c->p_v, c->nkv, 0}})))
+        return rc;
+    } else {
+      if ((rc = gemm(x, c->p_xh, c->p_xl, l.wq, c->p_q, c->nq, D, 0))) return rc;
+      if ((rc = gemm(x, c->p_xh, c->p_xl, l.wk, c->p_k, c->nkv, D, 0))) return rc;
+      if ((rc = gemm(x, c->p_xh, c->p_xl, l.wv, c->p_v, c->nkv, D, 0))) return rc;
+    }
     if (c->kv_elide && !soft) {
       HIPCHK(c, hipEventSynchronize(c->ev_keep));
       if (*c->h_keep && c->layer_slice[i] < 0) {
@@ -647,8 +670,14 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     if ((rc = gemm(a, c->p_ah, c->p_al, l.wo, c->p_H, D, c->nq, 1))) return rc;
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
                        (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
-    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wg, c->p_g, F, D, 0))) return rc;
-    if ((rc = gemm(x, c->p_xh, c->p_xl, l.wu, c->p_u, F, D, 0))) return rc;
+    if (hl) {
+      if ((rc = launch_gemm_hl_seg(c, st, c->p_xh, c->p_xl, T, D, 0,
+                                   {GemmSeg{(const bf16*)l.wg, c->p_g, F, 0}, GemmSeg{(const bf16*)l.wu, c->p_u, F, 0}})))
+        return rc;
+    } else {
+      if ((rc = gemm(x, c->p_xh, c->p_xl, l.wg, c->p_g, F, D, 0))) return rc;
+      if ((rc = gemm(x, c->p_xh, c->p_xl, l.wu, c->p_u, F, D, 0))) return rc;
+    }
     const unsigned sm_grid = (unsigned)std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536);
     if (hl)
       hipLaunchKernelGGL(k_silu_mul_split, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, c->p_zh, c->p_zl, (size_t)T * F);

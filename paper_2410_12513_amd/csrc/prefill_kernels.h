@@ -286,14 +286,13 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_split(const float* __restri
 
 // The same split-precision contraction with the activations already split by their producer
 // (Ah + Al, bf16 each): no conversion work here, which otherwise repeats once per column tile.
-__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
-                                                        const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
-                                                        int K, int accumulate) {
+__device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                     const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
+                                                     int K, int accumulate, int m0, int n0) {
   __shared__ __align__(16) uint16_t sAh[GB_M * GB_PITCH];
   __shared__ __align__(16) uint16_t sAl[GB_M * GB_PITCH];
   __shared__ __align__(16) uint16_t sB[GB_N * GB_PITCH];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int m0 = blockIdx.y * GB_M, n0 = blockIdx.x * GB_N;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
   floatx16_t acc[2][2];
 #pragma unroll
@@ -368,6 +367,26 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl(const bf16* __restrict__
         }
       }
     }
+}
+
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                        const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
+                                                        int K, int accumulate) {
+  gemm_nt_bf16_hl_tile(Ah, Al, W, C, M, N, K, accumulate, blockIdx.y * GB_M, blockIdx.x * GB_N);
+}
+
+// Several weight matrices applied to the same activations in one launch (Q, K and V; gate and up): the column
+// blocks of the segments follow each other in blockIdx.x, each segment with its own matrix, output and width.
+// A matrix of 1024 rows alone is 64 workgroups at 1024 tokens - a quarter of the compute units; together the
+// projections of one input fill whole rounds.
+struct GemmSeg { const bf16* W; float* C; int N; int blocks; };     // blocks = ceil(N / GB_N)
+struct GemmSegs { GemmSeg s[3]; int n; };
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl_seg(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                            GemmSegs segs, int M, int K, int accumulate) {
+  int bx = blockIdx.x, i = 0;
+  while (i + 1 < segs.n && bx >= segs.s[i].blocks) { bx -= segs.s[i].blocks; ++i; }
+  const GemmSeg g = segs.s[i];
+  gemm_nt_bf16_hl_tile(Ah, Al, g.W, g.C, M, g.N, K, accumulate, blockIdx.y * GB_M, bx * GB_N);
 }
 
 // fp32 variant (the small full-precision configuration): 64x64 tile, 4x4 per thread.
