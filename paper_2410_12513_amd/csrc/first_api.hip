@@ -557,6 +557,12 @@ int launch_gemm(first_ctx* c, hipStream_t st, int dtype, const void* A, const vo
 int launch_gemm_hl(first_ctx* c, hipStream_t st, const bf16* Ah, const bf16* Al, const void* W, float* C, int M, int N, int K,
                    int acc) {
   dim3 grid((N + GB_N - 1) / GB_N, (M + GB_M - 1) / GB_M);
+  if (M > GB_MS && (int)(grid.x * grid.y) <= device_cus()) {   // at most one 128-row tile per compute unit: use 64-row tiles
+    dim3 gs(grid.x, (M + GB_MS - 1) / GB_MS);
+    hipLaunchKernelGGL(k_gemm_nt_bf16_hl_s, gs, dim3(WG), 0, st, Ah, Al, reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
+    HIPCHK(c, hipGetLastError());
+    return FIRST_OK;
+  }
   hipLaunchKernelGGL(k_gemm_nt_bf16_hl, grid, dim3(WG), 0, st, Ah, Al, reinterpret_cast<const bf16*>(W), C, M, N, K, acc);
   HIPCHK(c, hipGetLastError());
   return FIRST_OK;

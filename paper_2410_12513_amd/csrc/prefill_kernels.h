@@ -286,44 +286,59 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_split(const float* __restri
 
 // The same split-precision contraction with the activations already split by their producer
 // (Ah + Al, bf16 each): no conversion work here, which otherwise repeats once per column tile.
+// BM x BN output tile per workgroup, the four waves arranged WGM x WGN over it (wave tile = (BM / WGM) x (BN / WGN),
+// a multiple of 32 x 32 each way).
+template <int BM, int BN, int WGM, int WGN>
 __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
                                                      const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
                                                      int K, int accumulate, int m0, int n0) {
-  __shared__ __align__(16) uint16_t sAh[GB_M * GB_PITCH];
-  __shared__ __align__(16) uint16_t sAl[GB_M * GB_PITCH];
-  __shared__ __align__(16) uint16_t sB[GB_N * GB_PITCH];
+  static_assert(WGM * WGN == WAVES, "four waves");
+  constexpr int TM = BM / WGM, TN = BN / WGN, IM = TM / 32, JN = TN / 32;
+  constexpr int VA = BM * 8 / WG, VB = BN * 8 / WG;            // 16-byte vectors per thread and K step
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && VA >= 1 && VB >= 1, "tile shape");
+  __shared__ __align__(16) uint16_t sAh[BM * GB_PITCH];
+  __shared__ __align__(16) uint16_t sAl[BM * GB_PITCH];
+  __shared__ __align__(16) uint16_t sB[BN * GB_PITCH];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  floatx16_t acc[2][2];
+  const int wm = (wave / WGN) * TM, wn = (wave % WGN) * TN;
+  floatx16_t acc[IM][JN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < IM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < JN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 rh[4], rl[4], rb[4];
+  uint4 rh[VA], rl[VA], rb[VB];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < VA; ++i) {
       const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
       const int k = k0 + kc;
-      rh[i] = make_uint4(0, 0, 0, 0); rl[i] = rh[i]; rb[i] = rh[i];
-      if (k < K) {
-        if (m0 + row < M) {
-          rh[i] = *reinterpret_cast<const uint4*>(Ah + (size_t)(m0 + row) * K + k);
-          rl[i] = *reinterpret_cast<const uint4*>(Al + (size_t)(m0 + row) * K + k);
-        }
-        if (n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
+      rh[i] = make_uint4(0, 0, 0, 0); rl[i] = rh[i];
+      if (k < K && m0 + row < M) {
+        rh[i] = *reinterpret_cast<const uint4*>(Ah + (size_t)(m0 + row) * K + k);
+        rl[i] = *reinterpret_cast<const uint4*>(Al + (size_t)(m0 + row) * K + k);
       }
+    }
+#pragma unroll
+    for (int i = 0; i < VB; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
+      const int k = k0 + kc;
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (k < K && n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
     }
   };
   auto stash = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < VA; ++i) {
       const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
       *reinterpret_cast<uint4*>(sAh + row * GB_PITCH + kc) = rh[i];
       *reinterpret_cast<uint4*>(sAl + row * GB_PITCH + kc) = rl[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VB; ++i) {
+      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
       *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
     }
   };
@@ -336,27 +351,29 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
     if (k0 + GB_K < K) fetch(k0 + GB_K);
 #pragma unroll
     for (int kk = 0; kk < GB_K; kk += 16) {
-      bf16x8_t ah[2], al[2], b[2];
+      bf16x8_t ah[IM], al[IM], b[JN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < IM; ++i) {
         const int ao = (wm + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3);
         ah[i] = *reinterpret_cast<const bf16x8_t*>(sAh + ao);
         al[i] = *reinterpret_cast<const bf16x8_t*>(sAl + ao);
-        b[i] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + i * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
       }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < JN; ++j)
+        b[j] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + j * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], b[j], acc[i][j], 0, 0, 0);
         }
     }
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < IM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < JN; ++j) {
       const int col = n0 + wn + j * 32 + (lane & 31);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -372,7 +389,16 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
 __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
                                                         const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
                                                         int K, int accumulate) {
-  gemm_nt_bf16_hl_tile(Ah, Al, W, C, M, N, K, accumulate, blockIdx.y * GB_M, blockIdx.x * GB_N);
+  gemm_nt_bf16_hl_tile<GB_M, GB_N, 2, 2>(Ah, Al, W, C, M, N, K, accumulate, blockIdx.y * GB_M, blockIdx.x * GB_N);
+}
+
+// The same with 64-row tiles, for shapes whose 128 x 128 tiles would leave every compute unit a single workgroup
+// (one wave per SIMD, nothing to overlap a barrier or a load with): twice the workgroups, two per compute unit.
+constexpr int GB_MS = 64;
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl_s(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                          const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
+                                                          int K, int accumulate) {
+  gemm_nt_bf16_hl_tile<GB_MS, GB_N, 2, 2>(Ah, Al, W, C, M, N, K, accumulate, blockIdx.y * GB_MS, blockIdx.x * GB_N);
 }
 
 // Several weight matrices applied to the same activations in one launch (Q, K and V; gate and up): the column
@@ -386,7 +412,7 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl_seg(const bf16* __restri
   int bx = blockIdx.x, i = 0;
   while (i + 1 < segs.n && bx >= segs.s[i].blocks) { bx -= segs.s[i].blocks; ++i; }
   const GemmSeg g = segs.s[i];
-  gemm_nt_bf16_hl_tile(Ah, Al, g.W, g.C, M, g.N, K, accumulate, blockIdx.y * GB_M, bx * GB_N);
+  gemm_nt_bf16_hl_tile<GB_M, GB_N, 2, 2>(Ah, Al, g.W, g.C, M, g.N, K, accumulate, blockIdx.y * GB_M, bx * GB_N);
 }
 
 // fp32 variant (the small full-precision configuration): 64x64 tile, 4x4 per thread.
