@@ -42,3 +42,22 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".h", ".hip", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("no CPU fallback", ""), f"{f} mentions the oracle"
+
+
+def test_build_reads_resource_remarks_and_limits_scratch():
+    """The build refuses a library in which a kernel that keeps loads in flight through inline asm spills registers."""
+    from paper_2410_12513_amd import build as B
+    text = """
+a.h:10:1: remark: Function Name: _ZN5first6k_stepILi128ELb1EEEvNS_10StepParamsE [-Rpass-analysis=kernel-resource-usage]
+a.h:10:1: remark:     VGPRs: 233 [-Rpass-analysis=kernel-resource-usage]
+a.h:10:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+a.h:10:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]
+b.h:20:1: remark: Function Name: _ZN5first8k_gateupINS_4bf16EEEvNS_9DecParamsE [-Rpass-analysis=kernel-resource-usage]
+b.h:20:1: remark:     VGPRs: 64 [-Rpass-analysis=kernel-resource-usage]
+b.h:20:1: remark:     ScratchSize [bytes/lane]: 288 [-Rpass-analysis=kernel-resource-usage]
+b.h:20:1: remark:     VGPRs Spill: 89 [-Rpass-analysis=kernel-resource-usage]
+"""
+    r = B.kernel_resources(text)
+    assert r["_ZN5first6k_stepILi128ELb1EEEvNS_10StepParamsE"] == {"vgprs": 233, "scratch": 0, "spills": 0}
+    assert r["_ZN5first8k_gateupINS_4bf16EEEvNS_9DecParamsE"] == {"vgprs": 64, "scratch": 288, "spills": 89}
+    assert B.SCRATCH_LIMITS["k_step"] == 0
