@@ -23,6 +23,10 @@ struct SeqList {
   int id[BATCH_SLOTS];
 };
 
+// One workgroup's share of a batched attention launch: split `split` of `nsplit` of the sequence in slot `slot`.
+struct AttnWork { unsigned char slot, split, nsplit; };
+constexpr int ATTN_WORK_MAX = 96;
+
 struct BatchParams {
   DecParams d;          // geometry, per-sequence state, layer pointers (d.b unused)
   SeqList seqs;         // sequences of this pass; slot j <-> sequence seqs.id[j]
@@ -41,6 +45,12 @@ struct BatchParams {
   const float* fuse_gain;
   float* ssq_part;
   int ssq_groups;
+  // k_attn_mfma_b with a work list (attn_nwork > 0): grid = (KV head, work item).  The host cuts every sequence into
+  // splits in proportion to its length, so the workgroups of a batch of long and short sequences walk about the same
+  // number of tiles and none is launched only to find that it has nothing to do.  Without a list: grid =
+  // (split, KV head, slot), as many splits per sequence as the grid has.
+  int attn_nwork;
+  AttnWork attn_work[ATTN_WORK_MAX];
   int xpitch;
   float* logits_all;    // [B][V] logits of the step (caller's buffer or the library's)
   // optional copies of the layer's matrices (and of the LM head) in MFMA tile order, see k_tile_weights
@@ -191,18 +201,21 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   static_assert(HD == 128 && G == 4, "lane layouts below: 8 value dims per lane, the 4 heads repeat down the 16 score rows");
   extern __shared__ __align__(16) float smem_f[];
   DecParams p = P.d;
-  p.b = P.seqs.id[blockIdx.z];
+  const bool listed = P.attn_nwork > 0;
+  const AttnWork work = P.attn_work[listed ? blockIdx.y : 0];
+  const int slot = listed ? work.slot : blockIdx.z;
+  p.b = P.seqs.id[slot];
   constexpr int HALF = HD / 2;
   constexpr int TILE_E = 64 * HD;                       // elements of one key (or value) tile
   constexpr int BPT = HD / 64;                          // 8 KB blocks (512 lanes x 16 B) per tile
   constexpr int NB = AS_NT * 2 * BPT;                   // blocks per iteration
   constexpr int KS = HD / 32;                           // MFMA k-steps over the head dimension
   constexpr int DL = HD / 16;                           // value dims per lane: lane (sub, dc), dc = lane % 16
-  const int b = p.b, Pg = p.P, g = blockIdx.y;
+  const int b = p.b, Pg = p.P, g = listed ? blockIdx.x : blockIdx.y;
   const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
   const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
-  const int nsplit = max(1, min((int)gridDim.x, (tiles + AS_NT - 1) / AS_NT));
-  const int s = blockIdx.x;
+  const int nsplit = max(1, min(listed ? (int)work.nsplit : (int)gridDim.x, (tiles + AS_NT - 1) / AS_NT));
+  const int s = listed ? (int)work.split : (int)blockIdx.x;
   if (s >= nsplit) return;
   // LDS carve-up
   bf16* tile_lds = reinterpret_cast<bf16*>(smem_f);
@@ -505,7 +518,7 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
         const bf16 h = from_f32<bf16>(v[j]);
         hi[j] = h.v; lo[j] = from_f32<bf16>(v[j] - to_f32(h)).v;
       }
-      const size_t at = bg_aidx(blockIdx.z, H * HD + q4);
+      const size_t at = bg_aidx(slot, H * HD + q4);
       *reinterpret_cast<uint2*>(P.x2h + at) = make_uint2(hi[0] | ((unsigned)hi[1] << 16), hi[2] | ((unsigned)hi[3] << 16));
       *reinterpret_cast<uint2*>(P.x2l + at) = make_uint2(lo[0] | ((unsigned)lo[1] << 16), lo[2] | ((unsigned)lo[3] << 16));
     }

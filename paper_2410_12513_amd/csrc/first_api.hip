@@ -452,7 +452,31 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       // a split's page ids must fit the kernel's LDS table whatever length a sequence reaches (a bound that
       // does not move with the lengths, so a captured graph stays valid)
       ns_shared = std::max(ns_shared, ((d.max_seq_len + 64) / 64 * 4 + AS_PT - 1) / AS_PT);
-      if (tiles_attn && shared_attn)
+      P.attn_nwork = 0;
+      if (tiles_attn && shared_attn && c->attn_splits <= 0) {
+        // work list: splits in proportion to each sequence's length - the fewest tiles per workgroup for which the batch
+        // still fits one round of the compute units at today's lengths (a cached graph keeps the list while the
+        // sequences grow: their splits just get longer)
+        const int min_sp = ((d.max_seq_len + 64) / 64 * 4 + AS_PT - 1) / AS_PT;    // a split's page ids fit the LDS table
+        int sp[BATCH_SLOTS];
+        for (int tpw = AS_NT; tpw <= AS_PT / 4; ++tpw) {
+          int wgs = 0;
+          for (int j = 0; j < keep.n; ++j) {
+            sp[j] = std::min(S_MAX, std::max(min_sp, (c->hlen[keep.id[j]] / 64 + 1 + tpw - 1) / tpw));
+            wgs += sp[j];
+          }
+          if (wgs * d.n_kv_heads <= c->num_cu || tpw == AS_PT / 4) {
+            if (wgs <= ATTN_WORK_MAX)
+              for (int j = 0; j < keep.n; ++j)
+                for (int q = 0; q < sp[j]; ++q)
+                  P.attn_work[P.attn_nwork++] = AttnWork{(unsigned char)j, (unsigned char)q, (unsigned char)sp[j]};
+            break;
+          }
+        }
+      }
+      if (tiles_attn && shared_attn && P.attn_nwork > 0)
+        hipLaunchKernelGGL((k_attn_mfma_b<128, 4>), dim3(d.n_kv_heads, P.attn_nwork), dim3(AS_THREADS), as_lds_bytes(4, 128), c->stream, P);
+      else if (tiles_attn && shared_attn)
         hipLaunchKernelGGL((k_attn_mfma_b<128, 4>), dim3(ns_shared, d.n_kv_heads, keep.n), dim3(AS_THREADS), as_lds_bytes(4, 128), c->stream, P);
       else if (tiles_attn && d.head_dim == 128)
         hipLaunchKernelGGL(k_attn_tiles_b<128>, dim3(nsplit, d.n_kv_heads, keep.n), dim3(AT_THREADS), attn_tiles_lds, c->stream, P);
