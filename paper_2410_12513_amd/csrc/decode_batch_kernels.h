@@ -45,6 +45,9 @@ struct BatchParams {
   const float* fuse_gain;
   float* ssq_part;
   int ssq_groups;
+  SeqList next;         // with fuse_gain: slot list of the consuming norm op when it differs from seqs (next.n > 0); the
+                        // epilogue then writes its rows of the split input and the sums of squares for those slots,
+                        // reading back the residual rows it has just updated (and the untouched rows of the others)
   // k_attn_mfma_b with a work list (attn_nwork > 0): grid = (KV head, work item).  The host cuts every sequence into
   // splits in proportion to its length, so the workgroups of a batch of long and short sequences walk about the same
   // number of tiles and none is launched only to find that it has nothing to do.  Without a list: grid =
@@ -834,6 +837,7 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   const float* grp = part + (size_t)tg * ks * (NS * 16 * ROWS);
   __shared__ float ssq_lds[(MODE == BG_O || MODE == BG_DN) ? BATCH_SLOTS * ROWS : 1];   // squares of the updated h, [slot][row]
   const bool fuse = (MODE == BG_O || MODE == BG_DN) && P.fuse_gain != nullptr;
+  const bool remap = fuse && P.next.n > 0;
   for (int e = tid; e < 16 * ROWS; e += THREADS) {
     const int slot = e / ROWS, r = e % ROWS, row = tg * ROWS + r;
     float sum[NS];
@@ -864,8 +868,33 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
       const float hn = p.h[(size_t)b * p.D + row] + sum[0];
       p.h[(size_t)b * p.D + row] = hn;
       ssq_lds[e] = hn * hn;
-      if (fuse) {                                              // the next norm op's input, split as k_xsplit would
+      if (fuse && !remap) {                                    // the next norm op's input, split as k_xsplit would
         const float v = hn * P.fuse_gain[row];
+        const bf16 hi = from_f32<bf16>(v);
+        P.xh[bg_aidx(slot, row)] = hi;
+        P.xl[bg_aidx(slot, row)] = from_f32<bf16>(v - to_f32(hi));
+      }
+    }
+  }
+  if ((MODE == BG_O || MODE == BG_DN) && remap) {
+    // the consumer's slots: this group's rows of every sequence it will read, straight from the residual stream
+    __syncthreads();                                           // (waits for the stores above as well)
+    constexpr int PER = 16 * ROWS / THREADS;                   // elements per thread
+    static_assert(PER * THREADS == 16 * ROWS, "whole rounds");
+    float hv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = tid + u * THREADS, slot = e / ROWS, row = tg * ROWS + e % ROWS;
+      const bool ok = slot < P.next.n && row < N;
+      hv[u] = p.h[(size_t)P.next.id[ok ? slot : 0] * p.D + (ok ? row : 0)];   // (rows stored above: same workgroup, after the barrier)
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = tid + u * THREADS, slot = e / ROWS, row = tg * ROWS + e % ROWS;
+      const bool ok = slot < P.next.n && row < N;
+      ssq_lds[e] = ok ? hv[u] * hv[u] : 0.f;
+      if (ok) {
+        const float v = hv[u] * P.fuse_gain[row];
         const bf16 hi = from_f32<bf16>(v);
         P.xh[bg_aidx(slot, row)] = hi;
         P.xl[bg_aidx(slot, row)] = from_f32<bf16>(v - to_f32(hi));

@@ -497,11 +497,11 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
       // from the epilogue if it runs on the same slot list
       int nx = i + 1;
       while (nx < d.n_layers && keeps[nx].n == 0) ++nx;
-      const bool next_same = same_list(keeps[nx], keep);
-      P.fuse_gain = !next_same ? nullptr : nx < d.n_layers ? c->layers[nx].g_attn : c->g_final;
+      P.fuse_gain = nx < d.n_layers ? c->layers[nx].g_attn : c->g_final;
+      if (!same_list(keeps[nx], keep)) P.next = keeps[nx];      // (the epilogue then writes the consumer's slots)
       groups = launch_bgemv<BG_DN>(c, P, d.d_model, d.d_ffn);
-      P.fuse_gain = nullptr;
-      x_groups = next_same ? groups : 0;
+      P.fuse_gain = nullptr; P.next.n = 0;
+      x_groups = groups;
     }
     P.seqs = all;
     if (x_groups == 0) xsplit(0, d.d_model, c->g_final);
