@@ -770,10 +770,28 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   {
     const uint4* xh = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zh : MODE == BG_O ? P.x2h : P.xh) + (size_t)s0 * 512);
     const uint4* xl = reinterpret_cast<const uint4*>((MODE == BG_DN ? P.zl : MODE == BG_O ? P.x2l : P.xl) + (size_t)s0 * 512);
-    for (int i = tid; i < ns * 64; i += THREADS) {
-      lds_a[i] = xh[i];
-      lds_a[per * 64 + i] = xl[i];
-    }
+    // A thread's pieces are requested in runs of 8, 4, 2 and 1 - every load of a run before its first write to LDS -
+    // so staging costs a few memory round trips (behind the weight loads already in flight), not one per piece.
+    const int np = ns * 64;
+    auto run = [&](int i0, auto sbc) __attribute__((always_inline)) {
+      constexpr int SB = decltype(sbc)::value;
+      u32x4_t vh[SB], vl[SB];
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        vh[u] = *reinterpret_cast<const u32x4_t*>(xh + i0 + u * THREADS);
+        vl[u] = *reinterpret_cast<const u32x4_t*>(xl + i0 + u * THREADS);
+      }
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        *reinterpret_cast<u32x4_t*>(lds_a + i0 + u * THREADS) = vh[u];
+        *reinterpret_cast<u32x4_t*>(lds_a + per * 64 + i0 + u * THREADS) = vl[u];
+      }
+    };
+    int i0 = tid;
+    for (; i0 + 7 * THREADS < np; i0 += 8 * THREADS) run(i0, std::integral_constant<int, 8>{});
+    if (i0 + 3 * THREADS < np) { run(i0, std::integral_constant<int, 4>{}); i0 += 4 * THREADS; }
+    if (i0 + THREADS < np) { run(i0, std::integral_constant<int, 2>{}); i0 += 2 * THREADS; }
+    if (i0 < np) run(i0, std::integral_constant<int, 1>{});
   }
   if ((MODE == BG_QKV || MODE == BG_GU) && wave == 0) {
     const float rv = bg_rinv_wave(P, K, lane);
