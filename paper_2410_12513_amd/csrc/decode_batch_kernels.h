@@ -856,22 +856,11 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
   __shared__ float ssq_lds[(MODE == BG_O || MODE == BG_DN) ? BATCH_SLOTS * ROWS : 1];   // squares of the updated h, [slot][row]
   const bool fuse = (MODE == BG_O || MODE == BG_DN) && P.fuse_gain != nullptr;
   const bool remap = fuse && P.next.n > 0;
-  for (int e = tid; e < 16 * ROWS; e += THREADS) {
+  auto finish = [&](int e, const float (&sum)[NS]) __attribute__((always_inline)) {
     const int slot = e / ROWS, r = e % ROWS, row = tg * ROWS + r;
-    float sum[NS];
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      float v[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) coh_issue4(v[q], grp + (size_t)min(q, ks - 1) * (NS * 16 * ROWS) + i * (16 * ROWS) + e);
-      coh_wait();
-      sum[i] = 0.f;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) { coh_use(v[q]); if (q < ks) sum[i] += v[q]; }
-    }
     if (slot >= P.seqs.n || row >= N) {
       if (MODE == BG_O || MODE == BG_DN) ssq_lds[e] = 0.f;
-      continue;
+      return;
     }
     const int b = P.seqs.id[slot];
     if (MODE == BG_QKV) {
@@ -892,6 +881,49 @@ __global__ void __launch_bounds__(GW * 64) k_bgemv_g(BatchParams P, int N, int K
         P.xh[bg_aidx(slot, row)] = hi;
         P.xl[bg_aidx(slot, row)] = from_f32<bf16>(v - to_f32(hi));
       }
+    }
+  };
+  if constexpr (MODE == BG_QKV || MODE == BG_GU) {
+    // every partial sum this thread needs - its 4 elements x streams x up to 8 slices - is requested before the first
+    // is used: one memory round trip for the whole epilogue instead of one per element and stream
+    constexpr int EPT = 16 * ROWS / THREADS;
+    static_assert(EPT * THREADS == 16 * ROWS, "whole rounds");
+    float pv[EPT][NS][8];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+#pragma unroll
+      for (int i = 0; i < NS; ++i)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          coh_issue4(pv[u][i][q], grp + (size_t)min(q, ks - 1) * (NS * 16 * ROWS) + i * (16 * ROWS) + tid + u * THREADS);
+    coh_wait();
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+      float sum[NS];
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        sum[i] = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { coh_use(pv[u][i][q]); if (q < ks) sum[i] += pv[u][i][q]; }
+      }
+      finish(tid + u * THREADS, sum);
+    }
+  } else {
+    // (the projections that add to the residual stream take one element per round: measured, the batch of loads
+    //  above makes them slower)
+    for (int e = tid; e < 16 * ROWS; e += THREADS) {
+      float sum[NS];
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) coh_issue4(v[q], grp + (size_t)min(q, ks - 1) * (NS * 16 * ROWS) + i * (16 * ROWS) + e);
+        coh_wait();
+        sum[i] = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { coh_use(v[q]); if (q < ks) sum[i] += v[q]; }
+      }
+      finish(e, sum);
     }
   }
   if ((MODE == BG_O || MODE == BG_DN) && remap) {
