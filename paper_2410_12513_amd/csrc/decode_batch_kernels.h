@@ -23,8 +23,13 @@ struct SeqList {
   int id[BATCH_SLOTS];
 };
 
-// One workgroup's share of a batched attention launch: split `split` of `nsplit` of the sequence in slot `slot`.
-struct AttnWork { unsigned char slot, split, nsplit; };
+// One workgroup's share of a batched attention launch: split `split` of `nsplit` of the sequence in slot `slot`,
+// packed into one dword (slot | split << 8 | nsplit << 16) so that the kernel fetches it with a scalar load from its
+// arguments (byte fields are fetched through the vector memory path: a full memory round trip before anything else).
+typedef uint32_t AttnWork;
+__host__ __device__ inline AttnWork attn_work_pack(int slot, int split, int nsplit) {
+  return (uint32_t)slot | ((uint32_t)split << 8) | ((uint32_t)nsplit << 16);
+}
 constexpr int ATTN_WORK_MAX = 96;
 
 struct BatchParams {
@@ -206,7 +211,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   DecParams p = P.d;
   const bool listed = P.attn_nwork > 0;
   const AttnWork work = P.attn_work[listed ? blockIdx.y : 0];
-  const int slot = listed ? work.slot : blockIdx.z;
+  const int work_slot = work & 0xff, work_split = (work >> 8) & 0xff, work_nsplit = (work >> 16) & 0xff;
+  const int slot = listed ? work_slot : (int)blockIdx.z;
   p.b = P.seqs.id[slot];
   constexpr int HALF = HD / 2;
   constexpr int TILE_E = 64 * HD;                       // elements of one key (or value) tile
@@ -217,8 +223,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   const int b = p.b, Pg = p.P, g = listed ? blockIdx.x : blockIdx.y;
   const int tid = threadIdx.x, wave = uni((int)(threadIdx.x >> 6)), lane = tid & 63;
   const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
-  const int nsplit = max(1, min(listed ? (int)work.nsplit : (int)gridDim.x, (tiles + AS_NT - 1) / AS_NT));
-  const int s = listed ? (int)work.split : (int)blockIdx.x;
+  const int nsplit = max(1, min(listed ? work_nsplit : (int)gridDim.x, (tiles + AS_NT - 1) / AS_NT));
+  const int s = listed ? work_split : (int)blockIdx.x;
   if (s >= nsplit) return;
   // LDS carve-up
   bf16* tile_lds = reinterpret_cast<bf16*>(smem_f);

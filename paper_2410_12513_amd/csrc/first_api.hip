@@ -469,7 +469,7 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
             if (wgs <= ATTN_WORK_MAX)
               for (int j = 0; j < keep.n; ++j)
                 for (int q = 0; q < sp[j]; ++q)
-                  P.attn_work[P.attn_nwork++] = AttnWork{(unsigned char)j, (unsigned char)q, (unsigned char)sp[j]};
+                  P.attn_work[P.attn_nwork++] = attn_work_pack(j, q, sp[j]);
             break;
           }
         }
