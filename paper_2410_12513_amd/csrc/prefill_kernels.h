@@ -40,17 +40,29 @@ __global__ void __launch_bounds__(WG) k_rmsnorm_router(const float* __restrict__
   const int lane = threadIdx.x & 63;
   if (t >= T) return;
   const float* row = H + (size_t)t * D;
+  // Eight 16-byte pieces of the row per lane and round, all requested before the first is used (one piece per round
+  // is one memory round trip per round); same order of additions as a piece-by-piece loop.
+  constexpr int RB = 8;
   float ss = 0.f, dot = 0.f;
-  for (int k = lane * 4; k < D; k += 256) {
-    const float4 v = *reinterpret_cast<const float4*>(row + k);
-    ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
-    if (rw) {
-      const float4 w = *reinterpret_cast<const float4*>(rw + k);
-      dot = fmaf(v.x, w.x, dot); dot = fmaf(v.y, w.y, dot); dot = fmaf(v.z, w.z, dot); dot = fmaf(v.w, w.w, dot);
+  for (int k0 = lane * 4; k0 < D; k0 += 256 * RB) {
+    float4 v[RB], w[RB];
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      const int k = min(k0 + 256 * u, D - 4);
+      v[u] = *reinterpret_cast<const float4*>(row + k);
+      w[u] = rw ? *reinterpret_cast<const float4*>(rw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      if (k0 + 256 * u < D) {
+        ss = fmaf(v[u].x, v[u].x, ss); ss = fmaf(v[u].y, v[u].y, ss); ss = fmaf(v[u].z, v[u].z, ss); ss = fmaf(v[u].w, v[u].w, ss);
+        dot = fmaf(v[u].x, w[u].x, dot); dot = fmaf(v[u].y, w[u].y, dot); dot = fmaf(v[u].z, w[u].z, dot); dot = fmaf(v[u].w, w[u].w, dot);
+      }
     }
   }
   ss = wave_sum(ss);
   const float r = 1.0f / sqrtf(ss / (float)D + eps);
+#pragma unroll 4
   for (int k = lane * 4; k < D; k += 256) {
     const float4 v = *reinterpret_cast<const float4*>(row + k);
     const float4 g = *reinterpret_cast<const float4*>(gain + k);
