@@ -9,6 +9,7 @@ constexpr int WG = 256;          // threads per workgroup in every kernel of thi
 constexpr int WAVES = WG / 64;   // wavefronts per workgroup
 
 struct bf16 { uint16_t v; };     // raw upper half of an fp32
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes that stay in registers (arrays of HIP's uint4 tend to end up in scratch)
 
 template <typename T> struct Vec;                // elements per 16-byte vector
 template <> struct Vec<float> { static constexpr int N = 4; };
@@ -67,6 +68,10 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   for (int w = 0; w < WAVES; ++w) t += red[w];
   return t;
 }
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait
+// for outstanding global loads, so prefetches stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 __device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
 __device__ __forceinline__ float siluf(float z) { return z / (1.0f + expf(-z)); }

@@ -298,6 +298,15 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_split(const float* __restri
 
 // The same split-precision contraction with the activations already split by their producer
 // (Ah + Al, bf16 each): no conversion work here, which otherwise repeats once per column tile.
+// A 16-byte global load whose destination the compiler must treat as in use from here on (it is written when the load
+// lands), a wait that leaves the N youngest loads of the wave outstanding, and the point from which a destination
+// may be read.  A kernel using these must not spill registers (see build.py).
+__device__ __forceinline__ void pf_issue16(u32x4_t& v, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+}
+template <int N> __device__ __forceinline__ void pf_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void pf_use(u32x4_t& v) { asm volatile("" : "+v"(v)); }
+
 // BM x BN output tile per workgroup, the four waves arranged WGM x WGN over it (wave tile = (BM / WGM) x (BN / WGN),
 // a multiple of 32 x 32 each way).
 template <int BM, int BN, int WGM, int WGN>
@@ -321,46 +330,48 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 rh[VA], rl[VA], rb[VB];
-  auto fetch = [&](int k0) {
+  // Two K steps of operands are in flight in registers: a load takes longer than the matrix cores need for one step.
+  // The loads are issued through inline asm and waited for by count (the compiler would sink ordinary loads down to
+  // their first use and wait for all of them at every barrier): rows and K offsets past the end are clamped for the
+  // load and zeroed when the registers go to LDS, the step count is rounded up to even, the barriers wait for LDS
+  // only, and pf_wait<NL> lets exactly the other stage's NL loads stay outstanding (loads return in order).
+  struct Stage { u32x4_t h[VA], l[VA], b[VB]; };
+  constexpr int NL = 2 * VA + VB;
+  const int nsteps = (K + GB_K - 1) / GB_K;
+  auto fetch = [&](Stage& R, int step) __attribute__((always_inline)) {
+    const int k0 = min(step, nsteps - 1) * GB_K;
+#pragma unroll
+    for (int i = 0; i < VA; ++i) {
+      const int v = tid + WG * i, row = min(m0 + (v >> 3), M - 1), k = min(k0 + ((v & 7) << 3), K - 8);
+      pf_issue16(R.h[i], Ah + (size_t)row * K + k);
+      pf_issue16(R.l[i], Al + (size_t)row * K + k);
+    }
+#pragma unroll
+    for (int i = 0; i < VB; ++i) {
+      const int v = tid + WG * i, row = min(n0 + (v >> 3), N - 1), k = min(k0 + ((v & 7) << 3), K - 8);
+      pf_issue16(R.b[i], W + (size_t)row * K + k);
+    }
+  };
+  auto stash = [&](Stage& R, int step) __attribute__((always_inline)) {
+    const int k0 = step * GB_K;
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int i = 0; i < VA; ++i) {
       const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
-      const int k = k0 + kc;
-      rh[i] = make_uint4(0, 0, 0, 0); rl[i] = rh[i];
-      if (k < K && m0 + row < M) {
-        rh[i] = *reinterpret_cast<const uint4*>(Ah + (size_t)(m0 + row) * K + k);
-        rl[i] = *reinterpret_cast<const uint4*>(Al + (size_t)(m0 + row) * K + k);
-      }
+      const bool ok = step < nsteps && k0 + kc < K && m0 + row < M;
+      pf_use(R.h[i]); pf_use(R.l[i]);
+      *reinterpret_cast<u32x4_t*>(sAh + row * GB_PITCH + kc) = ok ? R.h[i] : zero;
+      *reinterpret_cast<u32x4_t*>(sAl + row * GB_PITCH + kc) = ok ? R.l[i] : zero;
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
-      const int k = k0 + kc;
-      rb[i] = make_uint4(0, 0, 0, 0);
-      if (k < K && n0 + row < N) rb[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k);
+      const bool ok = step < nsteps && k0 + kc < K && n0 + row < N;
+      pf_use(R.b[i]);
+      *reinterpret_cast<u32x4_t*>(sB + row * GB_PITCH + kc) = ok ? R.b[i] : zero;
     }
   };
-  auto stash = [&]() {
-#pragma unroll
-    for (int i = 0; i < VA; ++i) {
-      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
-      *reinterpret_cast<uint4*>(sAh + row * GB_PITCH + kc) = rh[i];
-      *reinterpret_cast<uint4*>(sAl + row * GB_PITCH + kc) = rl[i];
-    }
-#pragma unroll
-    for (int i = 0; i < VB; ++i) {
-      const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
-      *reinterpret_cast<uint4*>(sB + row * GB_PITCH + kc) = rb[i];
-    }
-  };
-
-  fetch(0);
-  for (int k0 = 0; k0 < K; k0 += GB_K) {
-    __syncthreads();
-    stash();
-    __syncthreads();
-    if (k0 + GB_K < K) fetch(k0 + GB_K);
+  auto compute = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < GB_K; kk += 16) {
       bf16x8_t ah[IM], al[IM], b[JN];
@@ -373,15 +384,43 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
 #pragma unroll
       for (int j = 0; j < JN; ++j)
         b[j] = *reinterpret_cast<const bf16x8_t*>(sB + (wn + j * 32 + (lane & 31)) * GB_PITCH + kk + ((lane >> 5) << 3));
+      // low halves first, then high halves: two products into the same accumulator are never issued back to back
 #pragma unroll
       for (int i = 0; i < IM; ++i)
 #pragma unroll
-        for (int j = 0; j < JN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], b[j], acc[i][j], 0, 0, 0);
-        }
+        for (int j = 0; j < JN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < JN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], b[j], acc[i][j], 0, 0, 0);
     }
+  };
+
+  Stage R0, R1;
+  fetch(R0, 0);
+  fetch(R1, 1);
+  for (int s = 0; s < nsteps; s += 2) {
+    lds_barrier();                       // everyone has read the previous step's tiles
+    pf_wait<NL>();                       // stage 0 has landed; stage 1 may still be on its way
+    stash(R0, s);
+    lds_barrier();
+    fetch(R0, s + 2);
+    compute();
+    lds_barrier();
+    pf_wait<NL>();
+    stash(R1, s + 1);
+    lds_barrier();
+    fetch(R1, s + 3);
+    compute();
   }
+  // The last two fetches (clamped re-loads nobody reads) are still on their way: wait for them, and only then let go of
+  // their destinations - the compiler would otherwise hand those registers to the epilogue's addresses while the loads
+  // can still land in them.
+  pf_wait<0>();
+#pragma unroll
+  for (int i = 0; i < VA; ++i) { pf_use(R0.h[i]); pf_use(R0.l[i]); pf_use(R1.h[i]); pf_use(R1.l[i]); }
+#pragma unroll
+  for (int i = 0; i < VB; ++i) { pf_use(R0.b[i]); pf_use(R1.b[i]); }
 #pragma unroll
   for (int i = 0; i < IM; ++i)
 #pragma unroll

@@ -18,7 +18,6 @@ constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row 
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
 constexpr int SK_TSLOTS = 12;         // timestamps per segment: arrive, barrier, attention, stage, stream, results
 
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 // Pointers that come out of a struct in memory are "generic" to the compiler and would be
 // read with flat instructions (which also tick the LDS wait counter); these helpers state
@@ -124,9 +123,6 @@ __device__ __forceinline__ void coh_issue4(int& v, const int* p) {
   asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(as_global(p)) : "memory");
 }
 
-// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait
-// for outstanding global loads, so weight prefetches stay in flight across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 // Wave-wide sum through the DPP cross-lane paths (a few cycles per step instead of an LDS
 // round trip per step): quads, half rows, rows, then the two row broadcasts of gfx9.  The
 // total ends up in lane 63.  Fixed order, so results are reproducible.
