@@ -82,6 +82,16 @@ def test_few_attention_splits_walk_several_key_tiles_per_wave():
     _run("mini_hd128", [1500, 700, 90], 3, 66, splits=2)
 
 
+def test_attention_work_list_with_very_different_lengths():
+    # one to a dozen splits per sequence in the same launch (splits in proportion to the lengths)
+    _run("step_hd128", [20, 300, 1500, 64, 700], 3, 75)
+
+
+def test_attention_without_a_work_list_when_the_batch_needs_too_many_items():
+    # one KV head: the smallest splits still fit one round of the compute units, 7 x 17 items exceed the list
+    _run("mini_hd128", [2048, 2040, 2000, 2048, 1990, 2030, 2010], 2, 76)
+
+
 def test_other_page_size_uses_the_generic_attention_kernel():
     _run("mini_bf16", [70, 130, 45], 4, 68, page=32)
 
