@@ -309,7 +309,7 @@ __device__ __forceinline__ void pf_use(u32x4_t& v) { asm volatile("" : "+v"(v));
 
 // BM x BN output tile per workgroup, the four waves arranged WGM x WGN over it (wave tile = (BM / WGM) x (BN / WGN),
 // a multiple of 32 x 32 each way).
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NSTG = 2>
 __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
                                                      const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
                                                      int K, int accumulate, int m0, int n0) {
@@ -333,7 +333,7 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
   // Two K steps of operands are in flight in registers: a load takes longer than the matrix cores need for one step.
   // The loads are issued through inline asm and waited for by count (the compiler would sink ordinary loads down to
   // their first use and wait for all of them at every barrier): rows and K offsets past the end are clamped for the
-  // load and zeroed when the registers go to LDS, the step count is rounded up to even, the barriers wait for LDS
+  // load and zeroed when the registers go to LDS, the step count is rounded up to a multiple of the stages, the barriers wait for LDS
   // only, and pf_wait<NL> lets exactly the other stage's NL loads stay outstanding (loads return in order).
   struct Stage { u32x4_t h[VA], l[VA], b[VB]; };
   constexpr int NL = 2 * VA + VB;
@@ -396,31 +396,33 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
     }
   };
 
-  Stage R0, R1;
-  fetch(R0, 0);
-  fetch(R1, 1);
-  for (int s = 0; s < nsteps; s += 2) {
-    lds_barrier();                       // everyone has read the previous step's tiles
-    pf_wait<NL>();                       // stage 0 has landed; stage 1 may still be on its way
-    stash(R0, s);
-    lds_barrier();
-    fetch(R0, s + 2);
-    compute();
-    lds_barrier();
-    pf_wait<NL>();
-    stash(R1, s + 1);
-    lds_barrier();
-    fetch(R1, s + 3);
-    compute();
+  // NSTG stages (K steps) of operands in flight; the loop is unrolled over the stages so that every stage is a fixed
+  // set of registers.
+  Stage R[NSTG];
+#pragma unroll
+  for (int q = 0; q < NSTG; ++q) fetch(R[q], q);
+  for (int s = 0; s < nsteps; s += NSTG) {
+#pragma unroll
+    for (int q = 0; q < NSTG; ++q) {
+      lds_barrier();                       // everyone has read the previous step's tiles
+      pf_wait<NL * (NSTG - 1)>();          // this stage has landed; the younger ones may still be on their way
+      stash(R[q], s + q);
+      lds_barrier();
+      fetch(R[q], s + q + NSTG);
+      compute();
+    }
   }
-  // The last two fetches (clamped re-loads nobody reads) are still on their way: wait for them, and only then let go of
+  // The last fetches (clamped re-loads nobody reads) are still on their way: wait for them, and only then let go of
   // their destinations - the compiler would otherwise hand those registers to the epilogue's addresses while the loads
   // can still land in them.
   pf_wait<0>();
 #pragma unroll
-  for (int i = 0; i < VA; ++i) { pf_use(R0.h[i]); pf_use(R0.l[i]); pf_use(R1.h[i]); pf_use(R1.l[i]); }
+  for (int q = 0; q < NSTG; ++q) {
 #pragma unroll
-  for (int i = 0; i < VB; ++i) { pf_use(R0.b[i]); pf_use(R1.b[i]); }
+    for (int i = 0; i < VA; ++i) { pf_use(R[q].h[i]); pf_use(R[q].l[i]); }
+#pragma unroll
+    for (int i = 0; i < VB; ++i) pf_use(R[q].b[i]);
+  }
 #pragma unroll
   for (int i = 0; i < IM; ++i)
 #pragma unroll
