@@ -700,19 +700,16 @@ int prefill_one(first_ctx* c, int b, const int* ids, int T, float* hidden_out, f
     if ((rc = gemm(a, c->p_ah, c->p_al, l.wo, c->p_H, D, c->nq, 1))) return rc;
     hipLaunchKernelGGL(k_rmsnorm_router<float>, dim3((T + WAVES - 1) / WAVES), dim3(WG), 0, st, c->p_H, l.g_mlp,
                        (const float*)nullptr, x, (float*)nullptr, T, D, d.rms_eps, hl ? c->p_xh : nullptr, hl ? c->p_xl : nullptr);
-    if (hl) {
-      if ((rc = launch_gemm_hl_seg(c, st, c->p_xh, c->p_xl, T, D, 0,
-                                   {GemmSeg{(const bf16*)l.wg, c->p_g, F, 0}, GemmSeg{(const bf16*)l.wu, c->p_u, F, 0}})))
-        return rc;
+    if (hl) {        // SiLU(gate) * up in the GEMM's epilogue, written split for the down projection
+      hipLaunchKernelGGL(k_gemm_nt_bf16_hl_gu, dim3((F + GB_N / 2 - 1) / (GB_N / 2), (T + GB_M - 1) / GB_M), dim3(WG), 0, st, c->p_xh,
+                         c->p_xl, (const bf16*)l.wg, (const bf16*)l.wu, c->p_zh, c->p_zl, T, F, D);
+      HIPCHK(c, hipGetLastError());
     } else {
       if ((rc = gemm(x, c->p_xh, c->p_xl, l.wg, c->p_g, F, D, 0))) return rc;
       if ((rc = gemm(x, c->p_xh, c->p_xl, l.wu, c->p_u, F, D, 0))) return rc;
     }
     const unsigned sm_grid = (unsigned)std::min<size_t>(((size_t)T * F + WG - 1) / WG, 65536);
-    if (hl)
-      hipLaunchKernelGGL(k_silu_mul_split, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, c->p_zh, c->p_zl, (size_t)T * F);
-    else
-      hipLaunchKernelGGL(k_silu_mul<float>, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, z, (size_t)T * F);
+    if (!hl) hipLaunchKernelGGL(k_silu_mul<float>, dim3(sm_grid), dim3(WG), 0, st, c->p_g, c->p_u, z, (size_t)T * F);
     if ((rc = gemm(z, c->p_zh, c->p_zl, l.wd, c->p_H, D, F, 1))) return rc;
     if (soft)
       hipLaunchKernelGGL(k_soft_blend, dim3((unsigned)std::min<size_t>(((size_t)T * D + WG - 1) / WG, 4096)), dim3(WG), 0, st,
@@ -820,7 +817,9 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, &c->d_rope_cs, (size_t)B * c->half)); A(dev_alloc(c, &c->d_arg_part, (size_t)B * ARG_MAX_WG));
   A(dev_alloc(c, &c->p_H, (size_t)T * d.d_model)); A(dev_alloc(c, &c->p_q, (size_t)T * c->nq));
   A(dev_alloc(c, &c->p_k, (size_t)T * c->nkv)); A(dev_alloc(c, &c->p_v, (size_t)T * c->nkv));
-  A(dev_alloc(c, &c->p_g, (size_t)T * d.d_ffn)); A(dev_alloc(c, &c->p_u, (size_t)T * d.d_ffn));
+  if (d.dtype != FIRST_DTYPE_BF16) {   // (bf16 models form SiLU(gate) * up in the GEMM's epilogue: no fp32 gate / up matrices)
+    A(dev_alloc(c, &c->p_g, (size_t)T * d.d_ffn)); A(dev_alloc(c, &c->p_u, (size_t)T * d.d_ffn));
+  }
   A(dev_alloc(c, &c->p_sig, T)); A(dev_alloc(c, &c->p_cs, (size_t)T * c->half));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_x), (size_t)T * d.d_model * 4));
   A(dev_alloc(c, reinterpret_cast<char**>(&c->p_a), (size_t)T * c->nq * 4));

@@ -309,17 +309,23 @@ __device__ __forceinline__ void pf_use(u32x4_t& v) { asm volatile("" : "+v"(v));
 
 // BM x BN output tile per workgroup, the four waves arranged WGM x WGN over it (wave tile = (BM / WGM) x (BN / WGN),
 // a multiple of 32 x 32 each way).
-template <int BM, int BN, int WGM, int WGN, int NSTG = 2>
+// GU: the B tile is BN / 2 rows of W (gate) followed by the same BN / 2 rows of W2 (up); instead of storing C the
+// epilogue forms SiLU(gate) * up for the tile's BM x BN / 2 outputs and writes them split into zh + zl ([M, N] bf16 each).
+template <int BM, int BN, int WGM, int WGN, int NSTG = 2, bool GU = false>
 __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
                                                      const bf16* __restrict__ W, float* __restrict__ C, int M, int N,
-                                                     int K, int accumulate, int m0, int n0) {
+                                                     int K, int accumulate, int m0, int n0,
+                                                     const bf16* __restrict__ W2 = nullptr, bf16* __restrict__ zh = nullptr,
+                                                     bf16* __restrict__ zl = nullptr) {
   static_assert(WGM * WGN == WAVES, "four waves");
   constexpr int TM = BM / WGM, TN = BN / WGN, IM = TM / 32, JN = TN / 32;
   constexpr int VA = BM * 8 / WG, VB = BN * 8 / WG;            // 16-byte vectors per thread and K step
   static_assert(TM % 32 == 0 && TN % 32 == 0 && VA >= 1 && VB >= 1, "tile shape");
-  __shared__ __align__(16) uint16_t sAh[BM * GB_PITCH];
-  __shared__ __align__(16) uint16_t sAl[BM * GB_PITCH];
-  __shared__ __align__(16) uint16_t sB[BN * GB_PITCH];
+  __shared__ __align__(16) uint16_t sAll[(2 * BM + BN) * GB_PITCH];     // one block: the GU epilogue reuses it
+  uint16_t* sAh = sAll;
+  uint16_t* sAl = sAll + BM * GB_PITCH;
+  uint16_t* sB = sAll + 2 * BM * GB_PITCH;
+  static_assert(!GU || (WGN == 2 && VB % 2 == 0 && (size_t)BM * (BN / 2) * 4 <= sizeof(sAll)), "gate columns | up columns");
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = (wave / WGN) * TM, wn = (wave % WGN) * TN;
   floatx16_t acc[IM][JN];
@@ -348,8 +354,14 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
     }
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
-      const int v = tid + WG * i, row = min(n0 + (v >> 3), N - 1), k = min(k0 + ((v & 7) << 3), K - 8);
-      pf_issue16(R.b[i], W + (size_t)row * K + k);
+      const int v = tid + WG * i, k = min(k0 + ((v & 7) << 3), K - 8);
+      if (GU) {                                        // rows 0 .. BN/2-1 of the tile: gate, the rest: up (i decides)
+        const int row = min(n0 + ((v >> 3) & (BN / 2 - 1)), N - 1);
+        pf_issue16(R.b[i], (i < VB / 2 ? W : W2) + (size_t)row * K + k);
+      } else {
+        const int row = min(n0 + (v >> 3), N - 1);
+        pf_issue16(R.b[i], W + (size_t)row * K + k);
+      }
     }
   };
   auto stash = [&](Stage& R, int step) __attribute__((always_inline)) {
@@ -366,7 +378,7 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
 #pragma unroll
     for (int i = 0; i < VB; ++i) {
       const int v = tid + WG * i, row = v >> 3, kc = (v & 7) << 3;
-      const bool ok = step < nsteps && k0 + kc < K && n0 + row < N;
+      const bool ok = step < nsteps && k0 + kc < K && n0 + (GU ? (row & (BN / 2 - 1)) : row) < N;
       pf_use(R.b[i]);
       *reinterpret_cast<u32x4_t*>(sB + row * GB_PITCH + kc) = ok ? R.b[i] : zero;
     }
@@ -423,6 +435,40 @@ __device__ __forceinline__ void gemm_nt_bf16_hl_tile(const bf16* __restrict__ Ah
 #pragma unroll
     for (int i = 0; i < VB; ++i) pf_use(R[q].b[i]);
   }
+  if constexpr (GU) {
+    // the up waves (wn != 0) pass their accumulators through LDS to the gate waves of the same rows
+    float* u_lds = reinterpret_cast<float*>(sAll);                 // [BM][BN / 2]
+    lds_barrier();                                                 // every wave has finished reading the operand tiles
+    if (wn != 0) {
+#pragma unroll
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < JN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            u_lds[(wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * (BN / 2) + j * 32 + (lane & 31)] = acc[i][j][r];
+    }
+    lds_barrier();
+    if (wn == 0) {
+#pragma unroll
+      for (int i = 0; i < IM; ++i)
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
+          const int col = n0 + j * 32 + (lane & 31);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int rl = wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), row = m0 + rl;
+            if (row < M && col < N) {
+              const float z = siluf(acc[i][j][r]) * u_lds[rl * (BN / 2) + j * 32 + (lane & 31)];
+              const bf16 h = from_f32<bf16>(z);
+              zh[(size_t)row * N + col] = h;
+              zl[(size_t)row * N + col] = from_f32<bf16>(z - to_f32(h));
+            }
+          }
+        }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < IM; ++i)
 #pragma unroll
@@ -466,6 +512,16 @@ __global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl_seg(const bf16* __restri
   while (i + 1 < segs.n && bx >= segs.s[i].blocks) { bx -= segs.s[i].blocks; ++i; }
   const GemmSeg g = segs.s[i];
   gemm_nt_bf16_hl_tile<GB_M, GB_N, 2, 2>(Ah, Al, g.W, g.C, M, g.N, K, accumulate, blockIdx.y * GB_M, bx * GB_N);
+}
+
+// Gate and up projections with SiLU(gate) * up in the epilogue: a workgroup takes 64 columns of both matrices for its
+// 128 rows, so the MLP activation leaves the GEMM already split for the down projection - no fp32 gate / up
+// matrices in memory and no elementwise launch.  N = d_ffn.
+__global__ void __launch_bounds__(WG) k_gemm_nt_bf16_hl_gu(const bf16* __restrict__ Ah, const bf16* __restrict__ Al,
+                                                           const bf16* __restrict__ Wg, const bf16* __restrict__ Wu,
+                                                           bf16* __restrict__ zh, bf16* __restrict__ zl, int M, int N, int K) {
+  gemm_nt_bf16_hl_tile<GB_M, GB_N, 2, 2, 2, true>(Ah, Al, Wg, nullptr, M, N, K, 0, blockIdx.y * GB_M, blockIdx.x * (GB_N / 2), Wu,
+                                                  zh, zl);
 }
 
 // fp32 variant (the small full-precision configuration): 64x64 tile, 4x4 per thread.
