@@ -87,6 +87,12 @@ def test_attention_work_list_with_very_different_lengths():
     _run("step_hd128", [20, 300, 1500, 64, 700], 3, 75)
 
 
+def test_long_batched_run_keeps_its_graph_while_the_sequences_grow():
+    # 140 steps on one cached graph: every sequence crosses key-tile and page boundaries several times, so the splits
+    # of the attention work list (fixed when the graph was built) get longer, and new pages enter the tables
+    _run("step_hd128", [60, 130, 20], 140, 77)
+
+
 def test_attention_without_a_work_list_when_the_batch_needs_too_many_items():
     # one KV head: the smallest splits still fit one round of the compute units, 7 x 17 items exceed the list
     _run("mini_hd128", [2048, 2040, 2000, 2048, 1990, 2030, 2010], 2, 76)
