@@ -186,6 +186,25 @@ int first_decode_step(first_ctx *ctx, const int32_t *last_tokens, float *logits_
 int first_sample_top_k(first_ctx *ctx, const float *logits, const float *uniforms, float temperature,
                        int32_t top_k, int32_t *token_out, int32_t *candidates_out);
 
+/* first_sample_top_k for callers that cannot allocate device memory or hold a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same rule, same kernels and the same
+ * results as first_sample_top_k, on any logits: the per-chunk candidate lists of the first stage live in a
+ * 1 MiB device array that is part of the library image (one copy per GPU, held until the process ends), and
+ * the call makes no hipMalloc / hipFree or other allocating call.
+ *   hip_stream     hipStream_t the two kernels are enqueued on (NULL: the null stream)
+ *   logits         DEV fp32  [n_seq, vocab]
+ *   uniforms       DEV fp32  [n_seq]          one number in [0, 1) per sequence
+ *   token_out      DEV int32 [n_seq]
+ *   candidates_out DEV int32 [n_seq, top_k]   (may be NULL)
+ * Limit: n_seq * ceil(vocab / 2048) * top_k <= 131072, else FIRST_ERR_CAPACITY (e.g. vocab 128256, top_k 10:
+ * up to 208 sequences).  FIRST_ERR_ARG on null pointers or parameters out of range; nothing is written on
+ * error; the text of the failure is first_last_error(NULL).  All calls on one GPU share that GPU's array:
+ * calls that may overlap in time on one GPU (different streams, different threads) race and must be
+ * serialised by the caller; calls on one stream are ordered and safe. */
+int first_sample_top_k_static(void *hip_stream, const float *logits, int32_t n_seq, int32_t vocab,
+                              const float *uniforms, float temperature, int32_t top_k,
+                              int32_t *token_out, int32_t *candidates_out);
+
 int first_set_option(first_ctx *ctx, int32_t option, int32_t value);
 int first_sync(first_ctx *ctx);                          /* hipStreamSynchronize of the stream */
 const char *first_last_error(const first_ctx *ctx);      /* ctx may be NULL: last create error */

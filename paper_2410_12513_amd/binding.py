@@ -16,7 +16,7 @@ EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_ma
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
            "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len", "first_kv_usage", "first_soft_forward",
-           "first_lora_merge"]
+           "first_lora_merge", "first_sample_top_k_static"]
 
 
 class FirstError(RuntimeError):
@@ -323,5 +323,20 @@ def op_gemm_nt_f32a(A: torch.Tensor, W: torch.Tensor, Cm: torch.Tensor, accumula
     _check_dev(A, torch.float32, "A"); _check_dev(W, torch.bfloat16, "W"); _check_dev(Cm, torch.float32, "C", m * n)
     rc = lib.first_op_gemm_nt_f32a(_stream_ptr(stream), _ptr(A), _ptr(W), _ptr(Cm), C.c_int32(m), C.c_int32(n),
                                    C.c_int32(k), C.c_int32(int(accumulate)))
+    if rc != 0:
+        raise FirstError(rc, lib.first_last_error(None).decode())
+
+
+def sample_top_k_static(logits: torch.Tensor, uniforms: torch.Tensor, temperature: float, top_k: int,
+                        token_out: torch.Tensor, candidates_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """first_sample_top_k without a context and without any allocation (static scratch inside the library)."""
+    lib = load_library()
+    n_seq, vocab = logits.shape
+    _check_dev(logits, torch.float32, "logits"); _check_dev(uniforms, torch.float32, "uniforms", n_seq)
+    _check_dev(token_out, torch.int32, "token_out", n_seq)
+    if candidates_out is not None:
+        _check_dev(candidates_out, torch.int32, "candidates_out", n_seq * top_k)
+    rc = lib.first_sample_top_k_static(_stream_ptr(stream), _ptr(logits), C.c_int32(n_seq), C.c_int32(vocab), _ptr(uniforms),
+                                       C.c_float(temperature), C.c_int32(top_k), _ptr(token_out), _ptr(candidates_out))
     if rc != 0:
         raise FirstError(rc, lib.first_last_error(None).decode())

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -19,9 +20,20 @@
 
 using namespace first;
 
+// Scratch of first_sample_top_k_static, the entry point that allocates nothing: the per-chunk candidate lists of
+// its first stage.  Every device the library runs on holds its own copy of the array (at its own address) until
+// the process ends.  Host code never uses the array's name as an address: g_scratch_ptr[device] is what
+// hipGetSymbolAddress returned with that device current.
+constexpr long long STATIC_SCRATCH_CANDS = 131072;           // 1 MiB of {logit, index} pairs
+constexpr int STATIC_SCRATCH_MAX_DEV = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_CANDS * 8];
+static void* g_scratch_ptr[STATIC_SCRATCH_MAX_DEV] = {};
+static std::mutex g_scratch_mutex;
+
 namespace {
 
 thread_local std::string g_create_error;
+
 
 struct LayerPtrs {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
@@ -1089,6 +1101,47 @@ int first_sample_top_k(first_ctx* c, const float* logits, const float* uniforms,
   hipLaunchKernelGGL(k_topk_sample, dim3(c->B), dim3(SMP_THREADS), 0, c->stream, c->d_topk_part, chunks * top_k, top_k,
                      temperature, uniforms, token_out, candidates_out);
   HIPCHK(c, hipGetLastError());
+  return FIRST_OK;
+}
+
+int first_sample_top_k_static(void* hip_stream, const float* logits, int32_t n_seq, int32_t vocab, const float* uniforms,
+                              float temperature, int32_t top_k, int32_t* token_out, int32_t* candidates_out) {
+  auto bad = [](int code, const char* msg) { g_create_error = msg; return code; };
+  if (!logits || !uniforms || !token_out) return bad(FIRST_ERR_ARG, "first_sample_top_k_static: null pointer");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return bad(FIRST_ERR_ARG, "first_sample_top_k_static: temperature must be positive");
+  if (top_k < 1 || top_k > SMP_KMAX) return bad(FIRST_ERR_ARG, "first_sample_top_k_static: top_k must be in 1..64");
+  if (n_seq < 1 || vocab < 1) return bad(FIRST_ERR_ARG, "first_sample_top_k_static: n_seq and vocab must be positive");
+  const long long chunks = ((long long)vocab + SMP_CHUNK - 1) / SMP_CHUNK;
+  if ((long long)n_seq * chunks * top_k > STATIC_SCRATCH_CANDS || chunks > 65535 || n_seq > 65535)
+    return bad(FIRST_ERR_CAPACITY, "first_sample_top_k_static: n_seq * ceil(vocab / 2048) * top_k exceeds the 131072 candidates "
+                                   "of the static scratch array");
+  Cand* part = nullptr;
+  {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_SCRATCH_MAX_DEV)
+      return bad(FIRST_ERR_HIP, "first_sample_top_k_static: no current device (or device ordinal >= 64)");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {                       // once per device: the address of THIS device's copy of the array
+      void* p = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) {
+        g_create_error = std::string("first_sample_top_k_static: hipGetSymbolAddress: ") + hipGetErrorString(e);
+        return FIRST_ERR_HIP;
+      }
+      g_scratch_ptr[dev] = p;
+    }
+    part = reinterpret_cast<Cand*>(g_scratch_ptr[dev]);
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  // every candidate slot stage 2 reads is written by stage 1 of the same call: nothing to clear
+  hipLaunchKernelGGL(k_topk_part, dim3((unsigned)chunks, n_seq), dim3(SMP_THREADS), 0, st, logits, vocab, top_k, part);
+  hipLaunchKernelGGL(k_topk_sample, dim3(n_seq), dim3(SMP_THREADS), 0, st, part, (int)chunks * top_k, top_k, temperature, uniforms,
+                     token_out, candidates_out);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    g_create_error = std::string("first_sample_top_k_static: ") + hipGetErrorString(e);
+    return FIRST_ERR_HIP;
+  }
   return FIRST_OK;
 }
 
