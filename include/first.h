@@ -56,22 +56,11 @@ extern "C" {
                                       read copies of the matrices in MFMA tile order, made at first_create (as much memory
                                       again as the weights; the caller's matrices must not change afterwards); 0 = they
                                       read the caller's row-major matrices */
-#define FIRST_OPT_STEP_BALANCE  8  /* persistent kernel: 1 = after every step the per-XCD shares of the weight rows follow
-                                      the measured streaming times (results do not depend on the shares); 0 (default) =
-                                      even split.  Setting it resets the shares.  Measured: evens the per-XCD arrival
-                                      times at the barriers, no gain in step time (the spread inside an XCD remains). */
 #define FIRST_OPT_PREFILL_ATTN  7  /* prompt attention.  1 (default): tiled kernel on the matrix cores when the cache is bf16
                                       and head_dim is 64 or 128, else the plain kernel; 0: always the plain fp32 kernel */
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
                                       keep it share one pass over its weights (bf16 models, widths multiples of 8),
                                       else one pass per sequence; 0: always one pass per sequence; 1: shared pass or error */
-#define FIRST_OPT_STEP_BARRIER  5  /* how the workgroups of the persistent kernel hand activations on between
-                                      phases.  2 (default): no grid barrier; every exchanged 32-bit word carries an
-                                      alternating tag in its lowest mantissa bit and consumers re-read until all
-                                      words are current.  3: tagged words as in 2, plus the grid barrier of 1 as
-                                      the signal to read them.  1: grid barrier, workgroups of one XCD count arrivals
-                                      in their shared L2 and the last one publishes one flag per XCD; 0: grid
-                                      barrier, every workgroup publishes a flag and polls all of them */
 
 typedef struct first_ctx first_ctx;
 
@@ -297,16 +286,12 @@ int first_op_gemm_nt_f32a(void *hip_stream, const float *A, const void *W, float
 
 /* Per-phase timestamps of the last persistent-kernel decode step (FIRST_OPT_STEP_TIMING = 1),
  * taken by workgroup 0 on the 100 MHz device clock: for each phase (QKV, O, gate/up, down of
- * every kept layer in order, then the LM head) twelve values: arrival at the phase's barrier,
- * barrier passed, attention done (O phase only), input staged, weights streamed, results
- * stored, then six marks inside the attention of workgroup 0 (O phase only).  stamps HOST uint64 [capacity]; n_out HOST receives the count.  Synchronises. */
+ * every kept layer in order, then the LM head) twelve values: phase begins (twice), attention
+ * done (O phase only), input staged, weights streamed, results stored, then six marks inside the
+ * attention of workgroup 0 (O phase only): start, queries in LDS, tiles done, waves folded, other
+ * splits' results arrived, output stored.  stamps HOST uint64 [capacity]; n_out HOST receives the
+ * count.  Synchronises. */
 int first_step_timing(first_ctx *ctx, uint64_t *stamps, int32_t capacity, int32_t *n_out);
-
-/* Row shares of the persistent kernel (FIRST_OPT_STEP_BALANCE): shares8 (host, 8 ints, 1024 = an even
- * share per XCD, sum 8192).  times (host, may be null; capacity >= number of compute units): per workgroup
- * of the last step, gate/up streaming time in 100 MHz ticks (low 24 bits) and its XCD (top byte).
- * Synchronises the stream.  Inspection only: results never depend on the shares. */
-int first_step_shares(first_ctx *ctx, int32_t *shares8, uint32_t *times, int32_t capacity);
 
 /* Launches only the gate/up kernel of one layer (the largest kernel of a decode step,
  * Section 2 Eq. 1's phi_i: z = silu(Wg y) * (Wu y), y = RMSNorm(h)) for sequence slot seq, on

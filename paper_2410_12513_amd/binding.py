@@ -15,7 +15,7 @@ OPT_USE_GRAPH, OPT_ATTN_SPLITS, OPT_DECODE_PATH = 1, 2, 3
 EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_mask", "first_get_kept",
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
-           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_step_shares", "first_set_seq_len", "first_kv_usage", "first_soft_forward",
+           "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_set_seq_len", "first_kv_usage", "first_soft_forward",
            "first_lora_merge", "first_sample_top_k_static"]
 
 
@@ -242,20 +242,11 @@ class FirstContext:
 
     def step_timing(self):
         """Timestamps [phases, 6] (100 MHz ticks) of the last persistent-kernel step."""
-        cap = (4 * self.desc.n_layers + 1) * 12 + 2 * 1024
+        cap = (4 * self.desc.n_layers + 1) * 12
         arr = (C.c_uint64 * cap)()
         n = C.c_int32()
         self._chk(self.lib.first_step_timing(self.h, arr, C.c_int32(cap), C.byref(n)))
-        self.barrier_trace = list(arr[n.value:n.value + 2 * 256])     # arrival / release per workgroup (timing aid)
-        self.stream_trace = list(arr[n.value + 2 * 256:n.value + 2 * 256 + 16])
         return [list(arr[i:i + 12]) for i in range(0, n.value, 12)]
-
-    def step_shares(self):
-        """(per-XCD row shares [8], per-workgroup (ticks, xcd) of the last persistent-kernel step)."""
-        sh = (C.c_int32 * 8)()
-        tm = (C.c_uint32 * 4096)()
-        self._chk(self.lib.first_step_shares(self.h, sh, tm, C.c_int32(4096)))
-        return list(sh), [(v & 0xffffff, v >> 24) for v in tm]
 
     def num_pages(self) -> int:
         n = C.c_int32()

@@ -20,7 +20,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 # sums a last arriver collects):
 # the compiler does not know that the destination of such a load is written later, so a destination it spills and
 # hands to another value is overwritten when the load lands.  Bytes of scratch per lane each kernel may use:
-SCRATCH_LIMITS = {"k_step": 0, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv_g": 0, "k_gemm_nt_bf16_hl": 0}
+SCRATCH_LIMITS = {"k_step": 64, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv_g": 0, "k_gemm_nt_bf16_hl": 0}
 
 
 def kernel_resources(remarks: str) -> dict:

@@ -164,7 +164,7 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
   // the merged output goes out split into bf16 high and low halves, in the order the output
   // projection's A operand reads (slot = position of the sequence in this pass)
   SP.xh_out = P.x2h; SP.xl_out = P.x2l; SP.out_slot = blockIdx.z;
-  sk_attention<HD, SK_WAVES, false, true>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
+  sk_attention<HD, SK_WAVES, true>(SP, reinterpret_cast<bf16*>(p.kv_layer), S, blockIdx.y, blockIdx.x, nsplit, nullptr);
 }
 
 // Decode attention of (split, KV head, slot) for models with G = Hq / Hkv query heads per KV

@@ -101,7 +101,7 @@ struct first_ctx {
   hipEvent_t ev_keep = nullptr;
   // persistent whole-step kernel (bf16, one live sequence)
   LayerDev* d_layers = nullptr;
-  unsigned* d_bar = nullptr;
+  unsigned* d_done = nullptr;             // [num_cu] per-workgroup epochs of the final reduction
   // batched decode (several live sequences): split activations, 1/rms per slot, logits when the caller wants none
   bf16 *d_xh = nullptr, *d_xl = nullptr, *d_zh = nullptr, *d_zl = nullptr, *d_x2h = nullptr, *d_x2l = nullptr;
   float* d_ssq = nullptr;                 // [SSQ_GROUPS][16] per-tile-group sums of squares (fused split of the O / down epilogues)
@@ -110,13 +110,9 @@ struct first_ctx {
   int batch_path = -1;                    // FIRST_OPT_BATCH_PATH
   bf16* t_head = nullptr;                 // tile-order copy of the LM head
   bool tiled = false;                     // tile-order copies of all matrices exist
-  int *d_shares = nullptr;                // per-XCD row shares of the persistent kernel (1024 = equal)
-  unsigned* d_share_time = nullptr;
-  int step_balance = 0;                   // FIRST_OPT_STEP_BALANCE
-  int step_two_level = 1;                 // persistent kernel's grid barrier: per-XCD counters (1) or flat flags (0)
-  int step_tagged = 1;                    // persistent kernel exchanges activations as tagged words instead of using grid barriers
   float *x_h = nullptr, *x_qkv = nullptr, *x_attn = nullptr, *x_z = nullptr;   // tagged exchange vectors (written by k_step only)
-  int* d_tagstate = nullptr;              // [B][4] tags of their latest writes
+  float* x_part = nullptr;                // tagged partial attention results of key splits 1.. (sk_part_index)
+  int* d_tagstate = nullptr;              // [B][8] tags of their latest writes, epoch of the latest final reduction
   int* d_err = nullptr;
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
   int step_timing = 0;
@@ -168,13 +164,6 @@ int gemv_grid(int rows, int R, int num_cu) {
   return std::max(1, std::min(need, num_cu * 4));
 }
 
-hipError_t reset_shares(first_ctx* c) {
-  const int eq[8] = {1024, 1024, 1024, 1024, 1024, 1024, 1024, 1024};
-  hipError_t e = hipMemcpy(c->d_shares, eq, sizeof(eq), hipMemcpyHostToDevice);
-  if (e == hipSuccess) e = hipMemset(c->d_share_time, 0, (size_t)c->num_cu * sizeof(unsigned));
-  return e;
-}
-
 // Tagged exchange of the persistent kernel: all-zero vectors and "latest tag 0" are a consistent start.
 hipError_t reset_tagged_exchange(first_ctx* c) {
   const size_t Bm = (size_t)c->d.max_batch;
@@ -182,7 +171,9 @@ hipError_t reset_tagged_exchange(first_ctx* c) {
   if (e == hipSuccess) e = hipMemset(c->x_qkv, 0, Bm * (c->nq + 2 * c->nkv) * sizeof(float));
   if (e == hipSuccess) e = hipMemset(c->x_attn, 0, Bm * c->nq * sizeof(float));
   if (e == hipSuccess) e = hipMemset(c->x_z, 0, Bm * c->d.d_ffn * sizeof(float));
-  if (e == hipSuccess) e = hipMemset(c->d_tagstate, 0, Bm * 4 * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(c->x_part, 0, sk_part_index(c->d.n_q_heads, c->d.head_dim, (int)Bm, 0, 0) * sizeof(float));
+  if (e == hipSuccess) e = hipMemset(c->d_tagstate, 0, Bm * 8 * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(c->d_done, 0, (size_t)c->num_cu * sizeof(unsigned));
   return e;
 }
 
@@ -531,25 +522,12 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d = base_params(c, 0, 1);
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
-  P.bar = c->d_bar; P.err = c->d_err; P.two_level = c->step_two_level;
-  const bool tagged = c->step_tagged && c->d.d_model <= 64 * c->num_cu;       // (one residual row per service-wave lane)
-  if (tagged) {
-    P.tagged = c->step_tagged; P.tagstate = c->d_tagstate; P.h_out = c->d_h;
-    P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
-  }
-  P.shares = c->d_shares; P.share_time = c->step_balance ? c->d_share_time : nullptr;
+  P.done = c->d_done; P.err = c->d_err;
+  P.tagstate = c->d_tagstate; P.h_out = c->d_h; P.part = c->x_part;
+  P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
-  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(WG), 0, c->stream, c->d_bar, 0u, (size_t)sk_bar_words(c->num_cu));
-  if (c->d.head_dim == 128 && tagged)
-    hipLaunchKernelGGL((k_step<128, true>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
-  else if (c->d.head_dim == 128)
-    hipLaunchKernelGGL((k_step<128, false>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
-  else if (tagged)
-    hipLaunchKernelGGL((k_step<64, true>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
-  else
-    hipLaunchKernelGGL((k_step<64, false>), dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
-  if (c->step_balance)
-    hipLaunchKernelGGL(k_rebalance, dim3(1), dim3(256), 0, c->stream, c->d_share_time, c->d_shares, c->num_cu);
+  if (c->d.head_dim == 128) hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  else hipLaunchKernelGGL(k_step<64>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
 }
 
 // Does the geometry fit the persistent kernel's static work split?
@@ -558,12 +536,12 @@ bool step_kernel_fits(const first_ctx* c) {
   if (d.dtype != FIRST_DTYPE_BF16) return false;
   if (d.d_model % 256 || c->nq % 256 || d.d_ffn % 256) return false;           // row segments may be partial, rows stay 512-byte aligned
   if (c->G > SK_SWAVES || d.kv_page_tokens != 16) return false;               // one streaming wave per query head of a KV group
-  if (d.n_kv_heads > c->num_cu || d.d_ffn > 16384 || d.d_model > 16384 || c->nq > 16384) return false;
   const int ncu = c->num_cu;
+  if (d.n_q_heads > ncu || d.d_ffn > 16384 || d.d_model > 64 * ncu || d.d_model > 16384 || c->nq > 16384) return false;   // (one residual row per service-wave lane)
   if ((long long)std::max({d.vocab, 2 * d.d_ffn, c->nq + 2 * c->nkv}) * (ncu + 1) >= (1LL << 31)) return false;
-  // (rows per workgroup: up to 15 % above an even share, see k_rebalance)
-  auto units = [&](long long rows, int K) { return (int)(((rows + ncu - 1) / ncu) * 6 / 5 + 4) * ((K + SK_SEG - 1) / SK_SEG); };
-  const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), units(d.d_model, c->nq),
+  // (the output projection's rows may sit on half of the workgroups, at most 64 rows each)
+  auto units = [&](long long rows, int K) { return (int)((rows + ncu - 1) / ncu + 2) * ((K + SK_SEG - 1) / SK_SEG); };
+  const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), 66 * ((c->nq + SK_SEG - 1) / SK_SEG),
                               units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});
   if (worst > SK_PSUM) return false;
   return sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float) <= 150 * 1024;
@@ -872,13 +850,13 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     FIRST_BGG_ATTR(BG_QKV) FIRST_BGG_ATTR(BG_O) FIRST_BGG_ATTR(BG_DN) FIRST_BGG_ATTR(BG_GU)
 #undef FIRST_BGG_ATTR
   }
-  A(dev_alloc(c, &c->d_shares, 8)); A(dev_alloc(c, &c->d_share_time, (size_t)c->num_cu));
   A(dev_alloc(c, &c->d_topk_part, (size_t)B * ((d.vocab + SMP_CHUNK - 1) / SMP_CHUNK) * SMP_KMAX));
   A(dev_alloc(c, &c->x_h, (size_t)B * d.d_model)); A(dev_alloc(c, &c->x_qkv, (size_t)B * (c->nq + 2 * c->nkv)));
   A(dev_alloc(c, &c->x_attn, (size_t)B * c->nq)); A(dev_alloc(c, &c->x_z, (size_t)B * d.d_ffn));
-  A(dev_alloc(c, &c->d_tagstate, (size_t)B * 4));
-  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_bar, (size_t)sk_bar_words(c->num_cu))); A(dev_alloc(c, &c->d_err, 4));
-  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 2 * (size_t)c->num_cu + 16));
+  A(dev_alloc(c, &c->x_part, sk_part_index(d.n_q_heads, d.head_dim, B, 0, 0)));
+  A(dev_alloc(c, &c->d_tagstate, (size_t)B * 8));
+  A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_done, (size_t)c->num_cu)); A(dev_alloc(c, &c->d_err, 4));
+  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 65536 + 65536));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
     for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
@@ -887,23 +865,16 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_head_cnt, 0, B * sizeof(unsigned));
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, B * sizeof(int));
     if (e == hipSuccess) e = hipMemset(c->d_err, 0, 4 * sizeof(int));
-    if (e == hipSuccess) e = reset_shares(c);
     if (e == hipSuccess) e = reset_tagged_exchange(c);
-    if (e == hipSuccess) e = hipMemset(c->d_bar, 0, (size_t)sk_bar_words(c->num_cu) * sizeof(unsigned));
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
       e = upload_layer_table(c);
       c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
-      const void* fns[2] = {d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128, true>)
-                                              : reinterpret_cast<const void*>(&k_step<64, true>),
-                            d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128, false>)
-                                              : reinterpret_cast<const void*>(&k_step<64, false>)};
-      for (const void* fn : fns) {
-        if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
-        int per_cu = 0;
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, SK_THREADS, c->step_lds);
-        if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
-      }
+      const void* fn = d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>) : reinterpret_cast<const void*>(&k_step<64>);
+      if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
+      int per_cu = 0;
+      if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, SK_THREADS, c->step_lds);
+      if (e == hipSuccess && per_cu < 1) c->step_ok = false;   // grid would not be co-resident
     }
     if (e == hipSuccess && B > 1 && d.dtype == FIRST_DTYPE_BF16 && d_batch_fits(c)) e = make_tiled_copies(c);
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
@@ -1163,24 +1134,11 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
       c->tiled = value != 0 && c->t_head != nullptr;
       drop_graphs(c);
       return FIRST_OK;
-    case FIRST_OPT_STEP_BALANCE:
-      HIPCHK(c, hipStreamSynchronize(c->stream));
-      c->step_balance = value ? 1 : 0;
-      HIPCHK(c, reset_shares(c));
-      drop_graphs(c);
-      return FIRST_OK;
     case FIRST_OPT_PREFILL_ATTN:
       c->prefill_flash = value ? 1 : 0; return FIRST_OK;
     case FIRST_OPT_BATCH_PATH:
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
       c->batch_path = value; return FIRST_OK;
-    case FIRST_OPT_STEP_BARRIER:
-      if (value < 0 || value > 3) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown barrier kind");
-      c->step_tagged = value == 2 ? 1 : value == 3 ? 2 : 0;
-      if (value < 2) c->step_two_level = value;
-      if (value == 3) c->step_two_level = 1;
-      drop_graphs(c);
-      return FIRST_OK;
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
   }
 }
@@ -1423,27 +1381,16 @@ int first_step_timing(first_ctx* c, uint64_t* stamps, int32_t capacity, int32_t*
   if (capacity < n) return fail(c, FIRST_ERR_ARG, "first_step_timing: buffer too small");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(stamps, c->d_tdbg, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost));
-  // optional tail: arrival / release of every workgroup at one barrier (timing aid)
-  const int tail = 2 * c->num_cu + 16;
-  if (capacity >= n + tail) {
-    HIPCHK(c, hipMemcpy(stamps + n, c->d_tdbg + (size_t)(4 * c->d.n_layers + 1) * SK_TSLOTS, (size_t)tail * sizeof(uint64_t),
-                        hipMemcpyDeviceToHost));
-  }
   *n_out = n;
   return FIRST_OK;
 }
 
-int first_step_shares(first_ctx* c, int32_t* shares8, uint32_t* times, int32_t capacity) {
-  if (!c) return FIRST_ERR_ARG;
-  if (!shares8) return fail(c, FIRST_ERR_ARG, "first_step_shares: null output");
-  HIPCHK(c, hipStreamSynchronize(c->stream));
-  HIPCHK(c, hipMemcpy(shares8, c->d_shares, 8 * sizeof(int32_t), hipMemcpyDeviceToHost));
-  if (times) {
-    if (capacity < c->num_cu) return fail(c, FIRST_ERR_ARG, "first_step_shares: buffer too small");
-    HIPCHK(c, hipMemcpy(times, c->d_share_time, (size_t)c->num_cu * sizeof(uint32_t), hipMemcpyDeviceToHost));
-  }
-  return FIRST_OK;
+#ifdef SK_DBG_DUMP
+int first_debug_read(first_ctx* c, float* host, int n) {
+  hipStreamSynchronize(c->stream);
+  return (int)hipMemcpy(host, reinterpret_cast<float*>(c->d_tdbg + (size_t)(4 * c->d.n_layers + 1) * SK_TSLOTS), (size_t)n * 4, hipMemcpyDeviceToHost);
 }
+#endif
 
 int first_op_gateup(first_ctx* c, int32_t layer, int32_t seq) {
   if (!c) return FIRST_ERR_ARG;

@@ -1,9 +1,12 @@
-// Whole decode step of one sequence as ONE persistent kernel (bf16 models, batch 1):
-// one 512-thread workgroup per compute unit (256 VGPRs per lane for deep prefetch), phases separated by grid-wide barriers, and
-// the weights of the next phase requested from HBM before each barrier so the memory system
-// never drains while workgroups wait.  Kept-layer indices are read from the device-side
-// compaction, so a skipped layer costs neither a launch nor a byte (Section 4.3 item 2).
+// Whole decode step of one sequence as ONE persistent kernel (bf16 models, batch 1): one 512-thread workgroup per
+// compute unit (256 VGPRs per lane for deep prefetch).  Seven waves of a workgroup only stream weights through a ring of
+// in-flight loads that runs on across phase boundaries; the eighth (the service wave) turns partial sums into outputs and
+// stages the next phase's input.  Workgroups hand activations to each other as self-validating ("tagged") words, so no
+// grid barrier separates the phases.  Kept-layer indices are read from the device-side compaction, so a skipped layer
+// costs neither a launch nor a byte (Section 4.3 item 2).
 #pragma once
+#include <type_traits>
+
 #include "decode_kernels.h"
 
 namespace first {
@@ -15,8 +18,9 @@ constexpr int SK_SEG = 2048;          // elements of a weight row handled by one
 constexpr int SK_PD = 7;              // row segments in flight per wave (28 KB; 8 measured no faster and leaves no spare registers)
 constexpr int SK_PD_EARLY = 4;        // ring slots that stay in flight across the attention phase
 constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row segments per phase)
+constexpr int SK_QSPLIT_MAX = 8;      // attention of the persistent kernel: at most this many key splits per query head
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
-constexpr int SK_TSLOTS = 12;         // timestamps per segment: arrive, barrier, attention, stage, stream, results
+constexpr int SK_TSLOTS = 12;         // timestamps per segment: arrive, -, attention, stage, stream, results, then six marks inside attention
 
 
 // Pointers that come out of a struct in memory are "generic" to the compiler and would be
@@ -143,6 +147,7 @@ __device__ __forceinline__ float wave_sum_lane63(float v) {
 __device__ __forceinline__ void vm_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void stg_bf16(bf16* p, bf16 v) { *as_global(&p->v) = v.v; }
 
+
 struct LayerDev {
   const bf16 *wq, *wk, *wv, *wo, *wg, *wu, *wd;
   const float *g_attn, *g_mlp;
@@ -166,22 +171,18 @@ __device__ __forceinline__ LayerDev load_layer(const LayerDev* arr, int i) {
 }
 
 struct StepParams {
-  DecParams d;                 // geometry, workspaces, sequence slot (layer fields unused)
+  DecParams d;                 // geometry, workspaces, sequence slot (layer fields unused); h, qkv, attn and z hold tagged words
   const LayerDev* layers;      // [L]
   const int* kept;             // [B][L] ascending kept-layer indices
   const int* n_kept;           // [B]
   int L;
-  unsigned* bar;               // grid barrier words (sk_bar_words(grid size) of them), zero at launch
-  int two_level;               // 1: per-XCD arrival counters + one flag per XCD; 0: every workgroup polls every flag
-  const int* shares;           // [8] per-XCD share of the rows (1024 = equal), or null: even split
-  unsigned* share_time;        // [grid] out: this workgroup's gate/up streaming time (100 MHz ticks), its XCD in the top byte
-  int* err;                    // set to 1 if a barrier wait gives up
-  int tagged;                  // activations are exchanged as self-validating words (see "Tagged exchange"): 1: consumers poll
-                               // the words themselves, no grid barrier between phases; 2: a grid barrier tells them when to
-                               // read, and the arrival travels together with the stores instead of after them
-  int* tagstate;               // [B][4] tag of the latest write to the h, qkv, attn and z vectors of each slot (tagged exchange)
-  float* h_out;                // tagged exchange: [B][D] plain copy of the final hidden state (d.h then holds tagged words)
-  bf16 *xh_out, *xl_out;       // sk_attention<.., SPLIT_OUT>: the attention output as bf16 high / low halves in
+  unsigned* done;              // [grid] per-workgroup "my greedy candidate is stored" epochs (never cleared: epochs only grow)
+  int* err;                    // set to 1 if a wait between workgroups gives up
+  int* tagstate;               // [B][8]: tags of the latest writes to the h, qkv, attn and z vectors of each slot, [4] = epoch of the
+                               //         latest launch's final reduction
+  float* h_out;                // [B][D] plain copy of the final hidden state (d.h holds tagged words)
+  float* part;                 // [B][Hq][SK_QSPLIT_MAX][hd + 4] tagged partial attention results of key splits 1.. (o[hd], max, sum)
+  bf16 *xh_out, *xl_out;       // sk_attention<.., SPLIT_OUT> (batched path): the attention output as bf16 high / low halves in
   int out_slot;                //   A-operand order (bg_aidx) for slot out_slot, instead of fp32 in d.attn
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
 };
@@ -226,186 +227,6 @@ __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int
   s.mb = base; base += SK_WAVES * (hd + 2);
   s.flag = reinterpret_cast<int*>(base);
   return s;
-}
-
-// Arrive-and-wait over all workgroups without read-modify-write traffic, executed by ONE
-// wave (the service wave, which never has weight loads in flight: loads return in order, so
-// a poll issued behind a prefetch queue would wait for all of it).  Workgroup c stores the
-// barrier's epoch into flags[c]; the wave polls all flags until none is older.  The wave has
-// already waited for its own stores and exchanged data is accessed coherently, so no cache
-// maintenance is needed.  The poll is bounded: returns 0 if it gives up or sees another
-// workgroup's give-up flag, so that every wave of the grid still exits.
-__device__ __forceinline__ int grid_sync_wave(unsigned* flags, int* err, unsigned epoch, int cu, int ncu) {
-  const int lane = threadIdx.x & 63;
-  if (lane == 0) __hip_atomic_store(flags + cu, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (ncu > 256) {                                   // generic path: one poll at a time
-    unsigned spins = 0;
-    for (;;) {
-      bool ok = true;
-      for (int base = 0; base < ncu; base += 256) {
-        unsigned f[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) coh_issue4(f[i], flags + min(base + i * 64 + lane, ncu - 1));
-        coh_wait();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { coh_use(f[i]); ok = ok && (f[i] >= epoch); }
-      }
-      if (__all(ok)) return 1;
-      if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return 0;
-      }
-    }
-  }
-  // Up to 256 workgroups: four polls (4 loads per lane each) are kept in flight, so the flags
-  // are sampled several times per memory round trip instead of once.  The wave has nothing
-  // else outstanding (vmcnt(0) first), so the explicit counts below are exact.
-  const unsigned* f0 = flags + min(lane, ncu - 1);
-  const unsigned* f1 = flags + min(64 + lane, ncu - 1);
-  const unsigned* f2 = flags + min(128 + lane, ncu - 1);
-  const unsigned* f3 = flags + min(192 + lane, ncu - 1);
-  coh_wait();
-  unsigned spins = 0;
-  for (;;) {
-    // (all four polls are requested and consumed inside one iteration: a requested value must
-    // not be carried across the loop edge, where the compiler may copy it before it lands)
-    unsigned a[4][4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      coh_issue4(a[q][0], f0); coh_issue4(a[q][1], f1); coh_issue4(a[q][2], f2); coh_issue4(a[q][3], f3);
-      if (q < 3) __builtin_amdgcn_s_sleep(12);       // spread the polls over about one round trip
-    }
-    bool done = false;
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-    coh_use(a[0][0]); coh_use(a[0][1]); coh_use(a[0][2]); coh_use(a[0][3]);
-    done = done || __all(a[0][0] >= epoch && a[0][1] >= epoch && a[0][2] >= epoch && a[0][3] >= epoch);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    coh_use(a[1][0]); coh_use(a[1][1]); coh_use(a[1][2]); coh_use(a[1][3]);
-    done = done || __all(a[1][0] >= epoch && a[1][1] >= epoch && a[1][2] >= epoch && a[1][3] >= epoch);
-    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    coh_use(a[2][0]); coh_use(a[2][1]); coh_use(a[2][2]); coh_use(a[2][3]);
-    done = done || __all(a[2][0] >= epoch && a[2][1] >= epoch && a[2][2] >= epoch && a[2][3] >= epoch);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    coh_use(a[3][0]); coh_use(a[3][1]); coh_use(a[3][2]); coh_use(a[3][3]);
-    done = done || __all(a[3][0] >= epoch && a[3][1] >= epoch && a[3][2] >= epoch && a[3][3] >= epoch);
-    if (done) return 1;
-    if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-      __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return 0;
-    }
-  }
-}
-
-// Two-level variant.  All workgroups polling all flags makes a few cache lines very hot, and
-// that queueing dominates the barrier's latency.  Instead: workgroups on the same XCD (they
-// share an L2, where read-modify-write operations execute) count arrivals in a per-XCD
-// counter; the last arriver of an XCD publishes the epoch in that XCD's device-scope flag;
-// every workgroup then polls only those few flags (one cache line each).
-//
-// Layout behind the per-workgroup flags (at flags + sk_bar_x(ncu)), 32-dword stride per XCD:
-//   [0, 16*32): workgroups per XCD, counted at kernel start;  [16*32, 32*32): arrival counters;
-//   [32*32, 48*32): published epochs.  All zero at launch.
-constexpr int SK_XCD_SLOTS = 16, SK_XCD_STRIDE = 32;
-__host__ __device__ inline int sk_bar_x(int ncu) { return (ncu + 31) / 32 * 32; }
-__host__ __device__ inline int sk_bar_words(int ncu) { return sk_bar_x(ncu) + 3 * SK_XCD_SLOTS * SK_XCD_STRIDE; }
-
-__device__ __forceinline__ unsigned sk_xcc_id() {
-  unsigned v;
-  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
-  return v & (SK_XCD_SLOTS - 1);
-}
-// Fetch-and-add executed in this XCD's L2; waits for the old value (and for every older
-// memory operation of the wave).
-__device__ __forceinline__ unsigned sk_l2_add_ret(unsigned* ptr, unsigned v) {
-  unsigned r;
-  asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(r) : "v"(ptr), "v"(v) : "memory");
-  return r;
-}
-
-struct SkBar {
-  unsigned* flags;     // [ncu] per-workgroup epochs (flat barrier)
-  unsigned* xbase;     // per-XCD words (see layout above)
-  int* err;
-  unsigned x;          // this workgroup's XCD
-  unsigned my_n;       // workgroups on this XCD
-  unsigned n_lane;     // lane l < SK_XCD_SLOTS: workgroups on XCD l
-  int two_level;
-};
-
-// Executed by the service wave before the first barrier: count this workgroup on its XCD.
-__device__ __forceinline__ void sk_bar_init(SkBar& B, unsigned* bar, int* err, int ncu, int two_level) {
-  B.flags = bar; B.xbase = bar + sk_bar_x(ncu); B.err = err; B.two_level = two_level;
-  B.x = sk_xcc_id(); B.my_n = 0; B.n_lane = 0;
-  if (two_level && (threadIdx.x & 63) == 0) {
-    const unsigned old = __hip_atomic_fetch_add(B.xbase + B.x * SK_XCD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("" :: "v"(old));                  // the add has completed before the first arrival is published
-  }
-}
-
-__device__ __forceinline__ void grid_arrive(SkBar& B, unsigned& old);
-__device__ __forceinline__ int grid_wait(SkBar& B, unsigned epoch, unsigned& old);
-
-__device__ __forceinline__ int grid_sync(SkBar& B, unsigned epoch, int cu, int ncu) {
-  const int lane = threadIdx.x & 63;
-  if (!B.two_level || epoch == 1) {
-    const int ok = grid_sync_wave(B.flags, B.err, epoch, cu, ncu);
-    if (B.two_level) {                             // every workgroup has been counted: read the census
-      B.n_lane = ld_coh(B.xbase + (lane & (SK_XCD_SLOTS - 1)) * SK_XCD_STRIDE);
-      B.my_n = __builtin_amdgcn_readlane(B.n_lane, B.x);
-    }
-    return ok;
-  }
-  unsigned old = 0;
-  grid_arrive(B, old);
-  return grid_wait(B, epoch, old);
-}
-
-// The two halves of the two-level barrier (epoch > 1).  grid_arrive only requests the count
-// of this workgroup's arrival; `old` is defined after grid_wait has waited for it.  Stores
-// issued between the two travel concurrently with the arrival (useful only when readers can
-// tell on their own whether what they read is current, as with tagged words).
-__device__ __forceinline__ void grid_arrive(SkBar& B, unsigned& old) {
-  unsigned* cnt = B.xbase + (SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
-  // Only lane 0 adds, selected inside the statement: for the compiler every lane's `old` is
-  // defined here, so it has no reason to copy the register before the value has landed.
-  unsigned long long exec_save;
-  asm volatile("s_mov_b64 %1, exec\n\ts_mov_b64 exec, 1\n\tglobal_atomic_add %0, %2, %3, off sc0\n\ts_mov_b64 exec, %1"
-               : "=v"(old), "=&s"(exec_save) : "v"(cnt), "v"(1u) : "memory");
-}
-
-__device__ __forceinline__ int grid_wait(SkBar& B, unsigned epoch, unsigned& old) {
-  const int lane = threadIdx.x & 63;
-  const unsigned k = epoch - 1;
-  unsigned* pub = B.xbase + (2 * SK_XCD_SLOTS + B.x) * SK_XCD_STRIDE;
-  coh_wait();
-  coh_use(old);
-  if (lane == 0 && old + 1u == B.my_n * k) __hip_atomic_store(pub, k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const unsigned* f = B.xbase + (2 * SK_XCD_SLOTS + (lane & (SK_XCD_SLOTS - 1))) * SK_XCD_STRIDE;
-  const bool need = B.n_lane != 0;
-  coh_wait();
-  unsigned spins = 0;
-  for (;;) {
-    unsigned a[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      coh_issue4(a[q], f);
-      if (q < 3) __builtin_amdgcn_s_sleep(8);
-    }
-    bool done = false;
-    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-    coh_use(a[0]); done = done || __all(!need || a[0] >= k);
-    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    coh_use(a[1]); done = done || __all(!need || a[1] >= k);
-    asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-    coh_use(a[2]); done = done || __all(!need || a[2] >= k);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    coh_use(a[3]); done = done || __all(!need || a[3] >= k);
-    if (done) return 1;
-    if (++spins > SK_SPIN_LIMIT || __hip_atomic_load(B.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-      __hip_atomic_store(B.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return 0;
-    }
-  }
 }
 
 // A staged vector of K elements occupies K rounded up to whole 2048-element segments: the
@@ -632,9 +453,8 @@ struct SegDesc {
   bf16* kv;                     // KV pool of the layer (attention precedes SEG_O)
 };
 
-// Rows of a phase are dealt out in proportion to per-XCD shares (1024 = an equal share): w0 and
-// w1 are the cumulative shares before this workgroup and before the next one, out of
-// 1024 * ncu.  Equal shares give the even split n * cu / ncu.
+// Rows of a phase are dealt out evenly over ncu workgroups: w0 and w1 are 1024 x (this workgroup's rank, rank + 1) among
+// them (w0 = w1: no rows), which gives rows [n * rank / ncu, n * (rank + 1) / ncu).
 struct SkShare { int w0, w1, ncu; };
 
 __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, const SkShare& sh, int pair) {
@@ -659,7 +479,8 @@ __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   return d;
 }
 
-__device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh) {
+// sh: this workgroup's share of the rows of every phase but the output projection, whose rows are dealt by sh_o (see k_step).
+__device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh, const SkShare& sh_o) {
   const DecParams& p = P.d;
   const int nq = p.Hq * p.hd, nkv = p.Hkv * p.hd;
   SegDesc d{};
@@ -680,7 +501,7 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
       break;
     case SEG_O:
       d.m0 = lw.wo; d.n0 = p.D;
-      seg_split(d, p.D, nq, sh, 1);
+      seg_split(d, p.D, nq, sh_o, 1);
       break;
     case SEG_GU:
       d.m0 = lw.wg; d.m1 = lw.wu; d.inter = 1; d.gain = lw.g_mlp;
@@ -696,8 +517,8 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
 
 // Descriptor of segment s for this workgroup, every field in scalar registers.  Recomputed
 // where needed rather than carried through the segment loop.
-__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh) {
-  return seg_uniform(seg_desc_raw(P, s, nk, kept, sh));
+__device__ __forceinline__ SegDesc seg_desc(const StepParams& P, int s, int nk, const int* kept, const SkShare& sh, const SkShare& sh_o) {
+  return seg_uniform(seg_desc_raw(P, s, nk, kept, sh, sh_o));
 }
 
 // Address of row r of a segment.  All inputs are wave-uniform, so the cases are scalar
@@ -797,14 +618,13 @@ __device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg,
 // ---------------------------------------------------------------------------------------
 // Attention of workgroup (KV head g, split s): the waves = G query heads x (SK_WAVES/G) key groups,
 // lane = key for the scores, lane = (key subgroup, 8-dim chunk) for the weighted values.
-// NW = number of worker waves of the workgroup (the persistent kernel's streaming waves; the
-// stand-alone attention kernel of the batched path runs a full set of SK_WAVES workers).
-// EXT: the queries and the new key / value are already in LDS (sk_attn_prologue_tagged, run by
-// the service wave); the function returns false if that wave reported failure.  out_tag >= 0:
-// the attention output is written as tagged words.
-template <int HD, int NW = SK_SWAVES, bool EXT = false, bool SPLIT_OUT = false>
+// NW = number of worker waves of the workgroup.
+// This is the attention kernel body of the batched path's k_attn_tiles_b (the persistent kernel has its own, by query head).
+template <int HD, int NW, bool SPLIT_OUT>
 __device__ __forceinline__ bool sk_attention(const StepParams& P, bf16* pool, const SkLds& S, int g, int s, int nsplit,
-                                             unsigned long long* stamps, int out_tag = -1) {
+                                             unsigned long long* stamps) {
+  constexpr bool EXT = false;
+  constexpr int out_tag = -1;
   const DecParams& p = P.d;
 #define SK_ASTAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
   SK_ASTAMP(6);
@@ -1098,107 +918,409 @@ __device__ __forceinline__ bool sk_attention(const StepParams& P, bf16* pool, co
   return true;
 }
 
-// Tagged exchange: the service wave fetches this step's q (G heads), k and v of KV head g as
-// soon as they carry tag `bit`, rotates them and leaves them in LDS for sk_attention<.., EXT>;
-// the workgroup that owns the new position also appends k and v to the cache.  The service
-// wave has no other loads in flight, so its polls are not queued behind the key tiles the
-// worker waves have already requested.  Returns false if the wait gives up.
+// ---------------------------------------------------------------------------------------
+// Attention inside the persistent kernel.  Workgroup (query head H, key split s): its seven streaming waves take one
+// 64-key tile each (more in turn when the context is long), lane = (key subgroup, 8-dim chunk); keys AND values of a
+// tile are requested together, before the queries are known, so a tile costs one memory round trip.  The service wave
+// fetches q of head H and k, v of its KV head as soon as they are current, rotates them, appends the new k / v to the
+// cache (one of the G workgroups that share the KV head does) and afterwards folds the seven waves' partial results.
+// Key split 0 of a head then collects the other splits' partial results, which arrive as tagged words like every other
+// exchanged vector, and writes the head's attention output; there is no counter and no "last arriver".
+// The G query heads of a KV head sit on workgroups of the same XCD (workgroup index mod Hkv), so the tiles they
+// share are fetched from memory once and served to the others by that XCD's L2.
+struct SkAttnGeo {
+  int H, g, s, nsplit;          // query head, its KV head, this workgroup's key split, splits per head
+  int pos, tiles, t_first, t_last;
+  int nact;                     // streaming waves of the workgroup that take tiles (the others keep their weight ring in flight)
+  bool owns_new;                // the tile that holds the new position belongs to this split
+  bool appends;                 // ... and this workgroup is the one of its KV head that writes the new k / v to the cache
+};
+
+// Key splits per query head for a context of `tiles` 64-key tiles on a grid of ncu workgroups: as many as the grid
+// allows, so that a workgroup has few tiles and each of them a wave (and a SIMD) of its own - a tile is a few thousand
+// ALU cycles of one wave.  tps = tiles per split.
+__device__ __forceinline__ int sk_attn_splits(int tiles, int ncu, int Hq, int& tps) {
+#ifdef SK_DBG_NSPLIT1
+  const int smax = 1;
+#else
+  const int smax = max(1, min(SK_QSPLIT_MAX, ncu / Hq));
+#endif
+  tps = (tiles + smax - 1) / smax;
+  return (tiles + tps - 1) / tps;
+}
+
+__device__ __forceinline__ SkAttnGeo sk_attn_geo(const DecParams& p, int cu, int nsplit, int tps, int pos) {
+  SkAttnGeo a;
+  a.g = cu % p.Hkv;
+  const int j = cu / p.Hkv, hl = j % p.G;
+  a.s = j / p.G;
+  a.H = a.g * p.G + hl;
+  a.nsplit = nsplit; a.pos = pos;
+  a.tiles = (pos + 64) >> 6;
+  a.t_first = a.s * tps; a.t_last = min(a.tiles, a.t_first + tps);
+  a.nact = min(tps, SK_SWAVES);
+  a.owns_new = (pos >> 6) >= a.t_first && (pos >> 6) < a.t_last;
+  a.appends = a.owns_new && hl == 0;
+  return a;
+}
+
+__host__ __device__ __forceinline__ size_t sk_part_index(int Hq, int hd, int b, int H, int s) {
+  return (((size_t)b * Hq + H) * SK_QSPLIT_MAX + s) * (size_t)(hd + 4);
+}
+
+// Service wave: q of head H and k, v of KV head g into LDS as soon as they carry tag `bit` (rotated; q pre-scaled; k, v
+// rounded to the cache type, the values attention uses for the new position).  Returns false if the wait gives up.
 template <int HD>
-__device__ __forceinline__ bool sk_attn_prologue_tagged(const StepParams& P, bf16* pool, const SkLds& S, int g, int s,
-                                                        int nsplit, unsigned bit) {
+__device__ __forceinline__ bool sk_attn_prologue_head(const StepParams& P, bf16* pool, const SkLds& S, const SkAttnGeo& A, unsigned bit) {
   const DecParams& p = P.d;
-  constexpr int HALF = HD / 2;
-  constexpr int NQ = (SK_SWAVES * HALF + 63) / 64;      // q pairs per lane (up to SK_SWAVES query heads per KV head)
-  constexpr int NV = (HD + 63) / 64;
-  const int b = p.b, G = p.G, Pg = p.P, lane = sk_lane_opaque();
-  const int pos = uni(p.len[b]), nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
-  const int tps = (tiles + nsplit - 1) / nsplit;
-  const int t_first = s * tps, t_last = min(tiles, t_first + tps);
-  const bool owns_new = (pos >> 6) >= t_first && (pos >> 6) < t_last;
+  constexpr int HALF = HD / 2, NV = HD / 64;
+  const int b = p.b, Pg = p.P, lane = sk_lane_opaque();
   const int nq = p.Hq * HD, nkv = p.Hkv * HD;
   const float* qkv = p.qkv + (size_t)b * (nq + 2 * nkv);
-  float q1[NQ], q2[NQ], k1, k2, vv[NV];
-  const int dk = min(lane, HALF - 1);
+  const int dp = min(lane, HALF - 1);               // (HD = 64: lanes 32.. repeat the last pair)
+  float q1, q2, k1, k2, vv[NV];
   unsigned spins = 0;
   for (;;) {
     int e = 0;
+    coh_issue4(q1, qkv + A.H * HD + dp);
+    coh_issue4(q2, qkv + A.H * HD + dp + HALF);
+    coh_issue4(k1, qkv + nq + A.g * HD + dp);
+    coh_issue4(k2, qkv + nq + A.g * HD + dp + HALF);
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-      const int iq = min(j * 64 + lane, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
-      coh_issue4(q1[j], qkv + (g * G + hh) * HD + dq);
-      coh_issue4(q2[j], qkv + (g * G + hh) * HD + dq + HALF);
-    }
-    coh_issue4(k1, qkv + nq + g * HD + dk);
-    coh_issue4(k2, qkv + nq + g * HD + dk + HALF);
-#pragma unroll
-    for (int j = 0; j < NV; ++j) coh_issue4(vv[j], qkv + nq + nkv + g * HD + min(j * 64 + lane, HD - 1));
+    for (int j = 0; j < NV; ++j) coh_issue4(vv[j], qkv + nq + nkv + A.g * HD + j * 64 + lane);
     coh_issue4(e, P.err);
     coh_wait();
-    coh_use(e); coh_use(k1); coh_use(k2);
+    coh_use(e); coh_use(q1); coh_use(q2); coh_use(k1); coh_use(k2);
     SkTags t;
-    t.add(k1); t.add(k2);
-#pragma unroll
-    for (int j = 0; j < NQ; ++j) { coh_use(q1[j]); coh_use(q2[j]); t.add(q1[j]); t.add(q2[j]); }
+    t.add(q1); t.add(q2); t.add(k1); t.add(k2);
 #pragma unroll
     for (int j = 0; j < NV; ++j) { coh_use(vv[j]); t.add(vv[j]); }
     if (__all(t.good(bit))) break;
     if (sk_poll_give_up(spins, uni(e), P.err)) return false;
   }
-#pragma unroll
-  for (int j = 0; j < NQ; ++j) {
-    const int iq = j * 64 + lane, hh = iq / HALF, dq = iq - hh * HALF;
-    if (iq < G * HALF) {                              // rotate and pre-scale the queries
-      const float2 c = S.cs[dq];
-      const float a = sk_untag(q1[j]), bq = sk_untag(q2[j]);
-      S.qs[hh * HD + dq] = (a * c.x - bq * c.y) * p.qscale;
-      S.qs[hh * HD + dq + HALF] = (bq * c.x + a * c.y) * p.qscale;
-    }
+  const float2 c = S.cs[dp];
+  if (lane < HALF) {
+    const float a = sk_untag(q1), bq = sk_untag(q2);
+    S.qs[lane] = (a * c.x - bq * c.y) * p.qscale;
+    S.qs[lane + HALF] = (bq * c.x + a * c.y) * p.qscale;
   }
-  if (owns_new) {                                     // append the new key / value; keep the stored values in LDS
+  if (A.owns_new) {
     const int* pt = p.page_table + (size_t)b * p.max_pages;
-    const size_t head_off = (size_t)g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
-    const size_t base = (size_t)pt[pos / Pg] * p.page_elems + head_off + (size_t)(pos % Pg) * HD;
+    const size_t head_off = (size_t)A.g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
+    const size_t base = (size_t)pt[A.pos / Pg] * p.page_elems + head_off + (size_t)(A.pos % Pg) * HD;
     if (lane < HALF) {
-      const float2 c = S.cs[dk];
       const float a = sk_untag(k1), bk = sk_untag(k2);
       const bf16 r1 = from_f32<bf16>(a * c.x - bk * c.y), r2 = from_f32<bf16>(bk * c.x + a * c.y);
-      stg_bf16(pool + base + dk, r1); stg_bf16(pool + base + dk + HALF, r2);
-      S.knew[dk] = to_f32(r1); S.knew[dk + HALF] = to_f32(r2);
+      if (A.appends) { stg_bf16(pool + base + lane, r1); stg_bf16(pool + base + lane + HALF, r2); }
+      S.knew[lane] = to_f32(r1); S.knew[lane + HALF] = to_f32(r2);
     }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int dv = j * 64 + lane;
-      if (dv < HD) {
-        const bf16 r = from_f32<bf16>(sk_untag(vv[j]));
-        stg_bf16(pool + base + v_off + dv, r);
-        S.vnew[dv] = to_f32(r);
-      }
+      const bf16 r = from_f32<bf16>(sk_untag(vv[j]));
+      if (A.appends) stg_bf16(pool + base + v_off + dv, r);
+      S.vnew[dv] = to_f32(r);
     }
   }
   return true;
 }
 
-// The service wave's part of the attention phase: it only keeps step with the workgroup
-// barriers of sk_attention.
-__device__ __forceinline__ void sk_attention_service() {
+// Sum over the LPR (8 or 16) lanes that share a key row, through the DPP cross-lane paths; every lane of the group
+// ends up with the group's sum.
+template <int LPR>
+__device__ __forceinline__ float sk_keyrow_sum(float v) {
+  v = dpp_add<0xB1, 0xf>(v);     // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xf>(v);     // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xf>(v);    // row_half_mirror: 8 lanes
+  if (LPR == 16) v = dpp_add<0x140, 0xf>(v);    // row_mirror: 16 lanes
+  return v;
+}
+
+// Streaming waves of an attention workgroup.  Contains two workgroup barriers: after the first the queries are in LDS
+// (returns false if the service wave reported a failed wait), before the second this wave's partial result
+// (o[HD], max, sum) is in S.mb[wave].  Called by waves 0..nact-1 only: the others have no tiles, keep their weight ring in
+// flight instead and only take part in the two barriers (sk_attention_idle).
+template <int HD>
+__device__ __forceinline__ bool sk_attention_head(const StepParams& P, const bf16* pool, const SkLds& S, const SkAttnGeo& A,
+                                                  unsigned long long* stamps) {
+  const DecParams& p = P.d;
+#define SK_ASTAMP(slot) do { if (stamps && threadIdx.x == 0) stamps[slot] = wall_clock64(); } while (0)
+  SK_ASTAMP(6);
+  constexpr int LPR = HD / 8, RPI = 64 / LPR;       // lanes per key row, key rows per load instruction
+  constexpr int NKL = HD / 8;                       // 16-byte loads per lane and tile (keys; as many again for the values)
+  constexpr int PPT = 4;                            // 16-token pages per tile
+  const int Pg = p.P;
+  const int wave = uni((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
+  const int pos = A.pos, nkeys = pos + 1;
+  const int* pt = p.page_table + (size_t)p.b * p.max_pages;
+  const size_t head_off = (size_t)A.g * Pg * HD, v_off = (size_t)p.Hkv * Pg * HD;
+  const int sub = lane / LPR, dc = lane % LPR;
+
+  // One 64-key tile: load i of lane (sub, dc) holds dims dc*8 .. dc*8+7 of key t0 + RPI*i + sub, keys and values alike,
+  // so every load instruction reads whole rows and a lane ends up with the weights of exactly the keys whose values it
+  // holds.  A tile is four whole pages; pages past the sequence's last one are clamped to it (in bounds; weight 0).
+  // The loads are buffer loads the compiler knows as loads (one descriptor per page): it keeps them in flight across
+  // the barrier and the control flow below and waits for each register where it is first read.  (Loads issued through
+  // inline asm are only safe in straight-line code: at a branch the compiler may move a "value" it believes to be
+  // there to another register before the load has landed.)
+  u32x4_t kk[NKL], vv[NKL];
+  __amdgpu_buffer_rsrc_t prs[PPT];
+  const int page_bytes = (int)(p.page_elems * 2);
+  const int lane_off = (int)(head_off * 2) + (sub * HD + dc * 8) * 2;
+  auto tile_pages = [&](int t) {
+    const int last_page = pos / Pg;
+    int pg[PPT];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j) pg[j] = pt[min(t * PPT + j, last_page)];
+#pragma unroll
+    for (int j = 0; j < PPT; ++j)
+      prs[j] = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(uni(pool + (size_t)uni(pg[j]) * p.page_elems)), (short)0, page_bytes, 0x00020000);
+  };
+  auto request = [&]() {
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      const int kin = RPI * i;
+      kk[i] = __builtin_amdgcn_raw_buffer_load_b128(prs[kin / 16], lane_off + (kin % 16) * HD * 2, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      const int kin = RPI * i;
+      vv[i] = __builtin_amdgcn_raw_buffer_load_b128(prs[kin / 16], lane_off + (kin % 16) * HD * 2, (int)(v_off * 2), 0);
+    }
+  };
+  auto unpack = [](const u32x4_t w, float (&v)[8]) {
+    v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+    v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+    v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+    v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+  };
+  float m = -INFINITY, l = 0.f, o[8], qv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = 0.f;
+  // One tile whose loads are in flight.  EDGE: the sequence's last tile, which holds the slot of the new position (its
+  // key and value are taken from LDS afterwards: the cache write may not have landed) and possibly slots beyond it
+  // (never written): all of those get weight 0 and their contents never enter a sum (no NaN patterns).
+  // live = false: a wave beyond the split's last tile fetched an existing tile and ignores it.
+  auto tile = [&](int t, bool live, auto edge_tag) {
+    constexpr bool EDGE = decltype(edge_tag)::value;
+    const int t0 = t << 6;
+    float sc[NKL];
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      float kf[8];
+      unpack(kk[i], kf);
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d = fmaf(kf[e], qv[e], d);
+      sc[i] = d;
+    }
+    float mt = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      sc[i] = sk_keyrow_sum<LPR>(sc[i]);
+      if (EDGE && t0 + RPI * i + sub >= pos) sc[i] = -INFINITY;
+      mt = fmaxf(mt, sc[i]);
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off, 64));
+    // (an edge tile may hold no stored key at all: then nothing changes)
+    const bool any = live && mt > -INFINITY;
+    const float mn = any ? fmaxf(m, mt) : m;
+    const float corr = any ? expf(m - mn) : 1.f;
+    float ls = 0.f;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      sc[i] = (any && (!EDGE || t0 + RPI * i + sub < pos)) ? expf(sc[i] - mn) : 0.f;     // sc now holds the weights
+      ls += sc[i];
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) ls += __shfl_xor(ls, off, 64);
+    l = l * corr + ls;
+    m = mn;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= corr;
+#pragma unroll
+    for (int i = 0; i < NKL; ++i) {
+      float vf[8];
+      unpack(vv[i], vf);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float v = (EDGE && t0 + RPI * i + sub >= pos) ? 0.f : vf[e];
+        o[e] = fmaf(sc[i], v, o[e]);
+      }
+    }
+    if (EDGE && live) {
+      // the new position: key and value as stored (rounded to the cache type), from LDS; one more key of this wave
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d = fmaf(S.knew[dc * 8 + e], qv[e], d);
+      d = sk_keyrow_sum<LPR>(d);
+      const float mn2 = fmaxf(m, d);
+      const float c2 = expf(m - mn2), w = expf(d - mn2);      // (m = -inf: c2 = 0)
+      l = l * c2 + w;
+      m = mn2;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = fmaf(sub == 0 ? w : 0.f, S.vnew[dc * 8 + e], o[e] * c2);   // (the subgroups are summed below: once)
+    }
+  };
+  auto tile_any = [&](int t, bool live) {
+    if (t == (pos >> 6)) tile(t, live, std::true_type{});
+    else tile(t, live, std::false_type{});
+  };
+
+  int t = A.t_first + wave;
+  const bool live0 = t < A.t_last;
+  const int tfirst = live0 ? t : A.t_first;
+  tile_pages(tfirst);
+  request();
+  lds_barrier();                                   // q, new k / v and the verdict of the service wave's wait are in LDS
+  SK_ASTAMP(7);
+  if (uni(*S.flag) == 0) return false;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) qv[e] = S.qs[dc * 8 + e];     // this lane's 8 dims of the head's query
+  tile_any(tfirst, live0);
+  for (t += SK_SWAVES; t < A.t_last; t += SK_SWAVES) {
+    tile_pages(t);
+    request();
+    tile_any(t, true);
+  }
+  SK_ASTAMP(8);
+  // fold the key subgroups: afterwards lanes 0..LPR-1 hold dims lane*8 .. lane*8+7
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] += __shfl_xor(o[e], off, 64);
+  float* mb = S.mb + wave * (HD + 2);
+  if (lane < LPR) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mb[lane * 8 + e] = o[e];
+  }
+  if (lane == 0) { mb[HD] = m; mb[HD + 1] = l; }
+  lds_barrier();                                   // the service wave folds the waves' results
+#undef SK_ASTAMP
+  return true;
+}
+
+// A streaming wave without tiles: keeps step with the two barriers of sk_attention_head.
+__device__ __forceinline__ bool sk_attention_idle(const SkLds& S) {
   lds_barrier();
-  lds_barrier();
-  lds_barrier();
-  lds_barrier();
+  const bool ok = uni(*S.flag) != 0;
+  if (ok) lds_barrier();
+  return ok;
+}
+
+// Service wave, after the second barrier: folds the streaming waves' results in wave order; a split other than 0 leaves
+// its result as tagged words for split 0, which waits for them (tag `bit`), folds them in split order and writes the
+// head's attention output as tagged words.  Returns false if that wait gives up.
+template <int HD>
+__device__ __forceinline__ bool sk_attn_merge_head(const StepParams& P, const SkLds& S, const SkAttnGeo& A, unsigned bit,
+                                                   unsigned long long* stamps) {
+  const DecParams& p = P.d;
+  constexpr int NV = HD / 64;
+  const int lane = sk_lane_opaque();
+  float M = -INFINITY;
+  for (int w = 0; w < A.nact; ++w) M = fmaxf(M, S.mb[w * (HD + 2) + HD]);
+  float den = 0.f, a[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) a[j] = 0.f;
+  for (int w = 0; w < A.nact; ++w) {
+    const float* src = S.mb + w * (HD + 2);
+    const float lt = src[HD + 1];
+    if (lt > 0.f) {
+      const float wg = expf(src[HD] - M);
+      den = fmaf(lt, wg, den);
+#pragma unroll
+      for (int j = 0; j < NV; ++j) a[j] = fmaf(src[j * 64 + lane], wg, a[j]);
+    }
+  }
+#ifdef SK_DBG_DUMP
+  if (P.tdbg) {
+    float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS) + 8192 + blockIdx.x * (HD + 4);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) dbg[j * 64 + lane] = a[j];
+    if (lane == 0) { dbg[HD] = M; dbg[HD + 1] = den; }
+  }
+#endif
+  if (stamps && lane == 0) stamps[9] = wall_clock64();
+  if (A.s != 0) {
+    float* dst = P.part + sk_part_index(p.Hq, HD, p.b, A.H, A.s);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) st_coh(dst + j * 64 + lane, sk_tagged(a[j], bit));
+    if (lane < 2) st_coh(dst + HD + lane, sk_tagged(lane == 0 ? M : den, bit));
+    return true;
+  }
+  if (A.nsplit > 1) {
+    float po[SK_QSPLIT_MAX - 1][NV], pm[SK_QSPLIT_MAX - 1], pl[SK_QSPLIT_MAX - 1];
+    unsigned spins = 0;
+    for (;;) {
+      int e = 0;
+#pragma unroll
+      for (int q = 0; q < SK_QSPLIT_MAX - 1; ++q) {
+        const float* src = P.part + sk_part_index(p.Hq, HD, p.b, A.H, min(q + 1, A.nsplit - 1));
+#pragma unroll
+        for (int j = 0; j < NV; ++j) coh_issue4(po[q][j], src + j * 64 + lane);
+        coh_issue4(pm[q], src + HD);
+        coh_issue4(pl[q], src + HD + 1);
+      }
+      coh_issue4(e, P.err);
+      coh_wait();
+      coh_use(e);
+      SkTags t;
+#pragma unroll
+      for (int q = 0; q < SK_QSPLIT_MAX - 1; ++q) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) { coh_use(po[q][j]); t.add(po[q][j]); }
+        coh_use(pm[q]); coh_use(pl[q]);
+        t.add(pm[q]); t.add(pl[q]);
+      }
+      if (__all(t.good(bit))) break;
+      if (sk_poll_give_up(spins, uni(e), P.err)) return false;
+    }
+    if (stamps && lane == 0) stamps[10] = wall_clock64();
+    float M2 = M;
+#pragma unroll
+    for (int q = 0; q < SK_QSPLIT_MAX - 1; ++q) {
+      pm[q] = sk_untag(pm[q]); pl[q] = sk_untag(pl[q]);       // (untagging restores an infinite maximum exactly)
+      if (q + 1 < A.nsplit && pl[q] > 0.f) M2 = fmaxf(M2, pm[q]);
+    }
+    const float f0 = den > 0.f ? expf(M - M2) : 0.f;
+    den *= f0;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) a[j] *= f0;
+#pragma unroll
+    for (int q = 0; q < SK_QSPLIT_MAX - 1; ++q) {
+      if (q + 1 < A.nsplit && pl[q] > 0.f) {
+        const float wg = expf(pm[q] - M2);
+        den = fmaf(pl[q], wg, den);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) a[j] = fmaf(sk_untag(po[q][j]), wg, a[j]);
+      }
+    }
+  }
+  float* out = p.attn + (size_t)p.b * p.Hq * HD + A.H * HD;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) st_coh(out + j * 64 + lane, sk_tagged(a[j] / den, bit));
+  if (stamps && lane == 0) stamps[11] = wall_clock64();
+  return true;
 }
 
 // ---------------------------------------------------------------------------------------
-// Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds
-// (32 KB) in flight that runs on across phase boundaries, so HBM stays busy while the
-// workgroups synchronise.  The last wave is the service wave: it turns the partial sums of a
-// finished phase into its outputs, takes part in the grid barrier and stages the next
-// phase's input vector into LDS.  It never has weight loads in flight, which matters because
-// a wave's loads return in order: a barrier poll or an input load issued behind a prefetch
-// queue would wait for all of it.
+// Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds (28 KB) in flight that runs
+// on across phase boundaries, so HBM stays busy while the workgroups hand their results on.  The last wave is the
+// service wave: it turns the partial sums of a finished phase into its outputs, waits for the next phase's input and
+// stages it into LDS.  It never has weight loads in flight, which matters because a wave's loads return in order: a
+// poll or an input load issued behind a prefetch queue would wait for all of it.
 //
-// TAG selects the tagged exchange (see above): no grid barrier between phases; the only grid
-// barrier left is the one before the final token reduction.
-template <int HD, bool TAG>
+// Who does what in the attention + output-projection phase.  With Hq x nsplit <= half the grid (short contexts) the
+// first Hq x nsplit workgroups compute attention and own NO rows of the output projection; the others own all of them,
+// request every round of their rows before attention starts and hold them in the ring, so when the attention output
+// arrives the projection is a pass over registers.  The attention workgroups have no weight loads in flight meanwhile
+// (their ring registers hold the key and value tiles) and go on to request the gate/up rows as soon as their part of
+// attention is done.  With long contexts every workgroup computes attention and the projection's rows are dealt evenly.
+//
+// The residual rows a workgroup updates in the output and down projections are fetched by its service wave right
+// after it has staged the phase before (QKV or gate/up), when it has seen every word of h current.
+template <int HD>
 __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   extern __shared__ __align__(16) float smem_f[];
   const DecParams& p = P.d;
@@ -1206,215 +1328,175 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const bool service = wave == SK_SWAVES;
   const int b = p.b, D = p.D, F = p.F, nq = p.Hq * HD, nkv = p.Hkv * HD;
   const SkLds S = sk_carve(smem_f, D, nq, F, p.G, HD);
-  unsigned epoch = 0;
-  // cumulative row shares of this workgroup: workgroups are dealt to the XCDs round-robin, so
-  // workgroup c sits on XCD c % 8 (checked by the kernel that updates the shares)
-  SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
-  if (P.shares != nullptr && (ncu & 7) == 0) {
-    int pre = 0, pre1 = 0, tot = 0;
-    for (int j = 0; j < 8; ++j) {
-      const int sj = uni(P.shares[j]);
-      if (j < (cu & 7)) pre += sj;
-      if (j <= (cu & 7)) pre1 += sj;
-      tot += sj;
-    }
-    if (tot == 8192) { share.w0 = (cu >> 3) * 8192 + pre; share.w1 = (cu >> 3) * 8192 + pre1; }
-  }
-  share.w0 = uni(share.w0); share.w1 = uni(share.w1);
-  SkBar bar;
-  const bool detect = TAG && P.tagged == 2;       // tagged words plus a grid barrier as the "ready" signal
-  if (service) sk_bar_init(bar, P.bar, P.err, ncu, TAG && !detect ? 0 : P.two_level);
   float* h = p.h + (size_t)b * D;
-  // tagged exchange: tags of the latest writes of h, qkv, attn and z (the same in every wave of
-  // the grid: each flips when the phase that writes the vector begins)
-  unsigned tag_h = 0, tag_q = 0, tag_a = 0, tag_z = 0;
-  if (TAG) {
-    const int* ts = P.tagstate + 4 * b;
+  // tags of the latest writes of h, qkv, attn (and the attention partials) and z: the same in every wave of the grid,
+  // each flips when the phase that writes the vector begins
+  unsigned tag_h, tag_q, tag_a, tag_z, epoch;
+  {
+    const int* ts = P.tagstate + 8 * b;
     tag_h = (unsigned)uni(ld_coh(ts)) & 1u; tag_q = (unsigned)uni(ld_coh(ts + 1)) & 1u;
     tag_a = (unsigned)uni(ld_coh(ts + 2)) & 1u; tag_z = (unsigned)uni(ld_coh(ts + 3)) & 1u;
+    epoch = (unsigned)uni(ld_coh(ts + 4)) + 1u;
   }
   const int nk = uni(P.n_kept[b]);
   const int* kept = P.kept + (size_t)b * P.L;
   const int pos = uni(p.len[b]);
-  const int nkeys = pos + 1, tiles = (nkeys + 63) >> 6;
-  // attention splits: enough workgroups that each wave sees about one 64-key tile
-  const int nkg = max(1, SK_SWAVES / p.G);
-  int nsplit = (tiles + nkg - 1) / nkg;
-  nsplit = max(1, min(nsplit, min(S_MAX, ncu / p.Hkv)));
+  // attention: workgroup = (query head, key split), one 64-key tile per streaming wave where the grid allows
+  const int tiles = (pos + 64) >> 6;
+  int tps;
+  const int nsplit = sk_attn_splits(tiles, ncu, p.Hq, tps);
+  const int n_attn = p.Hq * nsplit;
+  const bool attn_wg = cu < n_attn;
+  const SkAttnGeo A = sk_attn_geo(p, attn_wg ? cu : 0, nsplit, tps, pos);
+  // output projection: rows on the workgroups that have no attention work when those are at least half the grid and
+  // enough for one residual row per service-wave lane
+#ifdef SK_DBG_OFIRST0
+  const int o_first = 0;
+#else
+  const int o_first = (2 * n_attn <= ncu && (ncu - n_attn) * 64 >= D) ? n_attn : 0;
+#endif
+  const SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
+  const SkShare share_o{cu >= o_first ? (cu - o_first) * 1024 : 0, cu >= o_first ? (cu - o_first + 1) * 1024 : 0, ncu - o_first};
 
+#ifdef SK_DBG_DUMP
+#define SK_XSTAMP(i) do { if (P.tdbg && cu == 0 && lane == 0) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[s * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define SK_XSTAMP(i) do { } while (0)
+#endif
 #define SK_STAMP(slot)                                                                 \
   do {                                                                                 \
     if (P.tdbg && cu == 0 && tid == SK_SWAVES * 64) P.tdbg[s * SK_TSLOTS + (slot)] = wall_clock64(); \
   } while (0)
-  // grid barrier: service wave synchronises, then the workgroup barrier hands the verdict on
-#define SK_GRID_SYNC()                                                                 \
-  do {                                                                                 \
-    if (service) {                                                                     \
-      const int ok_ = grid_sync(bar, ++epoch, cu, ncu);                                \
-      if (lane == 0) *S.flag = ok_;                                                    \
-    }                                                                                  \
-  } while (0)
-  // timing aid: arrival / release of EVERY workgroup at the barrier that opens segment 7 (the first down projection)
-#define SK_GRID_SYNC_TRACED()                                                          \
-  do {                                                                                 \
-    if (service) {                                                                     \
-      unsigned long long* tb_ = (P.tdbg && s == 7) ? P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 2 * cu : nullptr; \
-      if (tb_ && lane == 0) tb_[0] = wall_clock64();                                   \
-      const int ok_ = grid_sync(bar, ++epoch, cu, ncu);                                \
-      if (tb_ && lane == 0) tb_[1] = wall_clock64();                                   \
-      if (lane == 0) *S.flag = ok_;                                                    \
-    }                                                                                  \
-  } while (0)
 
+#ifdef SK_DBG_DUMP
+  if (P.tdbg && cu == 0 && tid == 0) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[1000] = wall_clock64();
+#endif
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
-  float h_own = 0.f;                               // tagged exchange: service-wave lane r keeps residual row row0 + r of this workgroup
   {
     int tok = uni(p.tokens[b]);
     tok = min(max(tok, 0), p.V - 1);
     const bf16* row = reinterpret_cast<const bf16*>(p.embed) + (size_t)tok * D;
-    if (TAG) {
-      // the rows this workgroup owns in every phase that writes h (at most 64, checked on the host)
-      SegDesc e{};
-      seg_split(e, D, D, share, 1);
-      tag_h ^= 1u;
-      if (service && lane < e.nrows) {
-        h_own = sk_untag(to_f32(row[e.row0 + lane]));
-        st_coh(h + e.row0 + lane, sk_tagged(h_own, tag_h));
-      }
-    } else {
-      const int r0 = (int)((unsigned)(D * cu) / (unsigned)ncu), r1 = (int)((unsigned)(D * (cu + 1)) / (unsigned)ncu);
-      for (int k = r0 + tid; k < r1; k += SK_THREADS) st_coh(h + k, to_f32(row[k]));
+    SegDesc e{};
+    seg_split(e, D, D, share, 1);                  // the rows this workgroup owns in the phases that write h (at most 64, checked on the host)
+    tag_h ^= 1u;
+    if (service && lane < e.nrows) {
+      const float v = sk_untag(to_f32(row[e.row0 + lane]));
+      st_coh(h + e.row0 + lane, sk_tagged(v, tag_h));
+      if (P.h_out != nullptr) P.h_out[(size_t)b * D + e.row0 + lane] = v;
+    }
+    // a key split other than 0 leaves "not yet" (the tag of the write before) in its slot of the attention partials:
+    // the slot may never have been used, or not since the context was shorter, and then carries the tag of some older write
+    if (service && attn_wg && A.s != 0) {
+      float* dst = P.part + sk_part_index(p.Hq, HD, b, A.H, A.s);
+      for (int i = lane; i < HD + 2; i += 64) st_coh(dst + i, sk_tagged(0.f, tag_a));
+      vm_wait_all();
     }
     for (int i = tid; i < HD / 2; i += SK_THREADS) {
       const double a = (double)pos * p.theta[i];
       S.cs[i] = make_float2((float)cos(a), (float)sin(a));
     }
   }
-  if (!TAG) vm_wait_all();                         // this wave's h rows are out
 
   const int nsegs = 4 * nk + 1;
-  const bool attn_wg = cu < p.Hkv * nsplit;
 
-  // The two roles run separate loops (so that the service wave carries no ring registers and
-  // the streaming waves no staging registers) with the same sequence of workgroup barriers.
+  // The two roles run separate loops (so that the service wave carries no ring registers and the streaming waves no
+  // staging registers) with the same sequence of workgroup barriers.
   if (service) {
-    // (with grid barriers the service wave's few polls gain from being issued ahead of the
-    // streaming waves' requests; measured: 0.6 % faster there, 1 % slower with the tagged exchange)
-    if (!TAG) __builtin_amdgcn_s_setprio(3);
-    lds_barrier();                                 // every wave's stores of the embedding are complete (and the rotation table)
-    unsigned gu_ticks = 0;
-    bool sync_ok = true;                           // tagged exchange with barrier: verdict of the latest grid barrier
-    // RMSNorm gains of the next phase that has a norm: constants, fetched while the phase before
-    // streams so that they are not in the way when the phase's input arrives
+    lds_barrier();                                 // the rotation table is in LDS
+    // RMSNorm gains of the next phase that has a norm: constants, fetched while the phase before streams so that they
+    // are not in the way when the phase's input arrives
     {
-      const SegDesc first = seg_desc(P, 0, nk, kept, share);
+      const SegDesc first = seg_desc(P, 0, nk, kept, share, share_o);
       if (first.gain != nullptr && D <= 4096) sk_gains_to_lds(S.gs, first.gain, D);
     }
+    float h_prev = 0.f;                            // lane r: residual row row0 + r of the coming output / down projection (tagged word)
+    // (a phase's descriptor is worked out while the phase before streams: nothing but the wait for the input and its
+    // staging stands between a phase's results and the next phase)
+    SegDesc cur = seg_desc(P, 0, nk, kept, share, share_o);
     for (int s = 0; s < nsegs; ++s) {
-      const SegDesc cur = seg_desc(P, s, nk, kept, share);
       SK_STAMP(0);
-      const bool fast_norm = cur.gain != nullptr && D <= 4096;
-      if (!TAG) SK_GRID_SYNC_TRACED();             // everything the segment reads has been written
-      else if (detect && s == 0) sync_ok = grid_sync(bar, ++epoch, cu, ncu) != 0;
       SK_STAMP(1);
-      bool staged_ok = sync_ok;
+      const bool fast_norm = cur.gain != nullptr && D <= 4096;
+      bool staged_ok = true;
       if (cur.kind == SEG_O) {
-        if (TAG) {
-          tag_a ^= 1u;
-          // q, k, v of this workgroup's KV head into LDS as soon as they are current
-          bool ok = true;
-          if (attn_wg) ok = sk_attn_prologue_tagged<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, tag_q);
-          if (lane == 0) *S.flag = ok && sync_ok ? 1 : 0;
-          lds_barrier();
-          if (uni(*S.flag) == 0) return;
-          if (attn_wg) { lds_barrier(); lds_barrier(); lds_barrier(); }
-          if (detect) sync_ok = grid_sync(bar, ++epoch, cu, ncu) != 0;     // (the merging waves did not wait for their stores)
-          SK_STAMP(2);
-          staged_ok = sync_ok && sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err);
-        } else {
-          lds_barrier();
-          if (uni(*S.flag) == 0) return;
-          if (attn_wg) sk_attention_service();
-          lds_barrier();                           // the attention output of this workgroup is out
-          SK_GRID_SYNC();
-          SK_STAMP(2);
-          sk_stage_wave<false>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, 0u, nullptr);
+        tag_a ^= 1u;
+        if (attn_wg) {
+          unsigned long long* stamps = (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr;
+          const bool ok = sk_attn_prologue_head<HD>(P, cur.kv, S, A, tag_q);
+          if (lane == 0) *S.flag = ok ? 1 : 0;
+          lds_barrier();                           // queries in LDS, verdict visible
+          if (!ok) return;
+          lds_barrier();                           // the streaming waves' partial results are in LDS
+          staged_ok = sk_attn_merge_head<HD>(P, S, A, tag_a, stamps);
         }
+        SK_STAMP(2);
+        if (cur.nrows > 0)
+          staged_ok = sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err) && staged_ok;
       } else if (cur.kind == SEG_DN) {
-        // the down projection starts on the first K-segment of its input; the rest is staged
-        // while it streams (after the workgroup barrier below)
-        staged_ok = sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err) && staged_ok;
+        // the down projection starts on the first K-segment of its input; the rest is staged while it streams (after
+        // the workgroup barrier below)
+        staged_ok = sk_stage_segments<true>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err);
         __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
       } else if (fast_norm) {
-        staged_ok = sk_stage_norm_wave<TAG>(S.xs, h, D, S.gs, p.eps, tag_h, P.err) && staged_ok;
+        staged_ok = sk_stage_norm_wave<true>(S.xs, h, D, S.gs, p.eps, tag_h, P.err);
       } else {
-        staged_ok = sk_stage_wave<TAG>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err) && staged_ok;
+        staged_ok = sk_stage_wave<true>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err);
       }
-      if (TAG && lane == 0) *S.flag = staged_ok ? 1 : 0;
+      if (lane == 0) *S.flag = staged_ok ? 1 : 0;
       SK_STAMP(3);
       lds_barrier();                               // input vector staged; verdict of the wait visible
-      if (uni(*S.flag) == 0) return;
-      // residual rows this workgroup will update: final since the barrier above, so they are
-      // fetched while the weights stream (tagged exchange: kept in a register instead)
-      float h_prev = h_own;
-      if (!TAG && (cur.kind == SEG_O || cur.kind == SEG_DN) && lane < cur.nrows) h_prev = ld_coh(h + cur.row0 + lane);
-      const bool timed = cur.kind == SEG_GU && P.share_time != nullptr;   // the longest phase measures this XCD's stream rate
-      const unsigned long long t_stream = timed ? wall_clock64() : 0ull;
+      if (!staged_ok) return;
+      const SegDesc nx = seg_desc(P, s + 1, nk, kept, share, share_o);
+      if (cur.kind == SEG_QKV || cur.kind == SEG_GU) {
+        // every word of h has just been seen current: fetch the rows the next phase of this workgroup adds to
+        h_prev = ld_coh(h + nx.row0 + min(lane, max(nx.nrows - 1, 0)));
+      }
       if (cur.kind == SEG_DN) {
         for (int c = 1; c < cur.nseg; c += 2) {
           const int c1 = min(c + 2, cur.nseg);
           // (a wait that gives up has said so in *P.err: the next phase's wait ends the workgroup)
-          sk_stage_segments<TAG>(S.zs, p.z + (size_t)b * F, F, c, c1, tag_z, P.err);
+          sk_stage_segments<true>(S.zs, p.z + (size_t)b * F, F, c, c1, tag_z, P.err);
           __hip_atomic_store(S.flag + 2, c1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
       }
-      if (s + 1 < nsegs && D <= 4096) {            // (this phase's staging has read S.gs already)
-        const float* next_gain = seg_desc(P, s + 1, nk, kept, share).gain;
-        if (next_gain != nullptr) sk_gains_to_lds(S.gs, next_gain, D);
-      }
+      if (s + 1 < nsegs && D <= 4096 && nx.gain != nullptr) sk_gains_to_lds(S.gs, nx.gain, D);   // (this phase's staging has read S.gs already)
+      SK_XSTAMP(0);
       lds_barrier();                               // partial sums complete
-      if (timed) gu_ticks += (unsigned)(wall_clock64() - t_stream);
       SK_STAMP(4);
-      // tagged exchange with barrier: the arrival is requested before the results are stored
-      // and awaited after, so the two travel together
-      const bool arrive = detect && s + 1 < nsegs;
-      unsigned arrived = 0;
-      if (arrive && bar.two_level) grid_arrive(bar, arrived);
       // results of the segment
       if (cur.kind == SEG_QKV) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
         tag_q ^= 1u;
         for (int r = lane; r < cur.nrows; r += 64) {
           const float v = sk_row_sum(S.psum, r, cur.nseg, cur.nrows);
-          st_coh(out + cur.row0 + r, TAG ? sk_tagged(v, tag_q) : v);
+          st_coh(out + cur.row0 + r, sk_tagged(v, tag_q));
         }
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
-        if (TAG) {
-          tag_h ^= 1u;
-          if (lane < cur.nrows) {
-            h_own = sk_untag(h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
-            st_coh(h + cur.row0 + lane, sk_tagged(h_own, tag_h));
-          }
-        } else {
-          if (lane < cur.nrows) st_coh(h + cur.row0 + lane, h_prev + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
-          for (int r = 64 + lane; r < cur.nrows; r += 64)
-            st_coh(h + cur.row0 + r, ld_coh(h + cur.row0 + r) + sk_row_sum(S.psum, r, cur.nseg, cur.nrows));
+        tag_h ^= 1u;
+#ifdef SK_DBG_DUMP
+        if (P.tdbg && cur.kind == SEG_O && lane < cur.nrows) {
+          float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
+          dbg[cur.row0 + lane] = sk_untag(h_prev);
+          dbg[D + cur.row0 + lane] = sk_row_sum(S.psum, lane, cur.nseg, cur.nrows);
+        }
+        if (P.tdbg && cur.kind == SEG_O && cu == ncu - 1) {
+          float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
+          for (int k = lane; k < nq; k += 64) dbg[2 * D + k] = S.xs[(((k >> 3) << 2) | (k & 3)) + ((k & 4) ? sk_plane(nq) : 0)];
+        }
+#endif
+        if (lane < cur.nrows) {
+          const float v = sk_untag(sk_untag(h_prev) + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
+          st_coh(h + cur.row0 + lane, sk_tagged(v, tag_h));
+          if (cur.kind == SEG_DN && P.h_out != nullptr) P.h_out[(size_t)b * D + cur.row0 + lane] = v;
         }
       } else if (cur.kind == SEG_GU) {
         float* z = p.z + (size_t)b * F;
         tag_z ^= 1u;
         for (int r = lane; r < cur.nrows / 2; r += 64) {
           const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg, cur.nrows), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg, cur.nrows);
-          const float v = siluf(gt) * up;
-          st_coh(z + cur.row0 / 2 + r, TAG ? sk_tagged(v, tag_z) : v);
+          st_coh(z + cur.row0 / 2 + r, sk_tagged(siluf(gt) * up, tag_z));
         }
       } else {
-        // (tagged exchange: the residual rows of this workgroup also go out as plain values)
-        if (TAG && P.h_out != nullptr) {
-          SegDesc e{};
-          seg_split(e, D, D, share, 1);
-          if (lane < e.nrows) P.h_out[(size_t)b * D + e.row0 + lane] = h_own;
-        }
         float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
@@ -1432,81 +1514,86 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           Best* dst = p.arg_part + (size_t)b * ARG_MAX_WG + cu;
           st_coh(&dst->v, best.v); st_coh(&dst->i, best.i);
         }
+        vm_wait_all();                             // the candidate is in memory before this workgroup says so
       }
-      if (!TAG || s == nsegs - 1) vm_wait_all();   // the stores are complete before this workgroup arrives at a barrier
-      if (arrive) sync_ok = (bar.two_level ? grid_wait(bar, ++epoch, arrived) : grid_sync(bar, ++epoch, cu, ncu)) != 0;
       SK_STAMP(5);
+      cur = nx;
     }
-    if (P.share_time != nullptr && lane == 0) P.share_time[cu] = min(gu_ticks, 0xffffffu) | (bar.x << 24);
-    // greedy token: workgroup 0 reduces the per-workgroup candidates
-    const int ok = grid_sync(bar, ++epoch, cu, ncu);
-    if (ok && cu == 0) {
-      Best bb{-INFINITY, 0x7fffffff};
-      const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
-      for (int i = lane; i < ncu; i += 64) { const Best c{ld_coh(&ap[i].v), ld_coh(&ap[i].i)}; if (better(c, bb)) bb = c; }
+    // greedy token: every workgroup publishes the launch's epoch once its candidate is stored; workgroup 0 waits for
+    // all of them and reduces.  Epochs only grow from launch to launch, so nothing is cleared in between.
+    if (lane == 0) __hip_atomic_store(P.done + cu, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (cu != 0) return;
+    {
+      unsigned spins = 0;
+      for (;;) {
+        bool ok = true;
+        int e = 0;
+        for (int base = 0; base < ncu; base += 256) {
+          unsigned f[4];
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const Best c{__shfl_xor(bb.v, o, 64), __shfl_xor(bb.i, o, 64)};
-        if (better(c, bb)) bb = c;
-      }
-      if (lane == 0) {
-        if (p.token_out) p.token_out[b] = bb.i;
-        if (p.advance_len) p.len[b] = pos + 1;
-        if (TAG) {
-          int* ts = P.tagstate + 4 * b;
-          st_coh(ts, (int)tag_h); st_coh(ts + 1, (int)tag_q); st_coh(ts + 2, (int)tag_a); st_coh(ts + 3, (int)tag_z);
+          for (int i = 0; i < 4; ++i) coh_issue4(f[i], P.done + min(base + i * 64 + lane, ncu - 1));
+          coh_issue4(e, P.err);
+          coh_wait();
+          coh_use(e);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { coh_use(f[i]); ok = ok && (f[i] == epoch); }
         }
+        if (__all(ok)) break;
+        if (sk_poll_give_up(spins, uni(e), P.err)) return;
       }
+    }
+    Best bb{-INFINITY, 0x7fffffff};
+    const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
+    for (int i = lane; i < ncu; i += 64) { const Best c{ld_coh(&ap[i].v), ld_coh(&ap[i].i)}; if (better(c, bb)) bb = c; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const Best c{__shfl_xor(bb.v, o, 64), __shfl_xor(bb.i, o, 64)};
+      if (better(c, bb)) bb = c;
+    }
+    if (lane == 0) {
+      if (p.token_out) p.token_out[b] = bb.i;
+      if (p.advance_len) p.len[b] = pos + 1;
+      int* ts = P.tagstate + 8 * b;
+      st_coh(ts, (int)tag_h); st_coh(ts + 1, (int)tag_q); st_coh(ts + 2, (int)tag_a); st_coh(ts + 3, (int)tag_z);
+      st_coh(ts + 4, (int)epoch);
+#ifdef SK_DBG_DUMP
+      if (P.tdbg) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[1001] = wall_clock64();
+#endif
     }
   } else {
     uint4 buf[SK_PD][4];
     {
-      const SegDesc first = seg_desc(P, 0, nk, kept, share);
+      const SegDesc first = seg_desc(P, 0, nk, kept, share, share_o);
 #pragma unroll
       for (int j = 0; j < SK_PD; ++j) sk_issue(first, j, true, wave, buf[j]);
     }
     lds_barrier();
+    SegDesc cur = seg_desc(P, 0, nk, kept, share, share_o);
     for (int s = 0; s < nsegs; ++s) {
-      const SegDesc cur = seg_desc(P, s, nk, kept, share);
-      const SegDesc nxt = seg_desc(P, s + 1, nk, kept, share);
       const float* xsrc = cur.kind == SEG_DN ? S.zs : S.xs;
-      if (cur.kind == SEG_O) {
-        if (!TAG) {
-          lds_barrier();
-          if (uni(*S.flag) == 0) return;
-        }
-        // only the SK_PD_EARLY lower ring slots stay in flight across attention (it needs the
-        // registers); the upper slots hold nothing here and are refilled right after
-#pragma unroll
-        for (int j = SK_PD_EARLY; j < SK_PD; ++j)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) buf[j][i] = make_uint4(0, 0, 0, 0);
+      if (cur.kind == SEG_O && attn_wg) {
+        // (a wave that takes tiles has nothing of the ring in flight here: its registers hold the keys and values)
         unsigned long long* stamps = (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr;
-        if (TAG) {
-          tag_a ^= 1u;
-          if (attn_wg) {
-            if (!sk_attention<HD, SK_SWAVES, true>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, stamps, (int)tag_a)) return;
-          } else {
-            lds_barrier();
-            if (uni(*S.flag) == 0) return;
-          }
-        } else if (attn_wg) {
-          sk_attention<HD>(P, cur.kv, S, cu / nsplit, cu % nsplit, nsplit, stamps);
-        }
+        if (wave < A.nact) {
+          if (!sk_attention_head<HD>(P, cur.kv, S, A, stamps)) return;
 #pragma unroll
-        for (int j = SK_PD_EARLY; j < SK_PD; ++j) sk_issue(cur, j, true, wave, buf[j]);
-        if (!TAG) lds_barrier();
+          for (int j = 0; j < SK_PD; ++j) sk_issue(cur, j, true, wave, buf[j]);
+        } else if (!sk_attention_idle(S)) {
+          return;
+        }
       }
+      const SegDesc nxt = seg_desc(P, s + 1, nk, kept, share, share_o);
       lds_barrier();                               // input vector staged
+      if (wave == 0) SK_XSTAMP(1);
+      if (wave == 6) SK_XSTAMP(4);
       if (uni(*S.flag) == 0) return;
-      // all blocks but the last request ahead inside this segment; the last one requests the
-      // first rounds of the next segment (no per-round choice between the two descriptors)
+      // all blocks but the last request ahead inside this segment; the last one requests the first rounds of the
+      // next segment (no per-round choice between the two descriptors)
       const int last0 = cur.nr_pad - SK_PD;
       const int* staged = cur.kind == SEG_DN ? S.flag + 2 : nullptr;
+      const bool ahead = !(nxt.kind == SEG_O && attn_wg && wave < A.nact);     // a wave with tiles requests its output-projection rows afterwards
       int seen = 1;
       for (int r0 = 0; r0 < last0; r0 += SK_PD) {
-        if (P.tdbg && s == 6 && cu == 0 && tid == 0 && r0 / SK_PD < 10)          // timing aid: progress of the GU stream
-          P.tdbg[(4 * P.L + 1) * SK_TSLOTS + 2 * ncu + r0 / SK_PD] = wall_clock64();
 #pragma unroll
         for (int j = 0; j < SK_PD; ++j) {
           sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
@@ -1516,55 +1603,18 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
 #pragma unroll
       for (int j = 0; j < SK_PD; ++j) {
         sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
-        sk_issue(nxt, j, nxt.kind != SEG_O || j < SK_PD_EARLY, wave, buf[j]);
+        sk_issue(nxt, j, ahead, wave, buf[j]);
+        if (j == 0 && wave == 0) SK_XSTAMP(6);
+        if (j == 0 && wave == 6) SK_XSTAMP(7);
       }
+      if (wave == 0) SK_XSTAMP(2);
+      if (wave == 6) SK_XSTAMP(5);
       lds_barrier();                               // partial sums complete
+      if (wave == 0) SK_XSTAMP(3);
+      cur = nxt;
     }
   }
-#undef SK_GRID_SYNC
-#undef SK_GRID_SYNC_TRACED
 #undef SK_STAMP
-}
-
-// Runs after k_step (one workgroup): turns the gate/up streaming times of the workgroups into
-// per-XCD row shares for the next launches.  An XCD that streams slower (its workgroups took
-// longer for their share) gets fewer rows, so that all workgroups reach the phase barriers
-// together.  Shares never change results: every row is computed the same way whoever owns it.
-// Nothing changes unless every workgroup c reported XCD c % 8 and a time.
-__global__ void __launch_bounds__(256) k_rebalance(const unsigned* __restrict__ share_time, int* __restrict__ shares, int ncu) {
-  __shared__ unsigned long long tsum[8];
-  __shared__ unsigned cnt[8];
-  __shared__ int bad;
-  const int tid = threadIdx.x;
-  if (tid < 8) { tsum[tid] = 0ull; cnt[tid] = 0u; }
-  if (tid == 0) bad = (ncu & 7) != 0 || ncu > 2048;
-  __syncthreads();
-  for (int c = tid; c < ncu; c += 256) {
-    const unsigned v = share_time[c], x = v >> 24, t = v & 0xffffffu;
-    if (x != (unsigned)(c & 7) || t == 0u || t == 0xffffffu) atomicOr(&bad, 1);
-    else { atomicAdd(&tsum[x], (unsigned long long)t); atomicAdd(&cnt[x], 1u); }
-  }
-  __syncthreads();
-  if (tid != 0 || bad) return;
-  float rate[8], tot = 0.f;
-  int cur[8], csum = 0;
-  for (int x = 0; x < 8; ++x) { cur[x] = shares[x]; csum += cur[x]; }
-  if (csum != 8192) { for (int x = 0; x < 8; ++x) cur[x] = 1024; }
-  for (int x = 0; x < 8; ++x) {
-    if (cnt[x] == 0u) return;
-    rate[x] = (float)cur[x] / ((float)tsum[x] / (float)cnt[x]);     // rows per tick this XCD sustained
-    tot += rate[x];
-  }
-  int nw[8], sum = 0, big = 0;
-  for (int x = 0; x < 8; ++x) {
-    const float target = 8192.f * rate[x] / tot;
-    int v = (int)(0.5f * (float)cur[x] + 0.5f * target + 0.5f);      // damped
-    v = max(870, min(1178, v));                                      // within 15 % of an equal share
-    nw[x] = v; sum += v;
-    if (nw[x] > nw[big]) big = x;
-  }
-  nw[big] += 8192 - sum;                                             // shares add up exactly
-  for (int x = 0; x < 8; ++x) shares[x] = nw[x];
 }
 
 }  // namespace first

@@ -13,8 +13,6 @@ pytestmark = pytest.mark.gpu
 torch.set_grad_enabled(False)
 
 OPT_DECODE_PATH = 3
-OPT_STEP_BARRIER = 5
-OPT_STEP_BALANCE = 8
 
 
 @pytest.mark.parametrize("model,n_prompt", [("step_hd128", 150), ("step_hd64", 70), ("step_g2", 200),
@@ -60,17 +58,10 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
     mask = make_skip_mask(desc.n_layers, 1 if desc.n_layers > 2 else 0, 43).tolist()
     inputs = [[int(t)] for t in make_prompt(desc.vocab, 24, 44)]
     runs = {}
-    # exchange kinds (option STEP_BARRIER): 2 tagged words (default), 3 tagged words + grid barrier,
-    # 1 two-level grid barrier, 0 flat grid barrier
-    for name, path, graph, barrier, balance in (("ops", 0, 1, 2, 0), ("step", 1, 1, 2, 0), ("step_again", 1, 1, 2, 0),
-                                                ("step_eager", 1, 0, 2, 0), ("step_shares", 1, 1, 2, 1),
-                                                ("tagged_barrier", 1, 1, 3, 0), ("two_level", 1, 1, 1, 0),
-                                                ("flat", 1, 1, 0, 0), ("two_level_shares", 1, 1, 1, 1)):
+    for name, path, graph in (("ops", 0, 1), ("step", 1, 1), ("step_again", 1, 1), ("step_eager", 1, 0)):
         desc, w, router, ctx = build(model, 43, max_seq_len=200)
         ctx.set_option(OPT_DECODE_PATH, path)
         ctx.set_option(1, graph)
-        ctx.set_option(OPT_STEP_BARRIER, barrier)
-        ctx.set_option(OPT_STEP_BALANCE, balance)
         _prefill(ctx, desc, [prompt])
         ctx.set_mask(0, mask)
         lg, tk = _decode(ctx, desc, inputs)
@@ -81,14 +72,8 @@ def test_step_kernel_agrees_with_per_op_kernels_and_is_reproducible(model):
     def same(a, b):
         return torch.equal(runs[a][0], runs[b][0]) and torch.equal(runs[a][1], runs[b][1]) and torch.equal(runs[a][2], runs[b][2])
 
+    # fixed summation orders everywhere: run to run, and graph replay against eager launches
     assert same("step", "step_again") and same("step", "step_eager")
-    # who owns which weight rows (the shares move with the measured streaming times) changes no arithmetic
-    assert same("step", "step_shares") and same("two_level", "two_level_shares")
-    # how readiness is detected changes no arithmetic: the two tagged kinds agree, and so do the two barriers
-    assert same("step", "tagged_barrier") and same("two_level", "flat")
-    # tagged words drop the last mantissa bit of the exchanged activations (relative 2^-23)
-    scale = float(runs["two_level"][0].abs().max())
-    assert float((runs["step"][0] - runs["two_level"][0]).abs().max()) <= 2e-5 * scale
     # same arithmetic up to fp32 summation order
     assert float((runs["step"][0] - runs["ops"][0]).abs().max()) <= 3e-3   # a new K/V may round to the neighbouring bf16
     assert float((runs["step"][2] - runs["ops"][2]).abs().max()) <= 3e-3 * float(runs["ops"][2].abs().max())
