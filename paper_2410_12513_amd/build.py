@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 # written later, so a destination it spills and hands to another value is overwritten when the load lands.  Bytes of
 # scratch per lane each kernel may use (k_step: a handful of loop-invariant values the compiler parks there at its
 # register limit; asm_check.py verifies that no in-flight destination is among them, or is touched in any other way):
-SCRATCH_LIMITS = {"k_step": 32, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv_g": 0, "k_gemm_nt_bf16_hl": 0}
+SCRATCH_LIMITS = {"k_step": 64, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv_g": 0, "k_gemm_nt_bf16_hl": 0}
 
 
 def kernel_resources(remarks: str) -> dict:

@@ -39,6 +39,7 @@ struct LayerPtrs {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
   const float *g_attn, *g_mlp;
   bf16 *t_qkv = nullptr, *t_o = nullptr, *t_g = nullptr, *t_u = nullptr, *t_d = nullptr;   // tile-order copies (batched decode)
+  bf16* wd_perm = nullptr;     // persistent kernel: down-projection matrix with its columns in z' order (sk_zperm_source)
 };
 
 }  // namespace
@@ -117,6 +118,7 @@ struct first_ctx {
   unsigned long long* d_tdbg = nullptr;   // step-kernel timestamps (FIRST_OPT_STEP_TIMING)
   int step_timing = 0;
   bool step_ok = false;        // geometry fits the persistent kernel
+  bool zperm = false;          // ... and every layer has its column-permuted copy of the down-projection matrix
   size_t step_lds = 0;
   // options and graph cache
   int use_graph = 1, attn_splits = 0, decode_path = -1;   // -1: persistent kernel when possible
@@ -201,6 +203,29 @@ void release_sequences(first_ctx* c) {
   reset_layer_slices(c);
 }
 
+// Column-permuted copies of the down-projection matrices for the persistent kernel's blocked gate/up phase (as much
+// memory again as those matrices: 117 MB per layer on the 8B shape), made only when the geometry allows the blocks and
+// at least that much device memory plus a 4 GiB margin is free; without them z keeps its natural order and the down
+// projection waits for the end of the gate/up phase.  The caller's matrices must not change afterwards.
+hipError_t make_permuted_down_copies(first_ctx* c) {
+  const first_model_desc& d = c->d;
+  if (!sk_zperm_fits(d.d_ffn, d.d_model, c->num_cu)) return hipSuccess;
+  if (getenv("FIRST_ZPERM") && atoi(getenv("FIRST_ZPERM")) == 0) return hipSuccess;   // (experiment)
+  const size_t per_layer = (size_t)d.d_model * d.d_ffn * sizeof(bf16);
+  size_t free_b = 0, total_b = 0;
+  if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < per_layer * d.n_layers + ((size_t)4 << 30)) return hipSuccess;
+  for (int i = 0; i < d.n_layers; ++i) {
+    LayerPtrs& l = c->layers[i];
+    if (dev_alloc(c, &l.wd_perm, (size_t)d.d_model * d.d_ffn)) return hipErrorOutOfMemory;
+    hipLaunchKernelGGL(k_permute_down_columns, dim3(4096), dim3(WG), 0, c->stream, reinterpret_cast<const bf16*>(l.wd), l.wd_perm,
+                       d.d_model, d.d_ffn, c->num_cu);
+  }
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  c->zperm = e == hipSuccess;
+  return e;
+}
+
 // Per-layer pointers of the persistent kernel (weights, gains, the layer's page pool).  The stream must be idle.
 hipError_t upload_layer_table(first_ctx* c) {
   const int L = c->d.n_layers;
@@ -208,7 +233,7 @@ hipError_t upload_layer_table(first_ctx* c) {
   for (int i = 0; i < L; ++i) {
     const LayerPtrs& l = c->layers[i];
     ld[i] = LayerDev{(const bf16*)l.wq, (const bf16*)l.wk, (const bf16*)l.wv, (const bf16*)l.wo, (const bf16*)l.wg,
-                     (const bf16*)l.wu, (const bf16*)l.wd, l.g_attn, l.g_mlp, (bf16*)kv_base(c, i)};
+                     (const bf16*)l.wu, c->zperm ? l.wd_perm : (const bf16*)l.wd, l.g_attn, l.g_mlp, (bf16*)kv_base(c, i)};
   }
   return hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
 }
@@ -523,7 +548,7 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
   P.layers = c->d_layers; P.kept = c->d_kept; P.n_kept = c->d_nkept; P.L = c->d.n_layers;
   P.done = c->d_done; P.err = c->d_err;
-  P.tagstate = c->d_tagstate; P.h_out = c->d_h; P.part = c->x_part;
+  P.tagstate = c->d_tagstate; P.h_out = c->d_h; P.part = c->x_part; P.zperm = c->zperm ? 1 : 0;
   P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
   if (c->d.head_dim == 128) hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
@@ -868,7 +893,8 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = reset_tagged_exchange(c);
     c->step_ok = step_kernel_fits(c);
     if (e == hipSuccess && c->step_ok) {
-      e = upload_layer_table(c);
+      e = make_permuted_down_copies(c);
+      if (e == hipSuccess) e = upload_layer_table(c);
       c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
       const void* fn = d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>) : reinterpret_cast<const void*>(&k_step<64>);
       if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);

@@ -181,6 +181,7 @@ struct StepParams {
   int* tagstate;               // [B][8]: tags of the latest writes to the h, qkv, attn and z vectors of each slot, [4] = epoch of the
                                //         latest launch's final reduction
   float* h_out;                // [B][D] plain copy of the final hidden state (d.h holds tagged words)
+  int zperm;                   // 1: the layers' down-projection matrices are the column-permuted copies (seg_blocks_gateup)
   float* part;                 // [B][Hq][SK_QSPLIT_MAX][hd + 4] tagged partial attention results of key splits 1.. (o[hd], max, sum)
   bf16 *xh_out, *xl_out;       // sk_attention<.., SPLIT_OUT> (batched path): the attention output as bf16 high / low halves in
   int out_slot;                //   A-operand order (bg_aidx) for slot out_slot, instead of fp32 in d.attn
@@ -200,7 +201,8 @@ struct SkLds {
   float2* cs;     // [hd/2]
   float* ps;      // [SK_WAVES][64]
   float* mb;      // [SK_WAVES][hd + 2]
-  int* flag;      // [4]
+  int* flag;      // [16]: [0] verdict of the service wave's latest wait, [2] K-segments of z staged for the down projection,
+                  //       [4 + w] rounds of the running phase streaming wave w has finished (gate/up in blocks)
 };
 
 __host__ __device__ inline size_t sk_lds_floats(int D, int nq, int F, int G, int hd) {
@@ -208,7 +210,7 @@ __host__ __device__ inline size_t sk_lds_floats(int D, int nq, int F, int G, int
   F = (F + 2047) / 2048 * 2048;
   const int gs = ((D + 2047) / 2048 * 2048) < 4096 ? ((D + 2047) / 2048 * 2048) : 4096;
   return (size_t)xs + F + SK_PSUM + gs + (SK_WAVES + 8) + (size_t)G * hd + 2 * hd + hd + SK_WAVES * 64 +
-         (size_t)SK_WAVES * (hd + 2) + 4;
+         (size_t)SK_WAVES * (hd + 2) + 16;
 }
 
 __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int G, int hd) {
@@ -447,7 +449,12 @@ struct SegDesc {
   int n0, n1, K, inter;
   int xplane;                   // offset of the second plane of the staged input vector (sk_plane(K))
   int row0, nrows, nseg, nunits, nr_pad;
-  unsigned inv_nrows;           // ceil(2^32 / nrows): unit / nrows = umulhi(unit, inv_nrows) for the small units here
+  // Unit order: the rows of a workgroup form blocks of bl rows; a block's units are ordered K-segment-major (all its rows
+  // of segment 0, then of segment 1, ...) and the blocks follow each other.  One block (bl = nrows) for every phase but
+  // gate/up, whose blocks are the chunks of z it produces for the down projection's K-segments (see seg_split_gateup).
+  int bl, upb, blk_stride;      // rows per block, units per block (bl * nseg), distance in rows between the blocks' first rows
+  unsigned inv_bl, inv_upb;     // ceil(2^32 / x): u / x = umulhi(u, inv_x) for the small u here (x <= 1 handled at use)
+  int sh_bl, sh_upb;            // log2 of bl and upb when the phase runs in blocks
   int kind;
   const float* gain;            // RMSNorm gain of the phase's input (null: no norm)
   bf16* kv;                     // KV pool of the layer (attention precedes SEG_O)
@@ -466,16 +473,85 @@ __device__ __forceinline__ void seg_split(SegDesc& d, int N, int K, const SkShar
   d.row0 = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w0) >> 10) / (unsigned)sh.ncu) * pair;
   d.nrows = (int)((unsigned)(((unsigned long long)(unsigned)n * (unsigned)sh.w1) >> 10) / (unsigned)sh.ncu) * pair - d.row0;
   d.nseg = (K + SK_SEG - 1) / SK_SEG;               // the last segment of a row may be partial (reads past the row end return zeros)
-  d.inv_nrows = d.nrows <= 1 ? 0u : (unsigned)((0x100000000ull + d.nrows - 1) / d.nrows);   // (nrows <= 1 handled at use)
   d.nunits = d.nrows * d.nseg;
+  d.bl = d.nrows; d.upb = d.nunits; d.blk_stride = 0; d.sh_bl = 0; d.sh_upb = 0;
+  d.inv_bl = d.bl <= 1 ? 0u : (unsigned)((0x100000000ull + d.bl - 1) / d.bl);
+  d.inv_upb = d.upb <= 1 ? 0u : (unsigned)((0x100000000ull + d.upb - 1) / d.upb);
   const int nr = (d.nunits + SK_SWAVES - 1) / SK_SWAVES;
   d.nr_pad = max(SK_PD, (nr + SK_PD - 1) / SK_PD * SK_PD);
+}
+
+// Gate/up in blocks, so that z leaves in the order the down projection consumes it.  The down projection reads its input
+// in K-segments of SK_SEG elements.  If every workgroup produced cs = SK_SEG / ncu elements of EVERY segment, finishing
+// them segment by segment, z's first segment would be complete, grid-wide, after 1 / nseg(F) of the gate/up phase
+// instead of at its end, and the down projection would never wait for its input.  Taking those elements from the
+// matching rows of the gate and up matrices (stride SK_SEG between a workgroup's blocks) measured 4 us per layer slower
+// than streaming one contiguous range of rows.  So the workgroup keeps its contiguous range - block k = its k-th group of
+// cs rows (gate and up interleaved: 2 cs rows of the stacked numbering) - and the ORDER OF z changes instead: element i
+// of block k of workgroup `rank` is z'[k * SK_SEG + cs * rank + i], and the down projection multiplies z' with a copy
+// of its matrix whose columns are permuted the same way (sk_zperm_source, made once at context creation).
+// Needs that copy (zperm), F to be whole segments and ncu to divide SK_SEG; otherwise one contiguous block, z in natural
+// order.  Called after seg_split(d, 2 * F, K, sh, 2).
+// (Written as selects between integers: a branch here makes the compiler keep the descriptor in scratch memory.)
+// (D enters through the K-segments of the gate/up input: rows and units per block must be powers of two)
+__host__ __device__ __forceinline__ bool sk_zperm_fits(int F, int D, int ncu) {
+  const int nsegk = (D + SK_SEG - 1) / SK_SEG, cs = ncu > 0 && SK_SEG % ncu == 0 ? SK_SEG / ncu : 0;
+  return F % SK_SEG == 0 && cs >= 1 && (cs & (cs - 1)) == 0 && (nsegk & (nsegk - 1)) == 0 && F / SK_SEG >= 2;
+}
+// Column of the caller's down-projection matrix (= natural index of z) that column j of the permuted copy holds.
+__host__ __device__ __forceinline__ int sk_zperm_source(int j, int F, int ncu) {
+  const int cs = SK_SEG / ncu, nblk = F / SK_SEG;
+  const int k = j / SK_SEG, rem = j - k * SK_SEG, rank = rem / cs, i = rem - rank * cs;
+  return cs * nblk * rank + cs * k + i;
+}
+__device__ __forceinline__ void seg_blocks_gateup(SegDesc& d, int F, const SkShare& sh, int zperm) {
+  const bool blocked = zperm != 0 && sk_zperm_fits(F, d.K, sh.ncu) && sh.w1 - sh.w0 == 1024;
+  const int cs = max(SK_SEG / sh.ncu, 1);
+  const int bl = 2 * cs, upb = bl * d.nseg;
+  d.bl = blocked ? bl : d.bl;
+  d.upb = blocked ? upb : d.upb;
+  d.blk_stride = blocked ? bl : 0;
+  d.inv_bl = blocked ? (unsigned)((0x100000000ull + bl - 1) / bl) : d.inv_bl;
+  d.inv_upb = blocked ? (unsigned)((0x100000000ull + upb - 1) / upb) : d.inv_upb;
+  d.sh_bl = 31 - __clz(bl); d.sh_upb = 31 - __clz(upb);
+}
+
+// Unit u of a phase -> K-segment (and row of the stacked / interleaved matrices).  One block: one multiply-high.
+// Blocks (gate/up): rows per block and units per block are powers of two (sk_zperm_fits), so shifts do.
+__device__ __forceinline__ int seg_unit_sg(const SegDesc& d, int u, int& rl_out) {
+  const int bl = uni(d.bl);
+  int sg, rl;
+  if (uni(d.blk_stride) != 0) {
+    const int v = u & (uni(d.upb) - 1);
+    sg = v >> uni(d.sh_bl);
+    rl = (u >> uni(d.sh_upb)) * bl + (v & (bl - 1));      // (blocks follow each other: blk_stride = bl)
+  } else {
+    sg = bl <= 1 ? u : uni((int)__umulhi((unsigned)u, d.inv_bl));
+    rl = u - sg * bl;
+  }
+  rl_out = rl;
+  return sg;
+}
+__device__ __forceinline__ void seg_unit(const SegDesc& d, int u, int& row, int& sg) {
+  int rl;
+  sg = seg_unit_sg(d, u, rl);
+  row = uni(d.row0) + rl;
+}
+// Sum over the K-segments of local row r (0 .. nrows-1 in unit order) of a finished phase or block.
+__device__ __forceinline__ float seg_row_sum(const float* psum, const SegDesc& d, int r) {
+  const int blk = d.blk_stride != 0 ? r >> d.sh_bl : 0;
+  const int base = blk * d.upb + (r - blk * d.bl);
+  float s = 0.f;
+  for (int g = 0; g < d.nseg; ++g) s += psum[base + g * d.bl];
+  return s;
 }
 
 __device__ __forceinline__ SegDesc seg_uniform(SegDesc d) {
   d.m0 = uni(d.m0); d.m1 = uni(d.m1); d.m2 = uni(d.m2); d.gain = uni(d.gain); d.kv = uni(d.kv);
   d.n0 = uni(d.n0); d.n1 = uni(d.n1); d.xplane = uni(d.xplane); d.K = uni(d.K); d.inter = uni(d.inter); d.row0 = uni(d.row0);
-  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.inv_nrows = (unsigned)uni((int)d.inv_nrows); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
+  d.nrows = uni(d.nrows); d.nseg = uni(d.nseg); d.nunits = uni(d.nunits); d.nr_pad = uni(d.nr_pad); d.kind = uni(d.kind);
+  d.bl = uni(d.bl); d.upb = uni(d.upb); d.blk_stride = uni(d.blk_stride); d.inv_bl = (unsigned)uni((int)d.inv_bl); d.inv_upb = (unsigned)uni((int)d.inv_upb);
+  d.sh_bl = uni(d.sh_bl); d.sh_upb = uni(d.sh_upb);
   return d;
 }
 
@@ -506,6 +582,7 @@ __device__ __forceinline__ SegDesc seg_desc_raw(const StepParams& P, int s, int 
     case SEG_GU:
       d.m0 = lw.wg; d.m1 = lw.wu; d.inter = 1; d.gain = lw.g_mlp;
       seg_split(d, 2 * p.F, p.D, sh, 2);
+      seg_blocks_gateup(d, p.F, sh, P.zperm);
       break;
     default:
       d.m0 = lw.wd; d.n0 = p.D;
@@ -550,11 +627,11 @@ __device__ __forceinline__ void sk_issue(const SegDesc& d, int round, bool enabl
   const int u = uni(round * SK_SWAVES + wave);
   const int valid = uni((int)(enable && u < d.nunits));   // SEG_NONE has no units
   const int uu = valid ? u : 0;
-  // units are ordered segment-major (all rows of K-segment 0, then of segment 1, ...), so the
-  // first rounds of a phase need only the first part of its input vector
-  const int nrows = uni(d.nrows);
-  const int sg = nrows <= 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nrows)), rl = uu - sg * nrows;
-  const unsigned long long ra = seg_row_addr(d, uni(d.row0) + rl);
+  // (units of a block are ordered segment-major, so the first rounds of a one-block phase need only the first part of
+  // its input vector)
+  int rw, sg;
+  seg_unit(d, uu, rw, sg);
+  const unsigned long long ra = seg_row_addr(d, rw);
   bf16* row = reinterpret_cast<bf16*>(((unsigned long long)(unsigned)uni((int)(ra >> 32)) << 32) | (unsigned)uni((int)(unsigned)ra));
   const int row_bytes = uni(d.K * 2);
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, row_bytes, 0x00020000);
@@ -577,9 +654,8 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
   const int valid = uni((int)(u < d.nunits));
   if (!valid) return;                              // padding round: the (zero) loads are accounted for, nothing to add
   const int lane = threadIdx.x & 63, K = uni(d.K);
-  const int uu = u;
-  const int nrows = uni(d.nrows);
-  const int sg = nrows <= 1 ? uu : uni((int)__umulhi((unsigned)uu, d.inv_nrows));
+  int rl_;
+  const int sg = seg_unit_sg(d, u, rl_);
   if (staged != nullptr && sg >= seen) {
     unsigned spins = 0;
     do {
@@ -609,11 +685,6 @@ __device__ __forceinline__ void sk_consume(const SegDesc& d, int round, int wave
   if (lane == 63) psum[u] = tot;
 }
 
-__device__ __forceinline__ float sk_row_sum(const float* psum, int rl, int nseg, int nrows) {
-  float s = 0.f;
-  for (int g = 0; g < nseg; ++g) s += psum[g * nrows + rl];
-  return s;
-}
 
 // ---------------------------------------------------------------------------------------
 // Attention of workgroup (KV head g, split s): the waves = G query heads x (SK_WAVES/G) key groups,
@@ -940,11 +1011,7 @@ struct SkAttnGeo {
 // allows, so that a workgroup has few tiles and each of them a wave (and a SIMD) of its own - a tile is a few thousand
 // ALU cycles of one wave.  tps = tiles per split.
 __device__ __forceinline__ int sk_attn_splits(int tiles, int ncu, int Hq, int& tps) {
-#ifdef SK_DBG_NSPLIT1
-  const int smax = 1;
-#else
   const int smax = max(1, min(SK_QSPLIT_MAX, ncu / Hq));
-#endif
   tps = (tiles + smax - 1) / smax;
   return (tiles + tps - 1) / tps;
 }
@@ -1304,6 +1371,24 @@ __device__ __forceinline__ bool sk_attn_merge_head(const StepParams& P, const Sk
   return true;
 }
 
+// dst[r][j] = src[r][sk_zperm_source(j)]: the down-projection matrix with its columns in the order in which the blocked
+// gate/up phase produces z (made once per layer at context creation).  Groups of SK_SEG / ncu columns move together.
+__global__ void __launch_bounds__(WG) k_permute_down_columns(const bf16* __restrict__ src, bf16* __restrict__ dst, int D, int F, int ncu) {
+  const int cs = SK_SEG / ncu;
+  const size_t groups = (size_t)D * (F / cs);
+  for (size_t g = (size_t)blockIdx.x * WG + threadIdx.x; g < groups; g += (size_t)gridDim.x * WG) {
+    const size_t r = g / (F / cs);
+    const int j = (int)(g - r * (F / cs)) * cs;
+    const bf16* in = src + r * F + sk_zperm_source(j, F, ncu);
+    bf16* out = dst + r * F + j;
+    if (cs % 8 == 0) {
+      for (int i = 0; i < cs; i += 8) *reinterpret_cast<uint4*>(out + i) = *reinterpret_cast<const uint4*>(in + i);
+    } else {
+      for (int i = 0; i < cs; ++i) out[i] = in[i];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds (28 KB) in flight that runs
 // on across phase boundaries, so HBM stays busy while the workgroups hand their results on.  The last wave is the
@@ -1350,11 +1435,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const SkAttnGeo A = sk_attn_geo(p, attn_wg ? cu : 0, nsplit, tps, pos);
   // output projection: rows on the workgroups that have no attention work when those are at least half the grid and
   // enough for one residual row per service-wave lane
-#ifdef SK_DBG_OFIRST0
-  const int o_first = 0;
-#else
   const int o_first = (2 * n_attn <= ncu && (ncu - n_attn) * 64 >= D) ? n_attn : 0;
-#endif
   const SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
   const SkShare share_o{cu >= o_first ? (cu - o_first) * 1024 : 0, cu >= o_first ? (cu - o_first + 1) * 1024 : 0, ncu - o_first};
 
@@ -1410,6 +1491,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       if (first.gain != nullptr && D <= 4096) sk_gains_to_lds(S.gs, first.gain, D);
     }
     float h_prev = 0.f;                            // lane r: residual row row0 + r of the coming output / down projection (tagged word)
+    int z_staged = 0;                              // K-segments of the coming down projection's input already in LDS
     // (a phase's descriptor is worked out while the phase before streams: nothing but the wait for the input and its
     // staging stands between a phase's results and the next phase)
     SegDesc cur = seg_desc(P, 0, nk, kept, share, share_o);
@@ -1433,16 +1515,20 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         if (cur.nrows > 0)
           staged_ok = sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err) && staged_ok;
       } else if (cur.kind == SEG_DN) {
-        // the down projection starts on the first K-segment of its input; the rest is staged while it streams (after
-        // the workgroup barrier below)
-        staged_ok = sk_stage_segments<true>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err);
-        __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // the down projection starts on the first K-segment of its input (already staged during gate/up when that ran
+        // in blocks); the rest is staged while it streams (after the workgroup barrier below)
+        if (z_staged == 0) {
+          staged_ok = sk_stage_segments<true>(S.zs, p.z + (size_t)b * F, F, 0, 1, tag_z, P.err);
+          z_staged = 1;
+          __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
       } else if (fast_norm) {
         staged_ok = sk_stage_norm_wave<true>(S.xs, h, D, S.gs, p.eps, tag_h, P.err);
       } else {
         staged_ok = sk_stage_wave<true>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err);
       }
       if (lane == 0) *S.flag = staged_ok ? 1 : 0;
+      if (cur.kind == SEG_GU && lane < SK_WAVES) S.flag[4 + lane] = 0;     // (rounds finished: counted from the barrier below)
       SK_STAMP(3);
       lds_barrier();                               // input vector staged; verdict of the wait visible
       if (!staged_ok) return;
@@ -1452,11 +1538,43 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         h_prev = ld_coh(h + nx.row0 + min(lane, max(nx.nrows - 1, 0)));
       }
       if (cur.kind == SEG_DN) {
-        for (int c = 1; c < cur.nseg; c += 2) {
+        for (int c = z_staged; c < cur.nseg; c += 2) {
           const int c1 = min(c + 2, cur.nseg);
           // (a wait that gives up has said so in *P.err: the next phase's wait ends the workgroup)
           sk_stage_segments<true>(S.zs, p.z + (size_t)b * F, F, c, c1, tag_z, P.err);
           __hip_atomic_store(S.flag + 2, c1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        z_staged = 0;
+      }
+#ifdef SK_V_T1
+      if (false) {
+#else
+      if (cur.kind == SEG_GU && cur.blk_stride != 0) {
+#endif
+        // Gate/up in blocks: block k is this workgroup's part of K-segment k of the down projection's input.  As soon
+        // as the streaming waves are through a block its z values go out, and the segment before it - by now complete
+        // grid-wide - is staged for the down projection, which therefore starts without waiting for anybody.
+        float* z = p.z + (size_t)b * F;
+        tag_z ^= 1u;
+        const int nblk = cur.nunits / cur.upb, cs = cur.bl >> 1;
+        for (int k = 0; k < nblk; ++k) {
+          const int need = (k + 1) * cur.upb;          // every unit below this one has been consumed
+          unsigned spins = 0;
+          for (;;) {
+            const int done = __hip_atomic_load(S.flag + 4 + min(lane, SK_SWAVES - 1), __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (__all(done * SK_SWAVES + min(lane, SK_SWAVES - 1) >= need) || ++spins > SK_SPIN_LIMIT) break;
+            __builtin_amdgcn_s_sleep(8);
+          }
+          for (int r = lane; r < cs; r += 64) {
+            const float gt = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r), up = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r + 1);
+            st_coh(z + k * SK_SEG + cs * cu + r, sk_tagged(siluf(gt) * up, tag_z));
+          }
+          if (k >= 1 && k + 1 < nblk) {               // (not behind the last block: the down projection is waiting for this wave)
+            // (a wait that gives up has said so in *P.err: the next phase's wait ends the workgroup)
+            sk_stage_segments<true>(S.zs, z, F, k - 1, k, tag_z, P.err);
+            z_staged = k;
+            __hip_atomic_store(S.flag + 2, k, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
         }
       }
       if (s + 1 < nsegs && D <= 4096 && nx.gain != nullptr) sk_gains_to_lds(S.gs, nx.gain, D);   // (this phase's staging has read S.gs already)
@@ -1468,7 +1586,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
         tag_q ^= 1u;
         for (int r = lane; r < cur.nrows; r += 64) {
-          const float v = sk_row_sum(S.psum, r, cur.nseg, cur.nrows);
+          const float v = seg_row_sum(S.psum, cur, r);
           st_coh(out + cur.row0 + r, sk_tagged(v, tag_q));
         }
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
@@ -1477,7 +1595,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         if (P.tdbg && cur.kind == SEG_O && lane < cur.nrows) {
           float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
           dbg[cur.row0 + lane] = sk_untag(h_prev);
-          dbg[D + cur.row0 + lane] = sk_row_sum(S.psum, lane, cur.nseg, cur.nrows);
+          dbg[D + cur.row0 + lane] = seg_row_sum(S.psum, cur, lane);
         }
         if (P.tdbg && cur.kind == SEG_O && cu == ncu - 1) {
           float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
@@ -1485,22 +1603,33 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
 #endif
         if (lane < cur.nrows) {
-          const float v = sk_untag(sk_untag(h_prev) + sk_row_sum(S.psum, lane, cur.nseg, cur.nrows));
+          const float v = sk_untag(sk_untag(h_prev) + seg_row_sum(S.psum, cur, lane));
           st_coh(h + cur.row0 + lane, sk_tagged(v, tag_h));
           if (cur.kind == SEG_DN && P.h_out != nullptr) P.h_out[(size_t)b * D + cur.row0 + lane] = v;
         }
-      } else if (cur.kind == SEG_GU) {
+#ifdef SK_V_T1
+      } else if (cur.kind == SEG_GU && cur.blk_stride != 0) {
+        float* z = p.z + (size_t)b * F;
+        tag_z ^= 1u;
+        const int cs = cur.bl >> 1;
+        for (int r = lane; r < cur.nrows / 2; r += 64) {
+          const float gt = seg_row_sum(S.psum, cur, 2 * r), up = seg_row_sum(S.psum, cur, 2 * r + 1);
+          const int k = r / cs;
+          st_coh(z + k * SK_SEG + cs * cu + (r - k * cs), sk_tagged(siluf(gt) * up, tag_z));
+        }
+#endif
+      } else if (cur.kind == SEG_GU && cur.blk_stride == 0) {
         float* z = p.z + (size_t)b * F;
         tag_z ^= 1u;
         for (int r = lane; r < cur.nrows / 2; r += 64) {
-          const float gt = sk_row_sum(S.psum, 2 * r, cur.nseg, cur.nrows), up = sk_row_sum(S.psum, 2 * r + 1, cur.nseg, cur.nrows);
+          const float gt = seg_row_sum(S.psum, cur, 2 * r), up = seg_row_sum(S.psum, cur, 2 * r + 1);
           st_coh(z + cur.row0 / 2 + r, sk_tagged(siluf(gt) * up, tag_z));
         }
-      } else {
+      } else if (cur.kind == SEG_HEAD) {
         float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
-          const float v = sk_row_sum(S.psum, r, cur.nseg, cur.nrows);
+          const float v = seg_row_sum(S.psum, cur, r);
           if (lg) lg[cur.row0 + r] = v;
           const Best c{v, cur.row0 + r};
           if (better(c, best)) best = c;
@@ -1593,16 +1722,23 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       const int* staged = cur.kind == SEG_DN ? S.flag + 2 : nullptr;
       const bool ahead = !(nxt.kind == SEG_O && attn_wg && wave < A.nact);     // a wave with tiles requests its output-projection rows afterwards
       int seen = 1;
+#ifdef SK_V_T1
+      const bool progress = false;
+#else
+      const bool progress = cur.kind == SEG_GU && cur.blk_stride != 0;     // the service wave sends z out block by block
+#endif
       for (int r0 = 0; r0 < last0; r0 += SK_PD) {
 #pragma unroll
         for (int j = 0; j < SK_PD; ++j) {
           sk_consume(cur, r0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
+          if (progress && lane == 0) __hip_atomic_store(S.flag + 4 + wave, r0 + j + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
           sk_issue(cur, r0 + j + SK_PD, true, wave, buf[j]);
         }
       }
 #pragma unroll
       for (int j = 0; j < SK_PD; ++j) {
         sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
+        if (progress && lane == 0) __hip_atomic_store(S.flag + 4 + wave, last0 + j + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         sk_issue(nxt, j, ahead, wave, buf[j]);
         if (j == 0 && wave == 0) SK_XSTAMP(6);
         if (j == 0 && wave == 6) SK_XSTAMP(7);
