@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--per-op", action="store_true", help="one kernel per fused op instead of the persistent kernel")
     ap.add_argument("--sample", action="store_true",
                     help="also time the headline mask with the paper's decoding rule (temperature 0.8, top-k 10) instead of greedy")
+    ap.add_argument("--no-tpot-grid", action="store_true",
+                    help="skip the sweep over the paper's skip fractions (random and fixed-interval masks, 8B and 3B-class shapes)")
     ap.add_argument("--train-forward", action="store_true",
                     help="also time the training-side pieces: soft-skip forward + loss terms over the prompt, LoRA merge of the gate matrices")
     args = ap.parse_args()
@@ -60,7 +62,7 @@ def main():
 
     import torch
     import paper_2410_12513_amd as P
-    from synth import CONFIGS, WORKLOADS, make_prompt, make_router, make_skip_mask, make_weights
+    from synth import CONFIGS, WORKLOADS, make_interval_mask, make_prompt, make_router, make_skip_mask, make_weights
 
     wl = WORKLOADS[args.workload]
     desc = CONFIGS[wl["model"]]
@@ -79,7 +81,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.time() - t0
 
-    ctx = P.FirstContext(desc, weights, router, max_batch=1, max_seq_len=n_prompt + W + K + 16, stream=stream)
+    ctx = P.FirstContext(desc, weights, router, max_batch=1, max_seq_len=n_prompt + 2 * (W + K) + 160, stream=stream)
     if args.no_graph:
         ctx.set_option(1, 0)
     ctx.set_option(3, 0 if args.per_op else 1)       # persistent kernel or error: never a silent fallback
@@ -110,7 +112,8 @@ def main():
         by = step_bytes(desc, L - k, mid_ctx)
         sweep.append({"skip_fraction": k / L, "kept_layers": L - k, "tokens_per_s": 1000.0 / ms,
                       "ms_per_step": ms, "step_bytes": by,
-                      "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)})
+                      "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                      "per_step_ms": per_step_distribution(ctx, stream, tok, logits, min(K, 128))})
     head = min(sweep, key=lambda r: abs(r["skip_fraction"] - args.headline_skip))
 
     sampled = None
@@ -188,7 +191,9 @@ def main():
     if os.path.exists(tpath):
         try:
             traffic_detail = json.load(open(tpath)).get("k_step" if persistent else "k_gateup")
-            if traffic_detail and traffic_detail.get("kept_layers") == head["kept_layers"]:
+            # the counter runs describe the kernel as it was then: they count only while its source is unchanged
+            if traffic_detail and traffic_detail.get("kept_layers") == head["kept_layers"] and \
+               traffic_detail.get("kernel_source_sha256") == kernel_source_hash():
                 traffic = traffic_detail["bytes_per_launch"]
         except Exception:
             traffic, traffic_detail = None, None
@@ -211,9 +216,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    grid = None
+    if not args.no_tpot_grid and not args.per_op and args.workload == "cfg3_8b":
+        grid = tpot_grid(P, args, stream, (desc, weights, router, ctx))
+
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(desc, weights, router, head, seed)
+        cpu = cpu_baseline(desc, weights, router, head, seed, n_prompt)
 
     out = {
         "metric": "decode tokens/sec at skip fraction s, batch 1 (8B-class); % of HBM roofline",
@@ -227,6 +236,7 @@ def main():
                    "decode_path": "per-op kernels" if args.per_op else "persistent kernel"},
         "hbm_roofline_frac_step": head["hbm_frac"],
         "sweep": sweep,
+        "tpot_grid": grid,
         "sampled_decode": sampled,
         "train_forward": train,
         "prefill": {"tokens": n_prompt, "ms": prefill_ms,
@@ -238,6 +248,83 @@ def main():
     }
     ctx.close()
     print(json.dumps(out))
+
+
+def kernel_source_hash():
+    """sha256 of the sources of the decode kernels (what profiles/traffic.json was measured on)."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("step_kernel.h", "decode_kernels.h", "common.h"):
+        with open(os.path.join(ROOT, "paper_2410_12513_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def per_step_distribution(ctx, stream, tok, logits, n):
+    """Median and 10th / 90th percentile of n further decode steps, one event pair per step on the library's stream
+    (outside the timed region above: the events sit between the launches)."""
+    import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    evs[0].record(stream)
+    for i in range(n):
+        ctx.decode_step(tok, logits, tok)
+        evs[i + 1].record(stream)
+    evs[n].synchronize()
+    t = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n))
+    return {"n": n, "median": t[n // 2], "p10": t[n // 10], "p90": t[(9 * n) // 10]}
+
+
+def tpot_grid(P, args, stream, have):
+    """Time per output token against the fraction of layers skipped, on the paper's own grid (10 / 15 / 20 / 25 / 35 %:
+    Section 5.2) for the two model geometries it used, with random-skip and fixed-interval masks (the two mask rules
+    of its baselines, Section 5.1) fed through first_set_mask.  Shapes and masks only: no trained routers, no datasets.
+    `have` = (desc, weights, router, ctx) of the model the caller already built, reused for its workload."""
+    import torch
+    from synth import CONFIGS, WORKLOADS, make_interval_mask, make_prompt, make_router, make_skip_mask, make_weights
+    rows = []
+    K, W = 64, 8
+    for workload in ("cfg3_8b", "cfg3_3b"):
+        wl = WORKLOADS[workload]
+        desc = CONFIGS[wl["model"]]
+        seed, n_prompt, L = wl["seed"], wl["prompt"], desc.n_layers
+        if have is not None and have[0] is desc:
+            weights, router, ctx, own = have[1], have[2], have[3], False
+        else:
+            weights = make_weights(desc, seed, device="cuda")
+            router = make_router(desc, seed, device="cuda")
+            ctx = P.FirstContext(desc, weights, router, max_batch=1, max_seq_len=n_prompt + 2 * (W + K) + 16, stream=stream)
+            ctx.set_option(3, 0 if args.per_op else 1)
+            own = True
+        prompt = make_prompt(desc.vocab, n_prompt, seed).cuda()
+        logits = torch.zeros(1, desc.vocab, device="cuda")
+        tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        base = None
+        for frac in (0.0, 0.10, 0.15, 0.20, 0.25, 0.35):
+            k = int(round(frac * L))
+            for rule in (("none",) if k == 0 else ("random", "interval")):
+                mask = (make_interval_mask(L, k) if rule == "interval" else make_skip_mask(L, k, seed)).tolist()
+                ctx.prefill_route(prompt, [n_prompt], token=tok)
+                ctx.set_mask(0, mask)
+                for _ in range(W):
+                    ctx.decode_step(tok, logits, tok)
+                ctx.sync()
+                ev0.record(stream)
+                for _ in range(K):
+                    ctx.decode_step(tok, logits, tok)
+                ev1.record(stream)
+                ev1.synchronize()
+                ms = ev0.elapsed_time(ev1) / K
+                base = ms if k == 0 else base
+                by = step_bytes(desc, L - k, n_prompt + W + K // 2)
+                rows.append({"model": wl["model"], "layers": L, "skipped": k, "skip_fraction": k / L, "mask_rule": rule,
+                             "tpot_ms": ms, "tokens_per_s": 1000.0 / ms, "tpot_vs_no_skip": ms / base,
+                             "hbm_frac": by / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)})
+        if own:
+            ctx.close()
+            del weights, router, ctx
+            torch.cuda.empty_cache()
+    return rows
 
 
 def batch_step_bytes(desc, masks, ctx_lens):
@@ -323,9 +410,12 @@ def bench_batch(args, wl, desc):
     print(json.dumps(out))
 
 
-def cpu_baseline(desc, weights, router, head, seed):
-    """The CPU oracle, as it stands, on this machine's host cores: a short prefill (16 tokens, so
-    the run stays bounded) then decode steps of the same model and mask, timed."""
+def cpu_baseline(desc, weights, router, head, seed, n_ctx):
+    """The CPU oracle, as it stands, on this box's host cores, in its fp32 mode ("full precision"), on a bounded
+    sample of the same workload: decode steps of the same model and mask at the workload's context length.  The
+    oracle's own prompt pass over n_ctx tokens would take minutes on the 8B shape, so its state is set up by a
+    16-token prompt pass and the KV cache of every layer is then filled to n_ctx positions with seeded synthetic
+    keys / values (decode cost depends on the cache's length, not on its contents)."""
     import torch
     from oracle import first_oracle as O
     from synth import make_prompt, make_skip_mask
@@ -336,18 +426,25 @@ def cpu_baseline(desc, weights, router, head, seed):
     t_copy = time.time() - t0
     L = desc.n_layers
     mask = make_skip_mask(L, L - head["kept_layers"], seed)
-    st = O.prefill_route(desc, w_cpu, r_cpu, make_prompt(desc.vocab, 16, seed))
+    cdt = torch.float32
+    st = O.prefill_route(desc, w_cpu, r_cpu, make_prompt(desc.vocab, 16, seed), cdt=cdt)
     st.set_mask(mask)
+    g = torch.Generator().manual_seed(seed)
+    kv_dt = st.K[0].dtype
+    for i in range(L):
+        st.K[i] = (torch.randn(n_ctx, desc.n_kv_heads, desc.head_dim, generator=g) * 0.5).to(kv_dt)
+        st.V[i] = (torch.randn(n_ctx, desc.n_kv_heads, desc.head_dim, generator=g) * 0.5).to(kv_dt)
+    st.pos = n_ctx
     tok, n, t_dec = st.token, 0, 0.0
-    while n < 2 or (t_dec < 10.0 and n < 64):
+    while n < 2 or (t_dec < 12.0 and n < 64):
         t1 = time.time()
-        _, tok = O.decode_step(desc, w_cpu, st, tok)
+        _, tok = O.decode_step(desc, w_cpu, st, tok, cdt=cdt)
         t_dec += time.time() - t1
         n += 1
     return {"value": n / t_dec, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{n} decode steps of the same model and mask after a 16-token oracle prefill "
-                      f"(context 16 instead of the workload's prompt; fp64 arithmetic); weights copied "
-                      f"device->host in {t_copy:.1f} s"}
+            "sample": f"{n} decode steps of the same model and mask at context {n_ctx} (the oracle in its fp32 mode; its "
+                      f"state from a 16-token prompt pass, the cache of every layer then filled to {n_ctx} positions with "
+                      f"seeded synthetic keys / values); weights copied device->host in {t_copy:.1f} s"}
 
 
 if __name__ == "__main__":

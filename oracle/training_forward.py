@@ -28,7 +28,11 @@ Pins (tests/test_training_pins.py): routers that saturate to exactly 1.0 / 0.0 t
 pass into the hard-gated pass of Eq. 2 (built from the pinned layer function); the zero router
 gives the midpoint of stream and layer output; cross entropy against the library routine and
 the closed form ln V for a zero head; hand-worked values for L_Reg, L_PP, the total and a
-2 x 2 rank-1 merge; the merged matrix applied to a vector equals the two-branch LoRA forward.
+2 x 2 rank-1 merge; the merged matrix applied to a vector equals the two-branch LoRA forward;
+all_position_logits row by row against the main oracle's lm_logits (itself pinned by the
+all-skip closed form) and against the library's rms_norm + linear on a head and gains chosen so
+that a dropped norm, a dropped gain or a transposed head misses by orders of magnitude; the
+cross entropy of a soft pass with a scaled head (far from ln V) against the library routine.
 """
 from __future__ import annotations
 

@@ -1416,16 +1416,18 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   float* h = p.h + (size_t)b * D;
   // tags of the latest writes of h, qkv, attn (and the attention partials) and z: the same in every wave of the grid,
   // each flips when the phase that writes the vector begins
+  // (everything a workgroup has to read before it can start is requested together: one memory round trip)
   unsigned tag_h, tag_q, tag_a, tag_z, epoch;
+  int nk, pos, tok;
   {
-    const int* ts = P.tagstate + 8 * b;
-    tag_h = (unsigned)uni(ld_coh(ts)) & 1u; tag_q = (unsigned)uni(ld_coh(ts + 1)) & 1u;
-    tag_a = (unsigned)uni(ld_coh(ts + 2)) & 1u; tag_z = (unsigned)uni(ld_coh(ts + 3)) & 1u;
-    epoch = (unsigned)uni(ld_coh(ts + 4)) + 1u;
+    const int ts_v = ld_coh(P.tagstate + 8 * b + (lane & 7));      // lane l: word l of the slot's exchange state
+    const int nk_v = P.n_kept[b], pos_v = p.len[b], tok_v = p.tokens[b];
+    tag_h = (unsigned)__builtin_amdgcn_readlane(ts_v, 0) & 1u; tag_q = (unsigned)__builtin_amdgcn_readlane(ts_v, 1) & 1u;
+    tag_a = (unsigned)__builtin_amdgcn_readlane(ts_v, 2) & 1u; tag_z = (unsigned)__builtin_amdgcn_readlane(ts_v, 3) & 1u;
+    epoch = (unsigned)__builtin_amdgcn_readlane(ts_v, 4) + 1u;
+    nk = uni(nk_v); pos = uni(pos_v); tok = uni(tok_v);
   }
-  const int nk = uni(P.n_kept[b]);
   const int* kept = P.kept + (size_t)b * P.L;
-  const int pos = uni(p.len[b]);
   // attention: workgroup = (query head, key split), one 64-key tile per streaming wave where the grid allows
   const int tiles = (pos + 64) >> 6;
   int tps;
@@ -1454,7 +1456,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
 #endif
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
   {
-    int tok = uni(p.tokens[b]);
     tok = min(max(tok, 0), p.V - 1);
     const bf16* row = reinterpret_cast<const bf16*>(p.embed) + (size_t)tok * D;
     SegDesc e{};
@@ -1470,7 +1471,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
     if (service && attn_wg && A.s != 0) {
       float* dst = P.part + sk_part_index(p.Hq, HD, b, A.H, A.s);
       for (int i = lane; i < HD + 2; i += 64) st_coh(dst + i, sk_tagged(0.f, tag_a));
-      vm_wait_all();
+      // (this wave waits for all its memory operations many times before it stores the slot's first real contents)
     }
     for (int i = tid; i < HD / 2; i += SK_THREADS) {
       const double a = (double)pos * p.theta[i];

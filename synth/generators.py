@@ -59,6 +59,7 @@ CONFIGS: Dict[str, ModelDesc] = {
     "mini_bf16": ModelDesc(4, 512, 8, 2, 64, 1416, 2003, dtype="bf16"),
     "mini_fp32": ModelDesc(3, 256, 4, 2, 64, 696, 1001, dtype="fp32"),
     "mini_hd128": ModelDesc(3, 512, 4, 1, 128, 1032, 1500, dtype="bf16"),
+    "mini_8b_heads": ModelDesc(2, 512, 32, 8, 128, 1032, 1500, dtype="bf16"),    # the 8B head geometry (32 query / 8 KV heads) on a narrow model
     # widths that are multiples of 2048: shapes the persistent whole-step decode kernel accepts
     "step_hd128": ModelDesc(3, 2048, 16, 4, 128, 4096, 5003, dtype="bf16"),
     "step_hd64": ModelDesc(2, 2048, 32, 8, 64, 2048, 3001, dtype="bf16"),
@@ -154,6 +155,19 @@ def make_skip_mask(n_layers: int, n_skip: int, seed: int) -> torch.Tensor:
     if n_skip:
         idx = rng.choice(np.arange(1, n_layers - 1), size=n_skip, replace=False)
         mask[idx] = 0
+    return torch.from_numpy(mask)
+
+
+def make_interval_mask(n_layers: int, n_skip: int) -> torch.Tensor:
+    """uint8 [L] keep mask with n_skip zeros at (as nearly as integers allow) equal intervals over the interior layers
+    1..L-2: the fixed-interval rule of the paper's baselines (Section 5.1)."""
+    if n_skip < 0 or n_skip > max(0, n_layers - 2):
+        raise ValueError("n_skip must lie in [0, L-2]")
+    mask = np.ones(n_layers, dtype=np.uint8)
+    inner = n_layers - 2
+    for i in range(n_skip):
+        mask[1 + ((2 * i + 1) * inner) // (2 * n_skip)] = 0
+    assert int((mask == 0).sum()) == n_skip
     return torch.from_numpy(mask)
 
 

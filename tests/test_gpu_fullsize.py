@@ -18,7 +18,13 @@ pytestmark = pytest.mark.gpu
 torch.set_grad_enabled(False)
 
 
-def _run(workload, n_skip, n_steps):
+RHO_TOL = {"bf16": 5e-4, "fp32": 1e-5}     # measured: 2.3e-4 on the 8B shape (activations enter the prompt GEMMs with 16 mantissa bits)
+
+
+def _run(workload, skips, n_steps):
+    """One oracle prompt pass, then for every mask of `skips` skipped layers a fresh prompt pass of the library and
+    n_steps teacher-forced decode steps against a copy of the oracle's state."""
+    import copy
     import paper_2410_12513_amd as P
     wl = WORKLOADS[workload]
     desc = CONFIGS[wl["model"]]
@@ -35,55 +41,73 @@ def _run(workload, n_skip, n_steps):
     ctx.set_option(3, 1)                                  # persistent kernel or error: no silent fallback
     logits = torch.zeros(1, desc.vocab, device="cuda")
     rho = torch.zeros(1, L, device="cuda")
+    gmask = torch.zeros(1, L, dtype=torch.uint8, device="cuda")
     tok = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ctx.prefill_route(prompt.cuda(), [n_prompt], rho=rho, logits=logits, token=tok)
+    ctx.prefill_route(prompt.cuda(), [n_prompt], rho=rho, mask=gmask, logits=logits, token=tok)
     first_logits = logits.cpu().clone()
-    st = O.prefill_route(desc, w, router, prompt, progress=progress)
-    # routers of this recipe sit close to 0.5: compare rho itself; masks where the margin allows
-    d_rho = (rho.cpu()[0] - st.rho).abs()
-    assert float(d_rho.max()) <= 1e-3
-    ok, ma, rel = logits_close(first_logits[0], st.logits, desc.dtype)
-    progress(f"{workload}: prefill logits max|d|={ma:.2e} rel={rel:.2e} max|d rho|={float(d_rho.max()):.1e}")
+    st0 = O.prefill_route(desc, w, router, prompt, progress=progress)
+    # routers of this recipe sit close to 0.5: rho itself within the measured bar, and the decision bit-exact on every
+    # layer whose oracle score is further from the threshold than that bar
+    d_rho = (rho.cpu()[0] - st0.rho).abs()
+    assert float(d_rho.max()) <= RHO_TOL[desc.dtype], float(d_rho.max())
+    decided = (st0.rho - 0.5).abs() > 2 * RHO_TOL[desc.dtype]
+    assert int(decided.sum()) >= L // 4, "the margin rule leaves too few layers to compare"
+    assert torch.equal(gmask.cpu()[0][decided], st0.mask.to(torch.uint8)[decided])
+    assert ctx.get_kept(0) == [i for i in range(L) if int(gmask[0, i])]
+    ok, ma, rel = logits_close(first_logits[0], st0.logits, desc.dtype)
+    progress(f"{workload}: prefill logits max|d|={ma:.2e} rel={rel:.2e} max|d rho|={float(d_rho.max()):.1e} "
+             f"masks compared on {int(decided.sum())} of {L} layers")
     assert ok, (ma, rel)
-    if top2_gap(st.logits) > 2 * ma:
-        assert int(tok[0]) == st.token
-    mask = make_skip_mask(L, n_skip, seed).tolist()
-    ctx.set_mask(0, mask)
-    st.set_mask(mask)
-    assert ctx.get_kept(0) == O.compact_kept(mask)
-    tin = torch.zeros(1, dtype=torch.int32, device="cuda")
-    t, worst = st.token, 0.0
-    for s in range(n_steps):
-        tin[0] = t
-        ctx.decode_step(tin, logits, tok)
-        ctx.sync()
-        ref, ref_tok = O.decode_step(desc, w, st, t)
-        ok, ma, rel = logits_close(logits[0], ref, desc.dtype)
-        worst = max(worst, ma)
-        progress(f"{workload}: decode step {s} max|d|={ma:.2e} rel={rel:.2e}")
-        assert ok, (s, ma, rel)
-        assert int(tok[0]) == int(torch.argmax(logits[0]))
-        if top2_gap(ref) > 2 * ma:
-            assert int(tok[0]) == ref_tok
-        t = ref_tok
-    assert ctx.seq_len(0) == n_prompt + n_steps
-    # kept layers appended KV equal to the oracle's; skipped layers hold only the prompt
-    i_kept, i_skip = O.compact_kept(mask)[1], mask.index(0) if 0 in mask else None
-    k, _ = ctx.kv_read(0, i_kept, n_prompt, n_steps)
-    kr = st.K[i_kept][n_prompt:].double()
-    assert float((k.cpu().double() - kr).norm() / kr.norm()) <= 1.5e-2
-    if i_skip is not None:
-        assert st.K[i_skip].shape[0] == n_prompt
+    if top2_gap(st0.logits) > 2 * ma:
+        assert int(tok[0]) == st0.token
+    worst = 0.0
+    for n_skip in skips:
+        if n_skip != skips[0]:
+            ctx.prefill_route(prompt.cuda(), [n_prompt], token=tok)      # a mask may only lose layers once decoding began
+        st = copy.deepcopy(st0)
+        mask = make_skip_mask(L, n_skip, seed).tolist()
+        ctx.set_mask(0, mask)
+        st.set_mask(mask)
+        assert ctx.get_kept(0) == O.compact_kept(mask)
+        tin = torch.zeros(1, dtype=torch.int32, device="cuda")
+        t = st.token
+        for s in range(n_steps):
+            tin[0] = t
+            ctx.decode_step(tin, logits, tok)
+            ctx.sync()
+            ref, ref_tok = O.decode_step(desc, w, st, t)
+            ok, ma, rel = logits_close(logits[0], ref, desc.dtype)
+            worst = max(worst, ma)
+            progress(f"{workload}: {n_skip} skipped, decode step {s} max|d|={ma:.2e} rel={rel:.2e}")
+            assert ok, (n_skip, s, ma, rel)
+            assert int(tok[0]) == int(torch.argmax(logits[0]))
+            if top2_gap(ref) > 2 * ma:
+                assert int(tok[0]) == ref_tok
+            t = ref_tok
+        assert ctx.seq_len(0) == n_prompt + n_steps
+        # kept layers appended KV equal to the oracle's; skipped layers hold only the prompt
+        i_kept, i_skip = O.compact_kept(mask)[1], mask.index(0) if 0 in mask else None
+        k, _ = ctx.kv_read(0, i_kept, n_prompt, n_steps)
+        kr = st.K[i_kept][n_prompt:].double()
+        assert float((k.cpu().double() - kr).norm() / kr.norm()) <= 1.5e-2
+        if i_skip is not None:
+            assert st.K[i_skip].shape[0] == n_prompt
     ctx.close()
     return worst
 
 
 def test_cfg2_1b_full_size():
-    _run("cfg2_1b", 4, 6)
+    _run("cfg2_1b", [4], 6)
 
 
-def test_cfg3_8b_full_size_quarter_skipped():
-    _run("cfg3_8b", 8, 3)
+def test_cfg3_8b_full_size_three_masks():
+    """The three masks the benchmark reports (0, 8 and 16 of 32 layers skipped) on one oracle prompt pass."""
+    _run("cfg3_8b", [0, 8, 16], 2)
+
+
+def test_cfg3_3b_full_size():
+    """The paper's second model geometry (28 layers, widths 3072 / 8192: partial row segments in the persistent kernel)."""
+    _run("cfg3_3b", [7], 2)
 
 
 def test_cfg4_8b_b16_full_size_sampled_sequences():
@@ -123,7 +147,7 @@ def test_cfg4_8b_b16_full_size_sampled_sequences():
     states = {}
     for b in picked:
         st = O.prefill_route(desc, w, router, prompts[b], progress=progress)
-        assert float((rho.cpu()[b] - st.rho).abs().max()) <= 1e-3
+        assert float((rho.cpu()[b] - st.rho).abs().max()) <= RHO_TOL[desc.dtype]
         ok, ma, rel = logits_close(first[b], st.logits, desc.dtype)
         progress(f"cfg4: sequence {b} (prompt {lens[b]}, {skips[b]} skipped) prefill logits max|d|={ma:.2e} rel={rel:.2e}")
         assert ok, (b, ma, rel)

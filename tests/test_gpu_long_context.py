@@ -74,3 +74,32 @@ def test_batched_decode_with_one_long_and_one_short_sequence():
             assert ok, (b, s, ma, rel)
     assert [ctx.seq_len(0), ctx.seq_len(1)] == [n_ctx + 3, 43]
     ctx.close()
+
+
+def test_batched_decode_with_the_8b_head_geometry_at_16k_keys():
+    """The batched path's matrix-core attention (4 query heads per KV head, head dimension 128) with the 8B head counts
+    (32 / 8) over 16 384 written positions, two sequences of very different length in one launch."""
+    desc = CONFIGS["mini_8b_heads"]
+    prompts = [make_prompt(desc.vocab, 24, 86), make_prompt(desc.vocab, 300, 87)]
+    n_ctx = 16384
+    desc, w, router, ctx = build("mini_8b_heads", 86, max_batch=2, max_seq_len=n_ctx + 16)
+    ctx.set_option(6, 1)                                  # shared pass or an error
+    sts = [O.prefill_route(desc, w, router, p) for p in prompts]
+    _prefill(ctx, desc, prompts)
+    masks = [[1, 1], [1, 1]]
+    for b, m in enumerate(masks):
+        ctx.set_mask(b, m)
+        sts[b].set_mask(m)
+    _fill(ctx, sts[0], desc, 0, n_ctx, 88)
+    forced = [[7, 9], [11, 13], [15, 17]]
+    refs = [O.generate(desc, w, sts[b], 3, forced=[row[b] for row in forced]) for b in range(2)]
+    lg, tk = _decode(ctx, desc, forced, B=2)
+    for b in range(2):
+        for s in range(3):
+            ok, ma, rel = logits_close(lg[s, b], refs[b][0][s], desc.dtype)
+            assert ok, (b, s, ma, rel)
+    assert [ctx.seq_len(0), ctx.seq_len(1)] == [n_ctx + 3, 303]
+    k, v = ctx.kv_read(0, 1, n_ctx, 3)
+    kr = sts[0].K[1][n_ctx:].double()
+    assert float((k.cpu().double() - kr).norm() / kr.norm()) <= 1.5e-2
+    ctx.close()

@@ -70,6 +70,39 @@ def test_soft_forward_and_loss_terms_match_oracle(model, lens):
     ctx.close()
 
 
+@pytest.mark.parametrize("model,n", [("mini_bf16", 131), ("mini_fp32", 40), ("step_hd128", 150)])
+def test_cross_entropy_sees_the_lm_head(model, n):
+    """With N(0, 0.02) weights the cross entropy sits within 0.1 of ln V whatever the logits are, so the bar above barely
+    sees the head.  Here the head is scaled by 12 and the final-norm gains are spread over [0.5, 1.5): the loss is far
+    from ln V, and it is compared with the oracle's head and cross entropy applied to the hidden states THE LIBRARY
+    returned - what is left is the error of the library's own norm + head + loss, a few fp32 roundings of logits of
+    size ~10 (the bf16 head weights are exact on both sides, activations enter with 16 mantissa bits) - and with the
+    whole oracle pass at a bar derived from the hidden-state tolerance."""
+    desc = CONFIGS[model]
+    w = make_weights(desc, 99)
+    g = torch.Generator().manual_seed(99)
+    w["lm_head"] = (w["lm_head"].float() * 12.0).to(w["lm_head"].dtype)
+    w["final_norm"] = 0.5 + torch.rand(desc.d_model, generator=g)
+    router = make_router(desc, 99, std=1.5)
+    ctx = P.FirstContext(desc, to_device(w, "cuda"), router.cuda(), max_batch=1, max_seq_len=n + 8)
+    prompt = make_prompt(desc.vocab, n, 99)
+    tg = _targets(prompt, holes=(3,))
+    got = _soft(ctx, desc, [prompt], [tg], 0.0, 0.0)
+    ce = float(got["terms"][0][0])
+    lg_own = TF.all_position_logits(desc, w, got["hidden"].double())
+    ce_own = float(TF.cross_entropy(lg_own, tg))
+    assert abs(ce_own - math.log(desc.vocab)) > 0.05                       # the head is visible in the loss
+    scale = float(lg_own.abs().max())
+    assert abs(ce - ce_own) <= 2 * 1e-4 * scale, (ce, ce_own, scale)       # |dCE| <= 2 max|dlogit|, logits to ~1e-5 relative
+    ref = TF.loss_terms(desc, w, router, prompt, tg, 0.0, 0.0)
+    rel_h = float((got["hidden"].double() - ref["hidden"]).norm() / ref["hidden"].norm())
+    assert rel_h <= TOL[desc.dtype]["rel"]
+    # hidden states off by rel_h (L2) move a logit by at most about rel_h * sqrt(D) * |logit| in the worst case; the
+    # observed effect is far smaller, so the bar is 2 * 8 * rel_h * scale
+    assert abs(ce - float(ref["ce"])) <= 16 * max(rel_h, 1e-6) * scale, (ce, float(ref["ce"]), rel_h, scale)
+    ctx.close()
+
+
 def test_zero_router_saturated_router_and_no_targets():
     desc = CONFIGS["mini_bf16"]
     L = desc.n_layers

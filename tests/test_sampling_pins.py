@@ -106,3 +106,30 @@ def test_fp32_decisions_equal_fp64_away_from_boundaries():
             assert S.sample_top_k(logits, u, 0.8, 10, np.float32) == S.sample_top_k(logits, u, 0.8, 10, np.float64)
             same += 1
     assert same > 180
+
+
+def test_decision_margin_against_a_brute_force_twin_and_by_hand():
+    """decision_margin decides which draws the GPU test holds to an exact token.  Twin: sort the softmax
+    probabilities of the k largest logits (library sort and softmax), accumulate, and take the distance from u to
+    the nearest inner edge.  By hand: probabilities 4/7, 2/7, 1/7 have inner edges 4/7 and 6/7."""
+    logits = np.log(np.array([1.0, 4.0, 2.0], dtype=np.float64))            # candidates in order: 1, 2, 0
+    for u, want in ((0.5, 4 / 7 - 0.5), (0.6, 0.6 - 4 / 7), (0.8, 6 / 7 - 0.8), (0.0, 4 / 7), (0.99, 0.99 - 6 / 7)):
+        assert abs(S.decision_margin(logits, u, 1.0, 3) - want) <= 1e-12
+    assert S.decision_margin(logits, 0.3, 1.0, 1) == 1.0                     # one candidate: no edge to cross
+    rng = np.random.default_rng(31)
+    for _ in range(100):
+        V, k, T = int(rng.integers(2, 300)), int(rng.integers(1, 20)), float(rng.uniform(0.2, 2.0))
+        lg = (rng.normal(size=V) * 3).astype(np.float64)
+        u = float(rng.random())
+        order = np.argsort(-lg, kind="stable")[:min(k, V)]
+        z = lg[order] / T
+        p = np.exp(z - z.max()); p /= p.sum()
+        edges = np.cumsum(p)[:-1]
+        want = float(np.min(np.abs(edges - u))) if len(edges) else 1.0
+        assert abs(S.decision_margin(lg, u, T, k) - want) <= 1e-12
+        # what the margin promises: moving u by less than the margin does not change the sampled token
+        m = S.decision_margin(lg, u, T, k)
+        if m < 1.0 and m > 1e-9:
+            for du in (-0.9 * m, 0.9 * m):
+                if 0.0 <= u + du < 1.0:
+                    assert S.sample_top_k(lg, u + du, T, k) == S.sample_top_k(lg, u, T, k)

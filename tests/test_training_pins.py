@@ -174,3 +174,58 @@ def test_lora_merge_by_hand_and_against_the_two_branch_forward():
     assert mb.dtype == torch.bfloat16
     assert torch.equal(mb, (Wb.double() + 4.0 * (B @ A)).to(torch.bfloat16))
     assert not torch.equal(mb, (Wb + (4.0 * (B @ A)).to(torch.bfloat16)))    # not two roundings
+
+
+def _scaled_weights(desc, seed, scale=6.0):
+    """Synthetic weights blown up so that logits and the cross entropy move well away from 0 / ln V, with norm gains
+    that are not all one (a dropped or misplaced gain must show)."""
+    w = make_weights(desc, seed)
+    g = torch.Generator().manual_seed(seed)
+    w["lm_head"] = (w["lm_head"].float() * scale).to(w["lm_head"].dtype)
+    w["final_norm"] = 0.5 + torch.rand(desc.d_model, generator=g)
+    return w
+
+
+def test_all_position_logits_against_the_pinned_single_row_head_and_a_library_twin():
+    """all_position_logits is what the cross entropy sees.  Two things it shares no code with: the main oracle's
+    lm_logits (pinned by the all-skip closed form), row by row on the same hidden states; and the library's
+    rms_norm + linear on weights whose final-norm gains differ from one and whose head is large enough that a
+    missing norm, a missing gain or a transposed head changes every logit by far more than the bar."""
+    desc = CONFIGS["mini_bf16"]
+    w = _scaled_weights(desc, 93)
+    g = torch.Generator().manual_seed(5)
+    H = torch.randn(7, desc.d_model, generator=g, dtype=F64) * 3.0
+    got = TF.all_position_logits(desc, w, H)
+    assert got.shape == (7, desc.vocab)
+    for j in range(7):
+        row = O.lm_logits(desc, w, H[j], F64).to(F64)                      # (returned as fp32)
+        assert float((got[j] - row).abs().max()) <= 1e-5 * float(row.abs().max())
+    twin = F.linear(F.rms_norm(H, (desc.d_model,), w["final_norm"].to(F64), desc.rms_eps), w["lm_head"].to(F64))
+    assert float((got - twin).abs().max()) <= 1e-12 * float(twin.abs().max())
+    assert float(got.abs().max()) > 1.0                                      # not vacuous
+    # the mistakes the pin is there for are far outside the bar
+    no_norm = H @ w["lm_head"].to(F64).T
+    no_gain = F.linear(F.rms_norm(H, (desc.d_model,), None, desc.rms_eps), w["lm_head"].to(F64))
+    assert float((got - no_norm).abs().max()) > 1e-2 and float((got - no_gain).abs().max()) > 1e-2
+    # scale invariance of RMSNorm: the logits do not move when the stream is scaled (up to eps)
+    big = TF.all_position_logits(desc, w, H * 64.0)
+    assert float((big - got).abs().max()) <= 1e-4 * float(got.abs().max())
+
+
+def test_cross_entropy_of_the_soft_pass_departs_from_ln_v_and_matches_the_library():
+    """With a scaled head the loss is nowhere near ln V, so agreement with the library's cross entropy on the
+    oracle's own logits (and position by position) says something about those logits."""
+    desc = CONFIGS["mini_bf16"]
+    w = _scaled_weights(desc, 94, scale=12.0)
+    router = make_router(desc, 94)
+    ids = make_prompt(desc.vocab, 11, 94)
+    targets = make_prompt(desc.vocab, 11, 95).long()
+    targets[3] = -1
+    out = TF.loss_terms(desc, w, router, ids, targets, 0.01, 0.1)
+    lg = TF.all_position_logits(desc, w, out["hidden"])
+    lib = F.cross_entropy(lg, targets, ignore_index=-1, reduction="mean")
+    assert abs(float(out["ce"]) - float(lib)) <= 1e-10 * abs(float(lib))
+    assert abs(float(out["ce"]) - math.log(desc.vocab)) > 0.05                # the head is visible in the loss
+    per_pos = F.cross_entropy(lg, targets, ignore_index=-1, reduction="none")
+    keep = targets >= 0
+    assert abs(float(per_pos[keep].mean()) - float(out["ce"])) <= 1e-10
