@@ -45,11 +45,16 @@ extern "C" {
 #define FIRST_DTYPE_BF16 1
 
 /* options for first_set_option */
-#define FIRST_OPT_USE_GRAPH     1  /* 1 (default): replay a cached hipGraph per mask; 0: eager launches */
+#define FIRST_OPT_USE_GRAPH     1  /* 1 (default): a decode step is a cached hipGraph (one per set of masks on the per-op and batched
+                                      paths; a single one on the persistent path, whose kernel reads the kept layers from
+                                      the device); 0: eager launches */
 #define FIRST_OPT_ATTN_SPLITS   2  /* KV splits per (sequence, KV head) in decode attention; 0 = auto   */
 #define FIRST_OPT_DECODE_PATH   3  /* -1 (default): persistent whole-step kernel when the model fits it
                                       (bf16, widths multiples of 256, one live sequence), else per-op
-                                      kernels; 0: always per-op kernels; 1: persistent kernel or error */
+                                      kernels; 0: always per-op kernels; 1: persistent kernel or error.
+                                      When device memory allows, first_create gives the persistent kernel a copy of every
+                                      layer's down-projection matrix with permuted columns (as much memory again as those
+                                      matrices); the caller's matrices must then not change after first_create. */
 
 #define FIRST_OPT_STEP_TIMING   4  /* 1: the persistent kernel records per-phase timestamps (first_step_timing) */
 #define FIRST_OPT_BATCH_TILED   9  /* batched decode: 1 (default when max_batch > 1 and device memory allows) = the mat-vecs
@@ -155,7 +160,9 @@ int first_get_kept(first_ctx *ctx, int32_t seq, int32_t *kept_idx, int32_t *n_ke
  * launched, leave h bit-identical and never touch their KV; then final norm, LM head and
  * greedy argmax.  len[b] grows by one.
  *   last_tokens DEV int32 [B]; logits_out DEV fp32 [B, V] (may be NULL); token_out DEV int32 [B].
- * FIRST_ERR_STATE before prefill, FIRST_ERR_CAPACITY when a sequence is full. */
+ * FIRST_ERR_STATE before prefill, FIRST_ERR_CAPACITY when a sequence is full or no KV page is left (checked for
+ * every sequence before any page is handed out: a refusal changes nothing).  The token ids live on the device, where
+ * the host cannot see them: an id outside [0, vocab) is clamped to that range by the kernels, not refused. */
 int first_decode_step(first_ctx *ctx, const int32_t *last_tokens, float *logits_out,
                       int32_t *token_out);
 
@@ -195,7 +202,12 @@ int first_sample_top_k_static(void *hip_stream, const float *logits, int32_t n_s
                               int32_t *token_out, int32_t *candidates_out);
 
 int first_set_option(first_ctx *ctx, int32_t option, int32_t value);
-int first_sync(first_ctx *ctx);                          /* hipStreamSynchronize of the stream */
+/* hipStreamSynchronize of the stream.  The workgroups of the persistent decode kernel wait for each other with bounded
+ * waits; one that gives up (it should never happen: it means part of the grid was not running) makes every later
+ * launch leave at its first wait, so tokens and logits stop changing.  first_sync - and every other entry point that
+ * synchronises the stream: first_get_kept, first_seq_len, first_get_hidden, first_kv_read / first_kv_write - reports
+ * this once as FIRST_ERR_HIP and resets the exchange state; the steps since the failed wait must be repeated. */
+int first_sync(first_ctx *ctx);
 const char *first_last_error(const first_ctx *ctx);      /* ctx may be NULL: last create error */
 
 /* ---- inspection taps used by the parity tests (synchronise the stream) ------------------ */

@@ -122,7 +122,9 @@ struct first_ctx {
   size_t step_lds = 0;
   // options and graph cache
   int use_graph = 1, attn_splits = 0, decode_path = -1;   // -1: persistent kernel when possible
-  std::map<std::string, hipGraphExec_t> graphs;
+  struct CachedGraph { hipGraphExec_t exec; unsigned long long used; };
+  std::map<std::string, CachedGraph> graphs;
+  unsigned long long graph_clock = 0;
 };
 
 namespace {
@@ -210,7 +212,6 @@ void release_sequences(first_ctx* c) {
 hipError_t make_permuted_down_copies(first_ctx* c) {
   const first_model_desc& d = c->d;
   if (!sk_zperm_fits(d.d_ffn, d.d_model, c->num_cu)) return hipSuccess;
-  if (getenv("FIRST_ZPERM") && atoi(getenv("FIRST_ZPERM")) == 0) return hipSuccess;   // (experiment)
   const size_t per_layer = (size_t)d.d_model * d.d_ffn * sizeof(bf16);
   size_t free_b = 0, total_b = 0;
   if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < per_layer * d.n_layers + ((size_t)4 << 30)) return hipSuccess;
@@ -238,9 +239,27 @@ hipError_t upload_layer_table(first_ctx* c) {
   return hipMemcpy(c->d_layers, ld.data(), L * sizeof(LayerDev), hipMemcpyHostToDevice);
 }
 
+// (an executable graph may still be running on the stream: wait before destroying it)
 void drop_graphs(first_ctx* c) {
-  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
+  if (c->graphs.empty()) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second.exec);
   c->graphs.clear();
+}
+
+// A wait between workgroups of the persistent kernel that gave up says so in d_err; every later launch then leaves at
+// its first wait.  Called by the entry points that have just synchronised the stream: reports it once and starts the
+// exchange state afresh.
+int check_step_error(first_ctx* c, const char* who) {
+  int err = 0;
+  HIPCHK(c, hipMemcpy(&err, c->d_err, sizeof(int), hipMemcpyDeviceToHost));
+  if (err) {
+    (void)hipMemset(c->d_err, 0, 4 * sizeof(int));
+    (void)reset_tagged_exchange(c);
+    return fail(c, FIRST_ERR_HIP, std::string(who) + ": a wait between workgroups of the persistent decode kernel gave up; "
+                                  "the tokens and logits of the steps since are not valid");
+  }
+  return FIRST_OK;
 }
 
 DecParams base_params(const first_ctx* c, int b, int S) {
@@ -541,6 +560,11 @@ void enqueue_decode_batched(first_ctx* c, const int* tokens, float* logits, int*
   }
 }
 
+// The instantiation of the persistent kernel for this context's head dimension.
+const void* step_kernel_fn(const first_ctx* c) {
+  return c->d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>) : reinterpret_cast<const void*>(&k_step<64>);
+}
+
 // One decode token of the single live sequence as one persistent kernel.
 void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, int* token_out) {
   StepParams P{};
@@ -551,8 +575,8 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.tagstate = c->d_tagstate; P.h_out = c->d_h; P.part = c->x_part; P.zperm = c->zperm ? 1 : 0;
   P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
-  if (c->d.head_dim == 128) hipLaunchKernelGGL(k_step<128>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
-  else hipLaunchKernelGGL(k_step<64>, dim3(c->num_cu), dim3(SK_THREADS), c->step_lds, c->stream, P);
+  hipLaunchKernelGGL(reinterpret_cast<void (*)(StepParams)>(const_cast<void*>(step_kernel_fn(c))), dim3(c->num_cu), dim3(SK_THREADS),
+                     c->step_lds, c->stream, P);
 }
 
 // Does the geometry fit the persistent kernel's static work split?
@@ -896,7 +920,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
       e = make_permuted_down_copies(c);
       if (e == hipSuccess) e = upload_layer_table(c);
       c->step_lds = sk_lds_floats(d.d_model, c->nq, d.d_ffn, c->G, d.head_dim) * sizeof(float);
-      const void* fn = d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>) : reinterpret_cast<const void*>(&k_step<64>);
+      const void* fn = step_kernel_fn(c);
       if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->step_lds);
       int per_cu = 0;
       if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, SK_THREADS, c->step_lds);
@@ -1015,7 +1039,7 @@ int first_get_kept(first_ctx* c, int32_t seq, int32_t* kept_idx, int32_t* n_kept
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(kept_idx, c->d_kept + (size_t)seq * L, L * sizeof(int), hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(n_kept, c->d_nkept + seq, sizeof(int), hipMemcpyDeviceToHost));
-  return FIRST_OK;
+  return check_step_error(c, "first_get_kept");
 }
 
 int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_out, int32_t* token_out) {
@@ -1027,15 +1051,6 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   for (int b = 0; b < c->B; ++b) {
     if (c->hlen[b] + 1 > c->d.max_seq_len) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: sequence is full");
     max_len = std::max(max_len, c->hlen[b]);
-  }
-  // make sure the page that will receive position len[b] exists
-  for (int b = 0; b < c->B; ++b) {
-    if (c->hlen[b] / P >= c->seq_npages[b]) {
-      const int slot = alloc_page(c, b);
-      if (slot < 0) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: out of KV pages");
-      hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, c->stream, c->d_page_table + (size_t)b * c->max_pages + slot,
-                         c->h_page_table[(size_t)b * c->max_pages + slot]);
-    }
   }
   int S = c->attn_splits;
   if (S <= 0) S = (max_len + 128 + 127) / 128;
@@ -1050,6 +1065,24 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   if (c->batch_path == 1 && !persistent && !batched)
     return fail(c, FIRST_ERR_STATE, "first_decode_step: the batched path needs a bf16 model whose widths are multiples of 8 "
                                     "and more than one live sequence");
+  // the page that will receive position len[b] must exist: count what is missing before handing anything out, so
+  // that a refusal leaves every sequence as it was
+  {
+    int need = 0;
+    for (int b = 0; b < c->B; ++b)
+      if (c->hlen[b] / P >= c->seq_npages[b]) {
+        if (c->seq_npages[b] >= c->max_pages) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: out of KV pages");
+        ++need;
+      }
+    if (need > (int)c->free_pages.size()) return fail(c, FIRST_ERR_CAPACITY, "first_decode_step: out of KV pages");
+  }
+  for (int b = 0; b < c->B; ++b) {
+    if (c->hlen[b] / P >= c->seq_npages[b]) {
+      const int slot = alloc_page(c, b);
+      hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, c->stream, c->d_page_table + (size_t)b * c->max_pages + slot,
+                         c->h_page_table[(size_t)b * c->max_pages + slot]);
+    }
+  }
   auto enqueue = [&]() {
     if (persistent) enqueue_decode_step_kernel(c, last_tokens, logits_out, token_out);
     else if (batched) enqueue_decode_batched(c, last_tokens, logits_out, token_out, S);
@@ -1070,17 +1103,34 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
       for (int b = 0; b < c->B; ++b) key.append(reinterpret_cast<const char*>(c->hmask[b].data()), c->hmask[b].size());
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
-      if (c->graphs.size() >= 32) drop_graphs(c);
+      if (c->graphs.size() >= 32) {
+        // make room for one: the least recently used entry goes (it may still be running: wait first)
+        auto old = c->graphs.begin();
+        for (auto g = c->graphs.begin(); g != c->graphs.end(); ++g)
+          if (g->second.used < old->second.used) old = g;
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        (void)hipGraphExecDestroy(old->second.exec);
+        c->graphs.erase(old);
+      }
       hipGraph_t graph = nullptr;
       hipGraphExec_t exec = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
       enqueue();
-      HIPCHK(c, hipStreamEndCapture(c->stream, &graph));
-      HIPCHK(c, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+      const hipError_t e_launch = hipGetLastError();
+      const hipError_t e_end = hipStreamEndCapture(c->stream, &graph);      // (also what abandons a capture that went wrong)
+      if (e_launch != hipSuccess || e_end != hipSuccess) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return fail(c, FIRST_ERR_HIP, std::string("first_decode_step: graph capture: ") +
+                                          hipGetErrorString(e_launch != hipSuccess ? e_launch : e_end));
+      }
+      const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
       (void)hipGraphDestroy(graph);
-      it = c->graphs.emplace(key, exec).first;
+      if (e_inst != hipSuccess)
+        return fail(c, FIRST_ERR_HIP, std::string("first_decode_step: hipGraphInstantiate: ") + hipGetErrorString(e_inst));
+      it = c->graphs.emplace(key, first_ctx::CachedGraph{exec, 0}).first;
     }
-    HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+    it->second.used = ++c->graph_clock;
+    HIPCHK(c, hipGraphLaunch(it->second.exec, c->stream));
   }
   for (int b = 0; b < c->B; ++b) { c->hlen[b] += 1; c->decoded[b] = 1; }
   return FIRST_OK;
@@ -1172,15 +1222,7 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
 int first_sync(first_ctx* c) {
   if (!c) return FIRST_ERR_ARG;
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  int err = 0;
-  HIPCHK(c, hipMemcpy(&err, c->d_err, sizeof(int), hipMemcpyDeviceToHost));
-  if (err) {
-    // the exchange state is undefined after a wait that gave up: start it afresh
-    (void)hipMemset(c->d_err, 0, 4 * sizeof(int));
-    (void)reset_tagged_exchange(c);
-    return fail(c, FIRST_ERR_HIP, "first_sync: a wait between workgroups of the persistent decode kernel gave up");
-  }
-  return FIRST_OK;
+  return check_step_error(c, "first_sync");
 }
 
 const char* first_last_error(const first_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
@@ -1191,7 +1233,7 @@ int first_seq_len(first_ctx* c, int32_t seq, int32_t* len_out) {
   if (seq < 0 || seq >= c->B) return fail(c, FIRST_ERR_STATE, "first_seq_len: no such live sequence");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(len_out, c->d_len + seq, sizeof(int), hipMemcpyDeviceToHost));
-  return FIRST_OK;
+  return check_step_error(c, "first_seq_len");
 }
 
 int first_batch(first_ctx* c, int32_t* batch_out) {
@@ -1221,7 +1263,7 @@ static int kv_tap(first_ctx* c, int seq, int layer, int pos0, int n, float* k, f
   }
   HIPCHK(c, hipGetLastError());
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  return FIRST_OK;
+  return check_step_error(c, "first_kv");
 }
 
 int first_kv_read(first_ctx* c, int32_t seq, int32_t layer, int32_t pos0, int32_t n, float* k_out, float* v_out) {
@@ -1257,7 +1299,7 @@ int first_get_hidden(first_ctx* c, float* hidden_out) {
   HIPCHK(c, hipMemcpyAsync(hidden_out, c->d_h, (size_t)c->B * c->d.d_model * sizeof(float), hipMemcpyDeviceToDevice,
                            c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  return FIRST_OK;
+  return check_step_error(c, "first_get_hidden");
 }
 
 int first_set_page_order(first_ctx* c, const int32_t* perm) {

@@ -1547,11 +1547,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
         z_staged = 0;
       }
-#ifdef SK_V_T1
-      if (false) {
-#else
       if (cur.kind == SEG_GU && cur.blk_stride != 0) {
-#endif
         // Gate/up in blocks: block k is this workgroup's part of K-segment k of the down projection's input.  As soon
         // as the streaming waves are through a block its z values go out, and the segment before it - by now complete
         // grid-wide - is staged for the down projection, which therefore starts without waiting for anybody.
@@ -1608,17 +1604,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           st_coh(h + cur.row0 + lane, sk_tagged(v, tag_h));
           if (cur.kind == SEG_DN && P.h_out != nullptr) P.h_out[(size_t)b * D + cur.row0 + lane] = v;
         }
-#ifdef SK_V_T1
-      } else if (cur.kind == SEG_GU && cur.blk_stride != 0) {
-        float* z = p.z + (size_t)b * F;
-        tag_z ^= 1u;
-        const int cs = cur.bl >> 1;
-        for (int r = lane; r < cur.nrows / 2; r += 64) {
-          const float gt = seg_row_sum(S.psum, cur, 2 * r), up = seg_row_sum(S.psum, cur, 2 * r + 1);
-          const int k = r / cs;
-          st_coh(z + k * SK_SEG + cs * cu + (r - k * cs), sk_tagged(siluf(gt) * up, tag_z));
-        }
-#endif
       } else if (cur.kind == SEG_GU && cur.blk_stride == 0) {
         float* z = p.z + (size_t)b * F;
         tag_z ^= 1u;
@@ -1723,11 +1708,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       const int* staged = cur.kind == SEG_DN ? S.flag + 2 : nullptr;
       const bool ahead = !(nxt.kind == SEG_O && attn_wg && wave < A.nact);     // a wave with tiles requests its output-projection rows afterwards
       int seen = 1;
-#ifdef SK_V_T1
-      const bool progress = false;
-#else
       const bool progress = cur.kind == SEG_GU && cur.blk_stride != 0;     // the service wave sends z out block by block
-#endif
       for (int r0 = 0; r0 < last0; r0 += SK_PD) {
 #pragma unroll
         for (int j = 0; j < SK_PD; ++j) {
