@@ -19,10 +19,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 # polls of the persistent step kernel, the attention kernels of the batched path, the partial sums a last arriver
 # collects, the operand prefetch of the prefill GEMM): the compiler does not know that the destination of such a load is
 # written later, so a destination it spills and hands to another value is overwritten when the load lands.  Bytes of
-# scratch per lane each kernel may use (k_step: a handful of loop-invariant values the compiler parks there at its
-# register limit, k_attn_tiles_b likewise under its 128-register cap; asm_check.py verifies that no in-flight destination
-# is among them, or is touched in any other way; "k_bgemv" covers k_bgemv and k_bgemv_g):
-SCRATCH_LIMITS = {"k_step": 64, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv": 0, "k_gemm_nt_bf16_hl": 0}
+# scratch per lane each kernel may use (k_attn_tiles_b: a handful of loop-invariant values the compiler parks there under
+# the kernel's 128-register cap; asm_check.py verifies that no in-flight destination is among them, or is touched in any
+# other way; "k_bgemv" covers k_bgemv and k_bgemv_g):
+SCRATCH_LIMITS = {"k_step": 0, "k_attn_tiles_b": 32, "k_attn_mfma_b": 0, "k_bgemv": 0, "k_gemm_nt_bf16_hl": 0}
 
 
 def kernel_resources(remarks: str) -> dict:

@@ -15,8 +15,11 @@ constexpr int SK_THREADS = 512;
 constexpr int SK_WAVES = SK_THREADS / 64;
 constexpr int SK_SWAVES = SK_WAVES - 1;  // streaming waves; the last wave is the service wave (see k_step)
 constexpr int SK_SEG = 2048;          // elements of a weight row handled by one wave at a time (4 x 16 B per lane)
-constexpr int SK_PD = 7;              // row segments in flight per wave (28 KB; 8 measured no faster and leaves no spare registers)
-constexpr int SK_PD_EARLY = 4;        // ring slots that stay in flight across the attention phase
+// Row segments in flight per streaming wave (4 KB each).  Two - 14 MB over the chip - measured fastest on the 8B-class
+// shape at 24 kept layers: 2.09 ms per step against 2.19 (one), 2.14 (three), 2.17 (four, five) and 2.18 (seven).  A deeper
+// ring does not buy bandwidth, the memory system is saturated long before; it buys latency, and at every phase change the
+// requests for the next phase's first rounds queue ahead of the straggling waves' last loads of this one.
+constexpr int SK_PD = 2;
 constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row segments per phase)
 constexpr int SK_QSPLIT_MAX = 8;      // attention of the persistent kernel: at most this many key splits per query head
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
@@ -1390,16 +1393,15 @@ __global__ void __launch_bounds__(WG) k_permute_down_columns(const bf16* __restr
 }
 
 // ---------------------------------------------------------------------------------------
-// Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds (28 KB) in flight that runs
+// Wave roles.  Waves 0..SK_SWAVES-1 only stream weights: each keeps a ring of SK_PD rounds (8 KB) in flight that runs
 // on across phase boundaries, so HBM stays busy while the workgroups hand their results on.  The last wave is the
 // service wave: it turns the partial sums of a finished phase into its outputs, waits for the next phase's input and
 // stages it into LDS.  It never has weight loads in flight, which matters because a wave's loads return in order: a
 // poll or an input load issued behind a prefetch queue would wait for all of it.
 //
 // Who does what in the attention + output-projection phase.  With Hq x nsplit <= half the grid (short contexts) the
-// first Hq x nsplit workgroups compute attention and own NO rows of the output projection; the others own all of them,
-// request every round of their rows before attention starts and hold them in the ring, so when the attention output
-// arrives the projection is a pass over registers.  The attention workgroups have no weight loads in flight meanwhile
+// first Hq x nsplit workgroups compute attention and own NO rows of the output projection; the others own all of them
+// and have their first rounds in the ring when the attention output arrives.  The attention workgroups have no weight loads in flight meanwhile
 // (their ring registers hold the key and value tiles) and go on to request the gate/up rows as soon as their part of
 // attention is done.  With long contexts every workgroup computes attention and the projection's rows are dealt evenly.
 //
