@@ -1040,12 +1040,17 @@ struct SkAttnGeo {
   bool appends;                 // ... and this workgroup is the one of its KV head that writes the new k / v to the cache
 };
 
-// Key splits per query head for a context of `tiles` 64-key tiles on a grid of ncu workgroups: as many as the grid
-// allows, so that a workgroup has few tiles and each of them a wave (and a SIMD) of its own - a tile is a few thousand
-// ALU cycles of one wave.  tps = tiles per split.
+// Key splits per query head for a context of `tiles` 64-key tiles on a grid of ncu workgroups: many, so that a workgroup
+// has few tiles and each of them a wave (and a SIMD) of its own - a tile is a few thousand ALU cycles of one wave.  As
+// long as that still gives every tile a wave, a quarter of the grid is left out of attention: those workgroups go on
+// pulling in gate/up weights meanwhile (sk_prefetch), which measured better than their help with the tiles (8B-class
+// shape, 32 query heads: 6 splits 2.048 ms per step, 8 splits 2.061; 3B-class, 24 heads: 8 splits fit either way).
+// tps = tiles per split.
 __device__ __forceinline__ int sk_attn_splits(int tiles, int ncu, int Hq, int& tps) {
   const int smax = max(1, min(SK_QSPLIT_MAX, ncu / Hq));
-  tps = (tiles + smax - 1) / smax;
+  const int sfree = max(1, min(SK_QSPLIT_MAX, (ncu - ncu / 4) / Hq));
+  const int tps_free = (tiles + sfree - 1) / sfree;
+  tps = tps_free <= SK_SWAVES ? tps_free : (tiles + smax - 1) / smax;
   return (tiles + tps - 1) / tps;
 }
 
