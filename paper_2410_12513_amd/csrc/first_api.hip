@@ -905,7 +905,7 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
   A(dev_alloc(c, &c->x_part, sk_part_index(d.n_q_heads, d.head_dim, B, 0, 0)));
   A(dev_alloc(c, &c->d_tagstate, (size_t)B * 8));
   A(dev_alloc(c, &c->d_layers, L)); A(dev_alloc(c, &c->d_done, (size_t)c->num_cu)); A(dev_alloc(c, &c->d_err, 4));
-  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS + 65536 + 65536));
+  A(dev_alloc(c, &c->d_tdbg, (size_t)(4 * L + 1) * SK_TSLOTS));
   if (rc == FIRST_OK) {
     std::vector<double> theta(c->half);
     for (int i = 0; i < c->half; ++i) theta[i] = std::pow((double)d.rope_base, -2.0 * i / d.head_dim);
@@ -1453,12 +1453,6 @@ int first_step_timing(first_ctx* c, uint64_t* stamps, int32_t capacity, int32_t*
   return FIRST_OK;
 }
 
-#ifdef SK_DBG_DUMP
-int first_debug_read(first_ctx* c, float* host, int n) {
-  hipStreamSynchronize(c->stream);
-  return (int)hipMemcpy(host, reinterpret_cast<float*>(c->d_tdbg + (size_t)(4 * c->d.n_layers + 1) * SK_TSLOTS), (size_t)n * 4, hipMemcpyDeviceToHost);
-}
-#endif
 
 int first_op_gateup(first_ctx* c, int32_t layer, int32_t seq) {
   if (!c) return FIRST_ERR_ARG;

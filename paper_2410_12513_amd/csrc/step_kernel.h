@@ -1338,14 +1338,6 @@ __device__ __forceinline__ bool sk_attn_merge_head(const StepParams& P, const Sk
       for (int j = 0; j < NV; ++j) a[j] = fmaf(src[j * 64 + lane], wg, a[j]);
     }
   }
-#ifdef SK_DBG_DUMP
-  if (P.tdbg) {
-    float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS) + 8192 + blockIdx.x * (HD + 4);
-#pragma unroll
-    for (int j = 0; j < NV; ++j) dbg[j * 64 + lane] = a[j];
-    if (lane == 0) { dbg[HD] = M; dbg[HD + 1] = den; }
-  }
-#endif
   if (stamps && lane == 0) stamps[9] = wall_clock64();
   if (A.s != 0) {
     float* dst = P.part + sk_part_index(p.Hq, HD, p.b, A.H, A.s);
@@ -1478,19 +1470,11 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
   const SkShare share_o{cu >= o_first ? (cu - o_first) * 1024 : 0, cu >= o_first ? (cu - o_first + 1) * 1024 : 0, ncu - o_first};
 
-#ifdef SK_DBG_DUMP
-#define SK_XSTAMP(i) do { if (P.tdbg && cu == 0 && lane == 0) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[s * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define SK_XSTAMP(i) do { } while (0)
-#endif
 #define SK_STAMP(slot)                                                                 \
   do {                                                                                 \
     if (P.tdbg && cu == 0 && tid == SK_SWAVES * 64) P.tdbg[s * SK_TSLOTS + (slot)] = wall_clock64(); \
   } while (0)
 
-#ifdef SK_DBG_DUMP
-  if (P.tdbg && cu == 0 && tid == 0) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[1000] = wall_clock64();
-#endif
   // ---- h = E[token]; rotation table of this position (kept in LDS for the whole step)
   {
     tok = min(max(tok, 0), p.V - 1);
@@ -1612,7 +1596,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
       }
       if (s + 1 < nsegs && D <= 4096 && nx.gain != nullptr) sk_gains_to_lds(S.gs, nx.gain, D);   // (this phase's staging has read S.gs already)
-      SK_XSTAMP(0);
       lds_barrier();                               // partial sums complete
       SK_STAMP(4);
       // results of the segment
@@ -1625,17 +1608,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
         tag_h ^= 1u;
-#ifdef SK_DBG_DUMP
-        if (P.tdbg && cur.kind == SEG_O && lane < cur.nrows) {
-          float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
-          dbg[cur.row0 + lane] = sk_untag(h_prev);
-          dbg[D + cur.row0 + lane] = seg_row_sum(S.psum, cur, lane);
-        }
-        if (P.tdbg && cur.kind == SEG_O && cu == ncu - 1) {
-          float* dbg = reinterpret_cast<float*>(P.tdbg + (4 * P.L + 1) * SK_TSLOTS);
-          for (int k = lane; k < nq; k += 64) dbg[2 * D + k] = S.xs[(((k >> 3) << 2) | (k & 3)) + ((k & 4) ? sk_plane(nq) : 0)];
-        }
-#endif
         if (lane < cur.nrows) {
           const float v = sk_untag(sk_untag(h_prev) + seg_row_sum(S.psum, cur, lane));
           st_coh(h + cur.row0 + lane, sk_tagged(v, tag_h));
@@ -1708,9 +1680,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       int* ts = P.tagstate + 8 * b;
       st_coh(ts, (int)tag_h); st_coh(ts + 1, (int)tag_q); st_coh(ts + 2, (int)tag_a); st_coh(ts + 3, (int)tag_z);
       st_coh(ts + 4, (int)epoch);
-#ifdef SK_DBG_DUMP
-      if (P.tdbg) (P.tdbg + (4 * P.L + 1) * SK_TSLOTS + 32768)[1001] = wall_clock64();
-#endif
     }
   } else {
     uint4 buf[SK_PD][4];
@@ -1739,8 +1708,6 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // attention workgroup is awaited at that workgroup's own barriers, so those do not linger)
       if (cur.kind == SEG_O && !attn_wg) sk_prefetch(nxt, SK_PF_ROUNDS, wave);
       lds_barrier();                               // input vector staged
-      if (wave == 0) SK_XSTAMP(1);
-      if (wave == 6) SK_XSTAMP(4);
       if (uni(*S.flag) == 0) return;
       // all blocks but the last request ahead inside this segment; the last one requests the first rounds of the
       // next segment (no per-round choice between the two descriptors)
@@ -1762,13 +1729,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         sk_consume(cur, last0 + j, wave, buf[j], xsrc, S.psum, staged, seen);
         if (progress && lane == 0) __hip_atomic_store(S.flag + 4 + wave, last0 + j + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         sk_issue(nxt, j, ahead, wave, buf[j]);
-        if (j == 0 && wave == 0) SK_XSTAMP(6);
-        if (j == 0 && wave == 6) SK_XSTAMP(7);
       }
-      if (wave == 0) SK_XSTAMP(2);
-      if (wave == 6) SK_XSTAMP(5);
       lds_barrier();                               // partial sums complete
-      if (wave == 0) SK_XSTAMP(3);
       cur = nxt;
     }
   }
