@@ -182,6 +182,21 @@ int first_decode_step(first_ctx *ctx, const int32_t *last_tokens, float *logits_
 int first_sample_top_k(first_ctx *ctx, const float *logits, const float *uniforms, float temperature,
                        int32_t top_k, int32_t *token_out, int32_t *candidates_out);
 
+/* first_decode_step with that decoding rule in place of the greedy argmax (Appendix, "Inference settings"): the
+ * token written for sequence b is drawn from its top_k largest logits exactly as first_sample_top_k would draw it
+ * from the step's logits with the same uniforms (same candidates, same order, same fp32 arithmetic).  With one live
+ * sequence on the persistent kernel the rule is part of that kernel: every workgroup lists the first top_k
+ * candidates among its rows of the LM head and the workgroup that used to reduce the argmax merges the lists and
+ * draws, so the step stays one launch and writes no logits unless asked to.  On the other decode paths, or when
+ * top_k lists of all workgroups do not fit that kernel's LDS, the step's logits go through the kernels of
+ * first_sample_top_k on the same stream (into a buffer of the context if logits_out is NULL).
+ *   last_tokens DEV int32 [B]; uniforms DEV fp32 [B], one number in [0, 1) per sequence, read when the step runs;
+ *   temperature > 0; 1 <= top_k <= 64; logits_out DEV fp32 [B, V] (may be NULL); token_out DEV int32 [B];
+ *   candidates_out DEV int32 [B, top_k] (may be NULL).
+ * Errors as first_decode_step and first_sample_top_k; a refusal changes nothing. */
+int first_decode_step_sampled(first_ctx *ctx, const int32_t *last_tokens, const float *uniforms, float temperature,
+                              int32_t top_k, float *logits_out, int32_t *token_out, int32_t *candidates_out);
+
 /* first_sample_top_k for callers that cannot allocate device memory or hold a context: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same rule, same kernels and the same
  * results as first_sample_top_k, on any logits: the per-chunk candidate lists of the first stage live in a

@@ -16,7 +16,7 @@ EXPORTS = ["first_create", "first_destroy", "first_prefill_route", "first_set_ma
            "first_decode_step", "first_set_option", "first_sync", "first_last_error", "first_seq_len",
            "first_batch", "first_kv_read", "first_kv_write", "first_get_hidden", "first_set_page_order", "first_sample_top_k",
            "first_num_pages", "first_op_gemv", "first_op_gemm_nt", "first_op_gateup", "first_step_timing", "first_op_gemm_nt_f32a", "first_set_seq_len", "first_kv_usage", "first_soft_forward",
-           "first_lora_merge", "first_sample_top_k_static"]
+           "first_lora_merge", "first_sample_top_k_static", "first_decode_step_sampled"]
 
 
 class FirstError(RuntimeError):
@@ -185,6 +185,20 @@ class FirstContext:
         if logits is not None:
             _check_dev(logits, torch.float32, "logits")
         self._chk(self.lib.first_decode_step(self.h, _ptr(last_tokens), _ptr(logits), _ptr(token)))
+
+    def decode_step_sampled(self, last_tokens: torch.Tensor, uniforms: torch.Tensor, temperature: float, top_k: int,
+                            logits: Optional[torch.Tensor], token: torch.Tensor,
+                            candidates_out: Optional[torch.Tensor] = None) -> None:
+        B = self.batch()
+        _check_dev(last_tokens, torch.int32, "last_tokens")
+        _check_dev(uniforms, torch.float32, "uniforms", B)
+        _check_dev(token, torch.int32, "token")
+        if logits is not None:
+            _check_dev(logits, torch.float32, "logits")
+        if candidates_out is not None:
+            _check_dev(candidates_out, torch.int32, "candidates_out", B * top_k)
+        self._chk(self.lib.first_decode_step_sampled(self.h, _ptr(last_tokens), _ptr(uniforms), C.c_float(temperature),
+                                                     C.c_int32(top_k), _ptr(logits), _ptr(token), _ptr(candidates_out)))
 
     def set_option(self, option: int, value: int) -> None:
         self._chk(self.lib.first_set_option(self.h, C.c_int32(option), C.c_int32(value)))

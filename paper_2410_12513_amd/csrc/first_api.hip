@@ -72,6 +72,8 @@ struct first_ctx {
   unsigned* d_bg_cnt = nullptr;           //            arrival counters per tile group (zero between launches)
   size_t bg_part_floats = 0, bg_cnt_n = 0;
   Cand* d_topk_part = nullptr;            // [max_batch][chunks][SMP_KMAX] per-chunk candidates of first_sample_top_k
+  float* d_logits_own = nullptr;          // [max_batch][V] logits of a sampled step whose caller wants none
+  Cand* d_step_cands = nullptr;           // [workgroups][SMP_KMAX] per-workgroup candidates of a sampled step of the persistent kernel
   float2* d_rope_cs = nullptr;
   Best* d_arg_part = nullptr;
   // prefill workspace
@@ -565,8 +567,12 @@ const void* step_kernel_fn(const first_ctx* c) {
   return c->d.head_dim == 128 ? reinterpret_cast<const void*>(&k_step<128>) : reinterpret_cast<const void*>(&k_step<64>);
 }
 
+// What a sampled step adds to a greedy one (null: greedy).
+struct SampleArgs { const float* uniforms; float temperature; int top_k; int* candidates_out; };
+
 // One decode token of the single live sequence as one persistent kernel.
-void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, int* token_out) {
+
+void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, int* token_out, const SampleArgs* smp = nullptr) {
   StepParams P{};
   P.d = base_params(c, 0, 1);
   P.d.tokens = tokens; P.d.logits = logits; P.d.token_out = token_out; P.d.advance_len = 1;
@@ -575,6 +581,10 @@ void enqueue_decode_step_kernel(first_ctx* c, const int* tokens, float* logits, 
   P.tagstate = c->d_tagstate; P.h_out = c->d_h; P.part = c->x_part; P.zperm = c->zperm ? 1 : 0;
   P.d.h = c->x_h; P.d.qkv = c->x_qkv; P.d.attn = c->x_attn; P.d.z = c->x_z;
   P.tdbg = c->step_timing ? c->d_tdbg : nullptr;
+  if (smp) {
+    P.smp_k = smp->top_k; P.smp_temperature = smp->temperature; P.smp_u = smp->uniforms;
+    P.smp_part = c->d_step_cands; P.smp_cand_out = smp->candidates_out;
+  }
   hipLaunchKernelGGL(reinterpret_cast<void (*)(StepParams)>(const_cast<void*>(step_kernel_fn(c))), dim3(c->num_cu), dim3(SK_THREADS),
                      c->step_lds, c->stream, P);
 }
@@ -900,6 +910,8 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
 #undef FIRST_BGG_ATTR
   }
   A(dev_alloc(c, &c->d_topk_part, (size_t)B * ((d.vocab + SMP_CHUNK - 1) / SMP_CHUNK) * SMP_KMAX));
+  A(dev_alloc(c, &c->d_step_cands, (size_t)c->num_cu * SMP_KMAX));
+  A(dev_alloc(c, &c->d_logits_own, (size_t)B * d.vocab));
   A(dev_alloc(c, &c->x_h, (size_t)B * d.d_model)); A(dev_alloc(c, &c->x_qkv, (size_t)B * (c->nq + 2 * c->nkv)));
   A(dev_alloc(c, &c->x_attn, (size_t)B * c->nq)); A(dev_alloc(c, &c->x_z, (size_t)B * d.d_ffn));
   A(dev_alloc(c, &c->x_part, sk_part_index(d.n_q_heads, d.head_dim, B, 0, 0)));
@@ -1042,9 +1054,10 @@ int first_get_kept(first_ctx* c, int32_t seq, int32_t* kept_idx, int32_t* n_kept
   return check_step_error(c, "first_get_kept");
 }
 
-int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_out, int32_t* token_out) {
-  if (!c) return FIRST_ERR_ARG;
-  if (!last_tokens) return fail(c, FIRST_ERR_ARG, "first_decode_step: null tokens");
+namespace {
+// One decode step, greedy (smp null) or with the paper's decoding rule.  On the persistent kernel the rule is part of the
+// kernel's LM-head epilogue; elsewhere the step's logits go through the two sampling kernels.
+int decode_step_impl(first_ctx* c, const int32_t* last_tokens, float* logits_out, int32_t* token_out, const SampleArgs* smp) {
   if (c->B < 1) return fail(c, FIRST_ERR_STATE, "first_decode_step: no prefilled sequence");
   const int P = c->d.kv_page_tokens;
   int max_len = 0;
@@ -1062,6 +1075,9 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
                                     "multiples of 256, 16-token pages and exactly one live sequence");
   const bool batch_ok = bf && c->B > 1 && c->d_xh && d_batch_fits(c);
   const bool batched = !persistent && batch_ok && c->batch_path != 0;
+  // (the persistent kernel merges the workgroups' candidate lists in LDS: a large top_k may not fit there)
+  const bool fused = smp && persistent && smp->top_k <= sk_sample_kmax(c->d.d_model, c->nq, c->d.d_ffn, c->num_cu);
+  if (smp && !fused && !logits_out) logits_out = c->d_logits_own;
   if (c->batch_path == 1 && !persistent && !batched)
     return fail(c, FIRST_ERR_STATE, "first_decode_step: the batched path needs a bf16 model whose widths are multiples of 8 "
                                     "and more than one live sequence");
@@ -1084,10 +1100,16 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
     }
   }
   auto enqueue = [&]() {
-    if (persistent) enqueue_decode_step_kernel(c, last_tokens, logits_out, token_out);
+    if (persistent) enqueue_decode_step_kernel(c, last_tokens, logits_out, token_out, fused ? smp : nullptr);
     else if (batched) enqueue_decode_batched(c, last_tokens, logits_out, token_out, S);
     else if (bf) enqueue_decode_ops<bf16>(c, last_tokens, logits_out, token_out, S);
     else enqueue_decode_ops<float>(c, last_tokens, logits_out, token_out, S);
+    if (smp && !fused) {
+      const int chunks = (c->d.vocab + SMP_CHUNK - 1) / SMP_CHUNK;
+      hipLaunchKernelGGL(k_topk_part, dim3(chunks, c->B), dim3(SMP_THREADS), 0, c->stream, logits_out, c->d.vocab, smp->top_k, c->d_topk_part);
+      hipLaunchKernelGGL(k_topk_sample, dim3(c->B), dim3(SMP_THREADS), 0, c->stream, c->d_topk_part, chunks * smp->top_k, smp->top_k,
+                         smp->temperature, smp->uniforms, token_out, smp->candidates_out);
+    }
   };
   if (!c->use_graph) {
     enqueue();
@@ -1099,6 +1121,7 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
     key.append(reinterpret_cast<const char*>(&last_tokens), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&logits_out), sizeof(void*));
     key.append(reinterpret_cast<const char*>(&token_out), sizeof(void*));
+    if (smp) key.append(reinterpret_cast<const char*>(smp), sizeof(*smp));      // (pointers and values are part of the captured arguments)
     if (!persistent)
       for (int b = 0; b < c->B; ++b) key.append(reinterpret_cast<const char*>(c->hmask[b].data()), c->hmask[b].size());
     auto it = c->graphs.find(key);
@@ -1134,6 +1157,24 @@ int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_ou
   }
   for (int b = 0; b < c->B; ++b) { c->hlen[b] += 1; c->decoded[b] = 1; }
   return FIRST_OK;
+}
+}  // namespace
+
+int first_decode_step(first_ctx* c, const int32_t* last_tokens, float* logits_out, int32_t* token_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!last_tokens) return fail(c, FIRST_ERR_ARG, "first_decode_step: null tokens");
+  return decode_step_impl(c, last_tokens, logits_out, token_out, nullptr);
+}
+
+int first_decode_step_sampled(first_ctx* c, const int32_t* last_tokens, const float* uniforms, float temperature, int32_t top_k,
+                              float* logits_out, int32_t* token_out, int32_t* candidates_out) {
+  if (!c) return FIRST_ERR_ARG;
+  if (!last_tokens || !uniforms || !token_out) return fail(c, FIRST_ERR_ARG, "first_decode_step_sampled: null pointer");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(c, FIRST_ERR_ARG, "first_decode_step_sampled: temperature must be positive");
+  if (top_k < 1 || top_k > SMP_KMAX) return fail(c, FIRST_ERR_ARG, "first_decode_step_sampled: top_k must be in 1..64");
+  SampleArgs smp{};                                  // (zeroed: the struct's bytes are part of the graph key)
+  smp.uniforms = uniforms; smp.temperature = temperature; smp.top_k = top_k; smp.candidates_out = candidates_out;
+  return decode_step_impl(c, last_tokens, logits_out, token_out, &smp);
 }
 
 int first_sample_top_k(first_ctx* c, const float* logits, const float* uniforms, float temperature, int32_t top_k,

@@ -46,6 +46,24 @@ __device__ __forceinline__ Cand wg_first(Cand c, Cand* red) {
   return r;
 }
 
+// The draw: top[0..k) in order (SMP_NONE beyond the vocabulary), u in [0, 1).  One thread; every path that samples ends
+// in this function, so that they take the same decision on the same candidates.
+__device__ __forceinline__ int smp_draw(const Cand* top, int k, float temperature, float u) {
+  int kk = 0;
+  while (kk < k && top[kk].i != SMP_NONE) ++kk;
+  const float lmax = top[0].v;
+  float total = 0.f;
+  for (int j = 0; j < kk; ++j) total += expf((top[j].v - lmax) / temperature);
+  const float target = u * total;
+  float cum = 0.f;
+  int pick = kk > 0 ? top[kk - 1].i : 0;
+  for (int j = 0; j < kk; ++j) {
+    cum += expf((top[j].v - lmax) / temperature);
+    if (cum > target) { pick = top[j].i; break; }
+  }
+  return pick;
+}
+
 // Stage 1.  grid (chunks, sequences).  part[(seq * chunks + chunk) * k + r] = r-th candidate of the chunk.
 __global__ void __launch_bounds__(SMP_THREADS) k_topk_part(const float* __restrict__ logits, int V, int k, Cand* __restrict__ part) {
   __shared__ Cand red[SMP_THREADS / 64];
@@ -91,21 +109,7 @@ __global__ void __launch_bounds__(SMP_THREADS) k_topk_sample(const Cand* __restr
   }
   __syncthreads();
   if (tid < k && cand_out != nullptr) cand_out[(size_t)seq * k + tid] = top[tid].i == SMP_NONE ? -1 : top[tid].i;
-  if (tid == 0) {
-    int kk = 0;
-    while (kk < k && top[kk].i != SMP_NONE) ++kk;
-    const float lmax = top[0].v;
-    float total = 0.f;
-    for (int j = 0; j < kk; ++j) total += expf((top[j].v - lmax) / temperature);
-    const float target = uniforms[seq] * total;
-    float cum = 0.f;
-    int pick = kk > 0 ? top[kk - 1].i : 0;
-    for (int j = 0; j < kk; ++j) {
-      cum += expf((top[j].v - lmax) / temperature);
-      if (cum > target) { pick = top[j].i; break; }
-    }
-    token_out[seq] = pick;
-  }
+  if (tid == 0) token_out[seq] = smp_draw(top, k, temperature, uniforms[seq]);
 }
 
 }  // namespace first

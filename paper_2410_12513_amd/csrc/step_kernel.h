@@ -8,6 +8,7 @@
 #include <type_traits>
 
 #include "decode_kernels.h"
+#include "sample_kernels.h"
 
 namespace first {
 
@@ -21,6 +22,7 @@ constexpr int SK_SEG = 2048;          // elements of a weight row handled by one
 // requests for the next phase's first rounds queue ahead of the straggling waves' last loads of this one.
 constexpr int SK_PD = 2;
 constexpr int SK_PSUM = 2048;         // partial sums a workgroup can hold (row segments per phase)
+constexpr int SK_SMP_LISTS = 8;       // sampling in the kernel: candidate lists per lane of the merging wave (grids up to 512 workgroups)
 constexpr int SK_QSPLIT_MAX = 8;      // attention of the persistent kernel: at most this many key splits per query head
 constexpr unsigned SK_SPIN_LIMIT = 1u << 21;
 constexpr int SK_TSLOTS = 12;         // timestamps per segment: arrive, -, attention, stage, stream, results, then six marks inside attention
@@ -189,6 +191,12 @@ struct StepParams {
   bf16 *xh_out, *xl_out;       // sk_attention<.., SPLIT_OUT> (batched path): the attention output as bf16 high / low halves in
   int out_slot;                //   A-operand order (bg_aidx) for slot out_slot, instead of fp32 in d.attn
   unsigned long long* tdbg;    // optional [segments][SK_TSLOTS] timestamps of workgroup 0 (100 MHz clock)
+  // The paper's decoding rule in place of the greedy argmax (smp_k = 0: greedy; see sample_kernels.h)
+  int smp_k;                   // candidates, 1 .. sk_sample_kmax(...)
+  float smp_temperature;
+  const float* smp_u;          // [B] the caller's uniform draws
+  Cand* smp_part;              // [grid][smp_k] every workgroup's first smp_k candidates among its rows of the LM head
+  int* smp_cand_out;           // [B][smp_k] the sequence's candidates in order, -1 beyond the vocabulary (may be null)
 };
 
 // LDS carve-up (floats)
@@ -214,6 +222,16 @@ __host__ __device__ inline size_t sk_lds_floats(int D, int nq, int F, int G, int
   const int gs = ((D + 2047) / 2048 * 2048) < 4096 ? ((D + 2047) / 2048 * 2048) : 4096;
   return (size_t)xs + F + SK_PSUM + gs + (SK_WAVES + 8) + (size_t)G * hd + 2 * hd + hd + SK_WAVES * 64 +
          (size_t)SK_WAVES * (hd + 2) + 16;
+}
+
+// Largest top-k the persistent kernel can sample with on a grid of ncu workgroups: workgroup 0 merges ncu lists of k
+// candidates (value + index) in the LDS that the input vectors and the partial sums occupied, plus the k it picks.
+__host__ __device__ inline int sk_sample_kmax(int D, int nq, int F, int ncu) {
+  const int xs = ((D > nq ? D : nq) + 2047) / 2048 * 2048;
+  const long long floats = (long long)xs + (F + 2047) / 2048 * 2048 + SK_PSUM;
+  const long long k = floats / (2ll * ncu + 2);
+  if (ncu > 64 * SK_SMP_LISTS) return 0;
+  return (int)(k < SMP_KMAX ? k : SMP_KMAX);
 }
 
 __device__ __forceinline__ SkLds sk_carve(float* base, int D, int nq, int F, int G, int hd) {
@@ -1622,6 +1640,34 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         }
       } else if (cur.kind == SEG_HEAD) {
         float* lg = p.logits ? p.logits + (size_t)b * p.V : nullptr;
+        if (P.smp_k > 0) {
+          // Sampling: this workgroup's first smp_k candidates in the order (larger logit, lower index), by smp_k rounds
+          // of "first after the previous pick" over its logits, which wait in LDS (the input vector's place: the head
+          // has streamed).  Workgroup 0 merges the lists the same way below.
+          float* lv = S.xs;
+          for (int r = lane; r < cur.nrows; r += 64) {
+            const float v = seg_row_sum(S.psum, cur, r);
+            if (lg) lg[cur.row0 + r] = v;
+            lv[r] = v;
+          }
+          Cand last{INFINITY, -1};
+          Cand* dst = P.smp_part + (size_t)cu * P.smp_k;
+          for (int k = 0; k < P.smp_k; ++k) {
+            Cand first{-INFINITY, SMP_NONE};
+            for (int r = lane; r < cur.nrows; r += 64) {
+              const Cand e{lv[r], cur.row0 + r};
+              if (cand_before(last, e) && cand_before(e, first)) first = e;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+              const Cand c{__shfl_xor(first.v, o, 64), __shfl_xor(first.i, o, 64)};
+              if (cand_before(c, first)) first = c;
+            }
+            if (lane == 0) { st_coh(&dst[k].v, first.v); st_coh(&dst[k].i, first.i); }
+            last = first.i == SMP_NONE ? Cand{-INFINITY, SMP_NONE} : first;      // nothing left: nothing comes after
+          }
+          vm_wait_all();                           // the candidates are in memory before this workgroup says so
+        } else {
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
           const float v = seg_row_sum(S.psum, cur, r);
@@ -1639,6 +1685,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           st_coh(&dst->v, best.v); st_coh(&dst->i, best.i);
         }
         vm_wait_all();                             // the candidate is in memory before this workgroup says so
+        }
       }
       SK_STAMP(5);
       cur = nx;
@@ -1667,12 +1714,68 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       }
     }
     Best bb{-INFINITY, 0x7fffffff};
+    if (P.smp_k > 0) {
+      // all candidate lists into LDS (from the input vector's place on: nothing there is needed any more; the host
+      // checked that they fit), smp_k rounds over them, the draw by one lane
+      const int n = ncu * P.smp_k;
+      float* cv = S.xs;
+      int* ci = reinterpret_cast<int*>(S.xs) + n;
+      // (two candidates per 16-byte load, eight loads per lane in flight: one memory round trip per 1024 candidates;
+      // the list buffer has SMP_KMAX slots per workgroup, so the odd one past the end is there to be read and ignored)
+      const float* src = reinterpret_cast<const float*>(P.smp_part);
+      for (int j0 = 0; j0 < n; j0 += 2 * 64 * 8) {
+        f32x4_t q[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) coh_issue16(q[t], src + 2 * min(j0 + 2 * (t * 64 + lane), n - 1 + (n & 1) - 1));
+        coh_wait();
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          coh_use(q[t]);
+          const int j = j0 + 2 * (t * 64 + lane);
+          if (j < n) { cv[j] = q[t].x; ci[j] = __float_as_int(q[t].y); }
+          if (j + 1 < n) { cv[j + 1] = q[t].z; ci[j + 1] = __float_as_int(q[t].w); }
+        }
+      }
+      Cand* top = reinterpret_cast<Cand*>(ci + n);
+      // every list is in order already, so only the lists' heads compete: a lane looks after the lists of workgroups
+      // lane, lane + 64, ... (at most SK_SMP_LISTS of them: the host checks the grid), the winner's list moves on
+      Cand head[SK_SMP_LISTS];
+      int at[SK_SMP_LISTS];
+#pragma unroll
+      for (int l = 0; l < SK_SMP_LISTS; ++l) {
+        const int wg = l * 64 + lane;
+        at[l] = wg * P.smp_k;
+        head[l] = wg < ncu ? Cand{cv[at[l]], ci[at[l]]} : Cand{-INFINITY, SMP_NONE};
+      }
+      for (int k = 0; k < P.smp_k; ++k) {
+        Cand first{-INFINITY, SMP_NONE};
+#pragma unroll
+        for (int l = 0; l < SK_SMP_LISTS; ++l)
+          if (head[l].i != SMP_NONE && cand_before(head[l], first)) first = head[l];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+          const Cand c{__shfl_xor(first.v, o, 64), __shfl_xor(first.i, o, 64)};
+          if (cand_before(c, first)) first = c;
+        }
+        if (lane == 0) top[k] = first;
+#pragma unroll
+        for (int l = 0; l < SK_SMP_LISTS; ++l)
+          if (head[l].i == first.i && first.i != SMP_NONE) {       // (token ids are unique: this is the list it came from)
+            ++at[l];
+            head[l] = at[l] < (l * 64 + lane + 1) * P.smp_k ? Cand{cv[at[l]], ci[at[l]]} : Cand{-INFINITY, SMP_NONE};
+          }
+      }
+      if (P.smp_cand_out != nullptr)
+        for (int k = lane; k < P.smp_k; k += 64) P.smp_cand_out[(size_t)b * P.smp_k + k] = top[k].i == SMP_NONE ? -1 : top[k].i;
+      if (lane == 0) bb.i = smp_draw(top, P.smp_k, P.smp_temperature, P.smp_u[b]);
+    } else {
     const Best* ap = p.arg_part + (size_t)b * ARG_MAX_WG;
     for (int i = lane; i < ncu; i += 64) { const Best c{ld_coh(&ap[i].v), ld_coh(&ap[i].i)}; if (better(c, bb)) bb = c; }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       const Best c{__shfl_xor(bb.v, o, 64), __shfl_xor(bb.i, o, 64)};
       if (better(c, bb)) bb = c;
+    }
     }
     if (lane == 0) {
       if (p.token_out) p.token_out[b] = bb.i;

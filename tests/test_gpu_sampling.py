@@ -114,3 +114,73 @@ def test_sampling_rejects_bad_arguments():
     ctx.sync()
     assert int(tok[0]) == -7                             # nothing written on error
     ctx.close()
+
+
+@pytest.mark.parametrize("model,k", [("step_hd128", 10), ("step_hd128", 1), ("step_hd128", 15), ("step_hd128", 40),
+                                     ("step_hd64", 10), ("step_3k", 7)])
+def test_sampled_step_of_the_persistent_kernel_equals_step_then_sampler(model, k):
+    """first_decode_step_sampled on the persistent kernel (the rule inside the kernel's LM-head epilogue; k = 40 does
+    not fit its LDS and goes through the sampling kernels) against first_decode_step + first_sample_top_k in a twin
+    context: logits, candidates and tokens bit-identical over free-running steps, and the draw against the oracle."""
+    T = 0.8
+    twins = []
+    for _ in range(2):
+        desc, w, router, ctx = build(model, 73, max_seq_len=96, max_batch=1)
+        ctx.set_option(3, 1)                              # the persistent kernel or an error
+        prompt = make_prompt(desc.vocab, 21, 73)
+        lg = torch.zeros(1, desc.vocab, device="cuda")
+        tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ctx.prefill_route(prompt.cuda(), [len(prompt)], logits=lg, token=tok)
+        twins.append((ctx, lg, tok))
+    (ca, lga, toka), (cb, lgb, tokb) = twins
+    canda = torch.full((1, k), -5, dtype=torch.int32, device="cuda")
+    candb = torch.full((1, k), -5, dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(5)
+    exact = 0
+    for step in range(14):
+        u = torch.tensor([rng.random()], dtype=torch.float32).cuda()
+        with_logits = step % 3 != 2                        # every third step writes no logits on the fused side
+        ca.decode_step_sampled(toka, u, T, k, lga if with_logits else None, toka, canda)
+        cb.decode_step(tokb, lgb, tokb)
+        cb.sample_top_k(lgb, u, T, k, tokb, candb)
+        ca.sync(); cb.sync()
+        if with_logits:
+            assert torch.equal(lga, lgb)
+        assert torch.equal(canda, candb), step
+        assert int(toka[0]) == int(tokb[0]), step
+        exact += _check(lgb[0].cpu().numpy(), float(u[0]), T, k, toka[0].item(), canda[0].cpu().numpy())
+    assert exact >= 12
+    assert ca.seq_len(0) == cb.seq_len(0) == 21 + 14
+    ca.close(); cb.close()
+
+
+def test_sampled_step_on_the_other_paths_and_its_refusals():
+    """Two live sequences (no persistent kernel): the sampled step equals step + sampler; bad arguments are refused and
+    change nothing."""
+    import paper_2410_12513_amd as P
+    twins = []
+    for _ in range(2):
+        desc, w, router, ctx, prompts = _ctx("mini_bf16", B=2, n_prompt=14, seed=79)
+        lg = torch.zeros(2, desc.vocab, device="cuda")
+        tok = torch.zeros(2, dtype=torch.int32, device="cuda")
+        ids = torch.cat([p for p in prompts]).cuda()
+        ctx.prefill_route(ids, [len(p) for p in prompts], logits=lg, token=tok)
+        twins.append((ctx, lg, tok))
+    (ca, lga, toka), (cb, lgb, tokb) = twins
+    canda = torch.zeros(2, 10, dtype=torch.int32, device="cuda"); candb = torch.zeros_like(canda)
+    rng = np.random.default_rng(9)
+    for step in range(6):
+        u = torch.tensor(rng.random(2), dtype=torch.float32).cuda()
+        ca.decode_step_sampled(toka, u, 0.8, 10, lga if step % 2 == 0 else None, toka, canda)
+        cb.decode_step(tokb, lgb, tokb)
+        cb.sample_top_k(lgb, u, 0.8, 10, tokb, candb)
+        ca.sync(); cb.sync()
+        assert torch.equal(canda, candb) and torch.equal(toka, tokb)
+    before = ca.seq_len(0)
+    u = torch.zeros(2, device="cuda")
+    for T, k in ((0.0, 10), (float("nan"), 10), (0.8, 0), (0.8, 65)):
+        with pytest.raises(P.FirstError) as e:
+            ca.decode_step_sampled(toka, u, T, k, lga, toka)
+        assert e.value.code == -1
+    assert ca.seq_len(0) == before
+    ca.close(); cb.close()
