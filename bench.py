@@ -120,35 +120,36 @@ def main():
     if args.sample:
         # same mask, the paper's decoding rule instead of greedy, the sampled token feeds the next step: once as part of
         # the step (first_decode_step_sampled: inside the persistent kernel), once as first_sample_top_k on the logits
-        # of a greedy step
+        # of a greedy step, and greedy under the same conditions.  Launched directly, not through a captured graph: the
+        # address of each step's uniform number is an argument of the launch.
         k = L - head["kept_layers"]
         gen = torch.Generator(device="cpu").manual_seed(seed)
         uni = torch.rand(W + K, generator=gen).cuda()
-        u = torch.zeros(1, device="cuda")                  # (one buffer: its address is part of the captured step)
         scratch = torch.zeros(1, dtype=torch.int32, device="cuda")
         times = {}
-        for mode in ("in_step", "separate"):
+        ctx.set_option(1, 0)                               # USE_GRAPH off
+        for mode in ("greedy", "in_step", "separate"):
             ctx.prefill_route(prompt, [n_prompt], token=tok)
             ctx.set_mask(0, [0] * L if k >= L else make_skip_mask(L, k, seed).tolist())
             for i in range(W + K):
                 if i == W:
                     ctx.sync()
                     ev0.record(stream)
-                with torch.cuda.stream(stream):
-                    u.copy_(uni[i:i + 1], non_blocking=True)
                 if mode == "in_step":
-                    ctx.decode_step_sampled(tok, u, 0.8, 10, None, tok)
-                else:
+                    ctx.decode_step_sampled(tok, uni[i:i + 1], 0.8, 10, None, tok)
+                elif mode == "separate":
                     ctx.decode_step(tok, logits, scratch)
-                    ctx.sample_top_k(logits, u, 0.8, 10, tok)
+                    ctx.sample_top_k(logits, uni[i:i + 1], 0.8, 10, tok)
+                else:
+                    ctx.decode_step(tok, None, tok)
             ev1.record(stream)
             ev1.synchronize()
             times[mode] = ev0.elapsed_time(ev1) / K
+        ctx.set_option(1, 0 if args.no_graph else 1)
         ms = times["in_step"]
         sampled = {"temperature": 0.8, "top_k": 10, "kept_layers": head["kept_layers"], "ms_per_step": ms,
-                   "tokens_per_s": 1000.0 / ms, "greedy_ms_per_step": head["ms_per_step"],
-                   "ms_per_step_separate_sampling_kernels": times["separate"],
-                   "note": "each step includes a 4-byte device copy of the caller's uniform number"}
+                   "tokens_per_s": 1000.0 / ms, "greedy_ms_per_step": times["greedy"],
+                   "ms_per_step_separate_sampling_kernels": times["separate"], "launch": "direct (no graph)"}
 
     train = None
     if args.train_forward:

@@ -148,6 +148,29 @@ __device__ __forceinline__ float wave_sum_lane63(float v) {
   v = dpp_add<0x143, 0xc>(v);    // row_bcast31 into rows 2 and 3
   return v;
 }
+// The first candidate of a wave in the sampling order (larger logit, then lower token index; sample_kernels.h), the same
+// in every lane, through the same DPP paths: the pair travels as a 64-bit key whose unsigned order is that order.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void dpp_first(unsigned& hi, unsigned& lo) {
+  const unsigned oh = (unsigned)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, ROW_MASK, 0xf, false);
+  const unsigned ol = (unsigned)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, ROW_MASK, 0xf, false);
+  const bool take = oh > hi || (oh == hi && ol > lo);
+  hi = take ? oh : hi;
+  lo = take ? ol : lo;
+}
+__device__ __forceinline__ Cand wave_first(const Cand& c) {
+  const unsigned u = __float_as_uint(c.v + 0.0f);                       // (-0 and +0 are one logit)
+  unsigned hi = u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u), lo = ~(unsigned)c.i;
+  dpp_first<0xB1, 0xf>(hi, lo);      // quad_perm [1,0,3,2]
+  dpp_first<0x4E, 0xf>(hi, lo);      // quad_perm [2,3,0,1]
+  dpp_first<0x141, 0xf>(hi, lo);     // row_half_mirror
+  dpp_first<0x140, 0xf>(hi, lo);     // row_mirror
+  dpp_first<0x142, 0xa>(hi, lo);     // row_bcast15 into rows 1 and 3
+  dpp_first<0x143, 0xc>(hi, lo);     // row_bcast31 into rows 2 and 3: lane 63 has seen every lane
+  hi = (unsigned)__builtin_amdgcn_readlane((int)hi, 63);
+  lo = (unsigned)__builtin_amdgcn_readlane((int)lo, 63);
+  return Cand{__uint_as_float(hi ^ ((hi >> 31) ? 0x80000000u : 0xffffffffu)), (int)~lo};
+}
 // Waits until every global load and store this wave has issued is complete.
 __device__ __forceinline__ void vm_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void stg_bf16(bf16* p, bf16 v) { *as_global(&p->v) = v.v; }
@@ -1658,11 +1681,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
               const Cand e{lv[r], cur.row0 + r};
               if (cand_before(last, e) && cand_before(e, first)) first = e;
             }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-              const Cand c{__shfl_xor(first.v, o, 64), __shfl_xor(first.i, o, 64)};
-              if (cand_before(c, first)) first = c;
-            }
+            first = wave_first(first);
             if (lane == 0) { st_coh(&dst[k].v, first.v); st_coh(&dst[k].i, first.i); }
             last = first.i == SMP_NONE ? Cand{-INFINITY, SMP_NONE} : first;      // nothing left: nothing comes after
           }
@@ -1720,16 +1739,16 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       const int n = ncu * P.smp_k;
       float* cv = S.xs;
       int* ci = reinterpret_cast<int*>(S.xs) + n;
-      // (two candidates per 16-byte load, eight loads per lane in flight: one memory round trip per 1024 candidates;
+      // (two candidates per 16-byte load, sixteen loads per lane in flight: one memory round trip per 2048 candidates;
       // the list buffer has SMP_KMAX slots per workgroup, so the odd one past the end is there to be read and ignored)
       const float* src = reinterpret_cast<const float*>(P.smp_part);
-      for (int j0 = 0; j0 < n; j0 += 2 * 64 * 8) {
-        f32x4_t q[8];
+      for (int j0 = 0; j0 < n; j0 += 2 * 64 * 16) {
+        f32x4_t q[16];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) coh_issue16(q[t], src + 2 * min(j0 + 2 * (t * 64 + lane), n - 1 + (n & 1) - 1));
+        for (int t = 0; t < 16; ++t) coh_issue16(q[t], src + 2 * min(j0 + 2 * (t * 64 + lane), n - 1 + (n & 1) - 1));
         coh_wait();
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < 16; ++t) {
           coh_use(q[t]);
           const int j = j0 + 2 * (t * 64 + lane);
           if (j < n) { cv[j] = q[t].x; ci[j] = __float_as_int(q[t].y); }
@@ -1752,11 +1771,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
 #pragma unroll
         for (int l = 0; l < SK_SMP_LISTS; ++l)
           if (head[l].i != SMP_NONE && cand_before(head[l], first)) first = head[l];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-          const Cand c{__shfl_xor(first.v, o, 64), __shfl_xor(first.i, o, 64)};
-          if (cand_before(c, first)) first = c;
-        }
+        first = wave_first(first);
         if (lane == 0) top[k] = first;
 #pragma unroll
         for (int l = 0; l < SK_SMP_LISTS; ++l)
