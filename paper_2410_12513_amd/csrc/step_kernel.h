@@ -106,6 +106,8 @@ __device__ __forceinline__ void coh_use(T& v) { asm volatile("" : "+v"(v)); }
 // finish staging a phase's input it needs every workgroup's output of the phase before), and
 // each vector is written at most once per phase, so a reader only ever meets the write it
 // waits for or the one before it.  Relative error of dropping the last mantissa bit: 2^-23.
+// Nothing computes on a tagged word: an infinity with tag 1 is a NaN pattern while it sits in memory and the same
+// infinity again after sk_untag.
 __device__ __forceinline__ float sk_tagged(float v, unsigned bit) {
   return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
 }
