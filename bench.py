@@ -54,6 +54,8 @@ def main():
                     help="also time the headline mask with the paper's decoding rule (temperature 0.8, top-k 10) instead of greedy")
     ap.add_argument("--no-tpot-grid", action="store_true",
                     help="skip the sweep over the paper's skip fractions (random and fixed-interval masks, 8B and 3B-class shapes)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the two batch workloads (cfg4_8b_b16, cfg5_8b_16k) that the default run appends")
     ap.add_argument("--train-forward", action="store_true",
                     help="also time the training-side pieces: soft-skip forward + loss terms over the prompt, LoRA merge of the gate matrices")
     args = ap.parse_args()
@@ -67,7 +69,7 @@ def main():
     wl = WORKLOADS[args.workload]
     desc = CONFIGS[wl["model"]]
     if wl["batch"] > 1:
-        return bench_batch(args, wl, desc)
+        return bench_batch(args, wl, desc, args.workload)
     seed = wl["seed"]
     n_prompt, L = wl["prompt"], desc.n_layers
     K, W = args.steps, args.warmup
@@ -261,6 +263,17 @@ def main():
         "setup_s": {"generate_weights": t_gen},
     }
     ctx.close()
+    if args.workload == "cfg3_8b" and not args.per_op and not args.no_other_workloads:
+        # the two batch workloads, 64 timed steps each, so that one default run carries every configuration
+        del ctx, weights, router
+        torch.cuda.empty_cache()
+        other = []
+        for name in ("cfg4_8b_b16", "cfg5_8b_16k"):
+            r = bench_batch(args, WORKLOADS[name], CONFIGS[WORKLOADS[name]["model"]], name, steps=64, emit=False)
+            other.append({"workload": r["config"]["workload"], "tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                          "steps": r["steps"], "step_bytes": r["roofline"]["bytes_per_launch"], "hbm_frac": r["roofline"]["frac"],
+                          "mean_kept_layers": r["config"]["mean_kept_layers"], "prefill": r["prefill"]})
+        out["other_workloads"] = other
     print(json.dumps(out))
 
 
@@ -355,16 +368,16 @@ def batch_step_bytes(desc, masks, ctx_lens):
     return by, used
 
 
-def bench_batch(args, wl, desc):
+def bench_batch(args, wl, desc, name, steps=None, emit=True):
     """Decode of a batch with one skip mask per sequence (the batch-16 mixed-mask and the batch-4
-    long-context workloads): aggregate tokens/s over all sequences."""
+    long-context workloads): aggregate tokens/s over all sequences.  Prints its JSON line (emit) or returns it."""
     import numpy as np
     import torch
     import paper_2410_12513_amd as P
     from synth import make_prompt, make_router, make_skip_mask, make_weights
 
     seed, B, L = wl["seed"], wl["batch"], desc.n_layers
-    K, W = min(args.steps, wl["decode"]), args.warmup
+    K, W = min(steps or args.steps, wl["decode"]), args.warmup
     rng = np.random.Generator(np.random.PCG64(seed))
     if isinstance(wl["prompt"], tuple):
         lens = [int(x) for x in rng.integers(wl["prompt"][0], wl["prompt"][1] + 1, size=B)]
@@ -410,7 +423,7 @@ def bench_batch(args, wl, desc):
         "value": B * 1000.0 / ms, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if desc.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {wl['model']} Llama-style decoder, batch {B}, prompts {min(lens)}..{max(lens)} "
+        "config": {"workload": f"{name}: {wl['model']} Llama-style decoder, batch {B}, prompts {min(lens)}..{max(lens)} "
                                f"tokens, skipped layers per sequence {min(skips)}..{max(skips)} of {L}",
                    "layers_kept_by_some_sequence": used, "mean_kept_layers": sum(sum(m) for m in masks) / B,
                    "kv_page_tokens": 16, "decode_path": "one pass per sequence" if args.per_op else "shared pass per layer"},
@@ -421,6 +434,10 @@ def bench_batch(args, wl, desc):
         "cpu_baseline": None,
     }
     ctx.close()
+    del ctx, weights, router, logits, prompts
+    torch.cuda.empty_cache()
+    if not emit:
+        return out
     print(json.dumps(out))
 
 

@@ -56,7 +56,7 @@ def test_prefill_route_matches_oracle(model):
     st = O.prefill_route(desc, w, router, prompt)
     got = _prefill(ctx, desc, [prompt])
     # router probabilities and the cached decisions
-    assert float((got["rho"][0] - st.rho).abs().max()) <= (1e-3 if desc.dtype == "bf16" else 2e-6)   # margin of the routers is 2e-3
+    assert float((got["rho"][0] - st.rho).abs().max()) <= (5e-4 if desc.dtype == "bf16" else 2e-6)   # (measured: up to 3.1e-4 at the 8B shape; the routers keep a margin of 2e-3)
     assert got["mask"][0].tolist() == st.mask.tolist()
     assert ctx.get_kept(0) == O.compact_kept(st.mask)
     assert ctx.seq_len(0) == prompt.numel()
