@@ -174,3 +174,41 @@ def test_cfg4_8b_b16_full_size_sampled_sequences():
         assert ctx.seq_len(b) == lens[b] + n_steps
         assert ctx.get_kept(b) == O.compact_kept(masks[b])
     ctx.close()
+
+
+def test_sampled_step_at_the_8b_shape():
+    """The decoding rule inside the persistent kernel at the benchmark's shape (256 workgroups, about 500 rows of the LM
+    head each, top-k 10 at temperature 0.8): candidates and token against the sampling oracle applied to the step's own
+    logits, and against first_sample_top_k on them."""
+    import numpy as np
+    import paper_2410_12513_amd as P
+    from oracle import sampling as S
+    desc = CONFIGS["8b"]
+    wg = make_weights(desc, 11, device="cuda")
+    rg = make_router(desc, 11, device="cuda")
+    prompt = make_prompt(desc.vocab, 96, 11)
+    ctx = P.FirstContext(desc, wg, rg, max_batch=1, max_seq_len=160, stream=torch.cuda.Stream())
+    ctx.set_option(3, 1)
+    logits = torch.zeros(1, desc.vocab, device="cuda")
+    tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tok2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cand = torch.zeros(1, 10, dtype=torch.int32, device="cuda")
+    cand2 = torch.zeros(1, 10, dtype=torch.int32, device="cuda")
+    ctx.prefill_route(prompt.cuda(), [96], token=tok)
+    ctx.set_mask(0, make_skip_mask(desc.n_layers, 8, 11).tolist())
+    rng = np.random.default_rng(3)
+    exact = 0
+    for step in range(6):
+        u = torch.tensor([rng.random()], dtype=torch.float32).cuda()
+        ctx.decode_step_sampled(tok, u, 0.8, 10, logits, tok, cand)
+        ctx.sample_top_k(logits, u, 0.8, 10, tok2, cand2)
+        ctx.sync()
+        lg = logits[0].cpu().numpy()
+        want = S.top_k_candidates(lg, 10)
+        assert [int(x) for x in cand[0].cpu()] == want
+        assert torch.equal(cand, cand2) and int(tok[0]) == int(tok2[0])
+        if S.decision_margin(lg, float(u[0]), 0.8, 10) > 1e-5:
+            assert int(tok[0]) == S.sample_top_k(lg, float(u[0]), 0.8, 10, np.float32)
+            exact += 1
+    assert exact >= 5
+    ctx.close()
