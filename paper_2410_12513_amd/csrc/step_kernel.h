@@ -381,6 +381,52 @@ __device__ __forceinline__ bool sk_stage_norm_wave(float* xs, const float* x, in
   return true;
 }
 
+// One wave's share of staging a normed input for K <= 4096 (gains in LDS): the groups of eight values wave * 64 + lane,
+// + 512, ... .  All eight waves of the workgroup take part - between two phases the streaming waves have nothing else
+// to do, and one wave alone spends most of a microsecond on the 64 values per lane that follow the poll.  The wave
+// re-reads its words until they carry tag `bit`, writes gain * x into xs - NOT yet divided by the root mean square,
+// which nobody knows before every wave is through - and returns its sum of squares; the phase's results are scaled
+// instead (sk_norm_scale).  Returns false if the wait gives up.
+__device__ __forceinline__ bool sk_stage_norm_slice(float* xs, const float* x, int K, const float* gs, unsigned bit,
+                                                    int* err, int wave, float& ssq) {
+  const int lane = sk_lane_opaque(), ngroups = K >> 3, plane = sk_plane(K);
+  float ss = 0.f;
+  unsigned spins = 0;
+  for (int g0 = wave * 64; g0 < ngroups; g0 += SK_WAVES * 64) {
+    const int g = g0 + lane, gc = min(g, ngroups - 1);       // (lanes past the end re-read the last group)
+    f32x4_t a, b;
+    for (;;) {
+      int e = 0;
+      coh_issue16(a, x + (gc << 3));
+      coh_issue16(b, x + (gc << 3) + 4);
+      coh_issue4(e, err);
+      coh_wait();
+      coh_use(a); coh_use(b); coh_use(e);
+      SkTags t;
+      t.add(a); t.add(b);
+      if (__all(t.good(bit))) break;
+      if (sk_poll_give_up(spins, uni(e), err)) return false;
+    }
+    if (g < ngroups) {
+      a = sk_untag(a); b = sk_untag(b);
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+      const f32x4_t ga = *reinterpret_cast<const f32x4_t*>(gs + (g << 2));
+      const f32x4_t gb = *reinterpret_cast<const f32x4_t*>(gs + plane + (g << 2));
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = a * ga;
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = b * gb;
+    }
+  }
+  ssq = wave_sum(ss);
+  return true;
+}
+// 1 / rms of the vector the eight waves staged (their sums of squares in red[0..8), added in wave order).
+__device__ __forceinline__ float sk_norm_scale(const float* red, int K, float eps) {
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < SK_WAVES; ++w) t += red[w];
+  return 1.0f / sqrtf(t / (float)K + eps);
+}
+
 // xs <- x or RMSNorm(x; gain), in the two-plane layout the 8-wide weight vectors read.
 // Executed by ONE wave (the service wave).  x was written by other workgroups in this
 // kernel: coherent 16-byte loads, 16 requested per lane before each wait (more in flight per
@@ -1548,6 +1594,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   // The two roles run separate loops (so that the service wave carries no ring registers and the streaming waves no
   // staging registers) with the same sequence of workgroup barriers.
   if (service) {
+    if (lane == 0) { S.flag[12] = 1; S.flag[13] = 1; }      // verdicts of the streaming waves' shares of staging, by phase parity
     lds_barrier();                                 // the rotation table is in LDS
     // RMSNorm gains of the next phase that has a norm: constants, fetched while the phase before streams so that they
     // are not in the way when the phase's input arrives
@@ -1588,7 +1635,11 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           __hip_atomic_store(S.flag + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
       } else if (fast_norm) {
-        staged_ok = sk_stage_norm_wave<true>(S.xs, h, D, S.gs, p.eps, tag_h, P.err);
+        // (every wave of the workgroup stages a share: see sk_stage_norm_slice; the streaming waves report to flag[12 + parity])
+        float ssq = 0.f;
+        staged_ok = sk_stage_norm_slice(S.xs, h, D, S.gs, tag_h, P.err, wave, ssq);
+        if (lane == 0) S.red[wave] = ssq;
+        sk_zero_pad(S.xs, D);
       } else {
         staged_ok = sk_stage_wave<true>(S.xs, h, D, cur.gain, p.eps, tag_h, P.err);
       }
@@ -1596,7 +1647,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       if (cur.kind == SEG_GU && lane < SK_WAVES) S.flag[4 + lane] = 0;     // (rounds finished: counted from the barrier below)
       SK_STAMP(3);
       lds_barrier();                               // input vector staged; verdict of the wait visible
-      if (!staged_ok) return;
+      if (!staged_ok || uni(S.flag[12 + (s & 1)]) == 0) return;
+      if (lane == 0) S.flag[12 + ((s + 1) & 1)] = 1;       // (the next phase's word: nobody looks at it before the next barrier but one)
+      // a normed input staged by all waves still lacks its 1 / rms: the phase's results are scaled by it
+      const float rs = fast_norm ? sk_norm_scale(S.red, D, p.eps) : 1.0f;
       const SegDesc nx = seg_desc(P, s + 1, nk, kept, share, share_o);
       if (cur.kind == SEG_QKV || cur.kind == SEG_GU) {
         // every word of h has just been seen current: fetch the rows the next phase of this workgroup adds to
@@ -1627,7 +1681,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
             __builtin_amdgcn_s_sleep(8);
           }
           for (int r = lane; r < cs; r += 64) {
-            const float gt = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r), up = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r + 1);
+            const float gt = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r) * rs, up = seg_row_sum(S.psum, cur, k * cur.bl + 2 * r + 1) * rs;
             st_coh(z + k * SK_SEG + cs * cu + r, sk_tagged(siluf(gt) * up, tag_z));
           }
           if (k >= 1 && k + 1 < nblk) {               // (not behind the last block: the down projection is waiting for this wave)
@@ -1646,7 +1700,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         float* out = p.qkv + (size_t)b * (nq + 2 * nkv);
         tag_q ^= 1u;
         for (int r = lane; r < cur.nrows; r += 64) {
-          const float v = seg_row_sum(S.psum, cur, r);
+          const float v = seg_row_sum(S.psum, cur, r) * rs;
           st_coh(out + cur.row0 + r, sk_tagged(v, tag_q));
         }
       } else if (cur.kind == SEG_O || cur.kind == SEG_DN) {
@@ -1660,7 +1714,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         float* z = p.z + (size_t)b * F;
         tag_z ^= 1u;
         for (int r = lane; r < cur.nrows / 2; r += 64) {
-          const float gt = seg_row_sum(S.psum, cur, 2 * r), up = seg_row_sum(S.psum, cur, 2 * r + 1);
+          const float gt = seg_row_sum(S.psum, cur, 2 * r) * rs, up = seg_row_sum(S.psum, cur, 2 * r + 1) * rs;
           st_coh(z + cur.row0 / 2 + r, sk_tagged(siluf(gt) * up, tag_z));
         }
       } else if (cur.kind == SEG_HEAD) {
@@ -1671,7 +1725,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           // has streamed).  Workgroup 0 merges the lists the same way below.
           float* lv = S.xs;
           for (int r = lane; r < cur.nrows; r += 64) {
-            const float v = seg_row_sum(S.psum, cur, r);
+            const float v = seg_row_sum(S.psum, cur, r) * rs;
             if (lg) lg[cur.row0 + r] = v;
             lv[r] = v;
           }
@@ -1691,7 +1745,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         } else {
         Best best{-INFINITY, 0x7fffffff};
         for (int r = lane; r < cur.nrows; r += 64) {
-          const float v = seg_row_sum(S.psum, cur, r);
+          const float v = seg_row_sum(S.psum, cur, r) * rs;
           if (lg) lg[cur.row0 + r] = v;
           const Best c{v, cur.row0 + r};
           if (better(c, best)) best = c;
@@ -1827,8 +1881,13 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // (a workgroup without attention work waits for the attention of the others: see sk_prefetch; every wave of an
       // attention workgroup is awaited at that workgroup's own barriers, so those do not linger)
       if (cur.kind == SEG_O && !attn_wg) sk_prefetch(nxt, SK_PF_ROUNDS, wave);
+      if (cur.gain != nullptr && D <= 4096) {      // this wave's share of the phase's normed input (sk_stage_norm_slice)
+        float ssq = 0.f;
+        const bool ok = sk_stage_norm_slice(S.xs, h, D, S.gs, tag_h, P.err, wave, ssq);
+        if (lane == 0) { S.red[wave] = ssq; if (!ok) S.flag[12 + (s & 1)] = 0; }
+      }
       lds_barrier();                               // input vector staged
-      if (uni(*S.flag) == 0) return;
+      if (uni(*S.flag) == 0 || uni(S.flag[12 + (s & 1)]) == 0) return;
       // all blocks but the last request ahead inside this segment; the last one requests the first rounds of the
       // next segment (no per-round choice between the two descriptors)
       const int last0 = cur.nr_pad - SK_PD;
@@ -1851,6 +1910,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
         sk_issue(nxt, j, ahead, wave, buf[j]);
       }
       lds_barrier();                               // partial sums complete
+      if (cur.kind == SEG_O || cur.kind == SEG_DN) tag_h ^= 1u;     // (the service wave is writing h with the other tag now)
       cur = nxt;
     }
   }
