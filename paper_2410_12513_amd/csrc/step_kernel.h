@@ -419,6 +419,32 @@ __device__ __forceinline__ bool sk_stage_norm_slice(float* xs, const float* x, i
   ssq = wave_sum(ss);
   return true;
 }
+// The same for an input without a norm (the attention output): the wave's groups of x into xs, untagged.
+__device__ __forceinline__ bool sk_stage_plain_slice(float* xs, const float* x, int K, unsigned bit, int* err, int wave) {
+  const int lane = sk_lane_opaque(), ngroups = K >> 3, plane = sk_plane(K);
+  unsigned spins = 0;
+  for (int g0 = wave * 64; g0 < ngroups; g0 += SK_WAVES * 64) {
+    const int g = g0 + lane, gc = min(g, ngroups - 1);
+    f32x4_t a, b;
+    for (;;) {
+      int e = 0;
+      coh_issue16(a, x + (gc << 3));
+      coh_issue16(b, x + (gc << 3) + 4);
+      coh_issue4(e, err);
+      coh_wait();
+      coh_use(a); coh_use(b); coh_use(e);
+      SkTags t;
+      t.add(a); t.add(b);
+      if (__all(t.good(bit))) break;
+      if (sk_poll_give_up(spins, uni(e), err)) return false;
+    }
+    if (g < ngroups) {
+      *reinterpret_cast<f32x4_t*>(xs + (g << 2)) = sk_untag(a);
+      *reinterpret_cast<f32x4_t*>(xs + plane + (g << 2)) = sk_untag(b);
+    }
+  }
+  return true;
+}
 // 1 / rms of the vector the eight waves staged (their sums of squares in red[0..8), added in wave order).
 __device__ __forceinline__ float sk_norm_scale(const float* red, int K, float eps) {
   float t = 0.f;
@@ -1624,8 +1650,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
           staged_ok = sk_attn_merge_head<HD>(P, S, A, tag_a, stamps);
         }
         SK_STAMP(2);
-        if (cur.nrows > 0)
-          staged_ok = sk_stage_wave<true>(S.xs, p.attn + (size_t)b * nq, nq, nullptr, 0.f, tag_a, P.err) && staged_ok;
+        if (cur.nrows > 0) {                       // (a share of it, like every wave of the workgroup)
+          staged_ok = sk_stage_plain_slice(S.xs, p.attn + (size_t)b * nq, nq, tag_a, P.err, wave) && staged_ok;
+          sk_zero_pad(S.xs, nq);
+        }
       } else if (cur.kind == SEG_DN) {
         // the down projection starts on the first K-segment of its input (already staged during gate/up when that ran
         // in blocks); the rest is staged while it streams (after the workgroup barrier below)
@@ -1866,6 +1894,7 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
     SegDesc cur = seg_desc(P, 0, nk, kept, share, share_o);
     for (int s = 0; s < nsegs; ++s) {
       const float* xsrc = cur.kind == SEG_DN ? S.zs : S.xs;
+      if (cur.kind == SEG_O) tag_a ^= 1u;          // (as the service wave does: the tag the attention output will carry)
       if (cur.kind == SEG_O && attn_wg) {
         // (a wave that takes tiles has nothing of the ring in flight here: its registers hold the keys and values)
         unsigned long long* stamps = (P.tdbg && cu == 0) ? P.tdbg + s * SK_TSLOTS : nullptr;
@@ -1881,6 +1910,10 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
       // (a workgroup without attention work waits for the attention of the others: see sk_prefetch; every wave of an
       // attention workgroup is awaited at that workgroup's own barriers, so those do not linger)
       if (cur.kind == SEG_O && !attn_wg) sk_prefetch(nxt, SK_PF_ROUNDS, wave);
+      if (cur.kind == SEG_O && cur.nrows > 0) {    // this wave's share of the attention output
+        const bool ok = sk_stage_plain_slice(S.xs, p.attn + (size_t)b * nq, nq, tag_a, P.err, wave);
+        if (lane == 0 && !ok) S.flag[12 + (s & 1)] = 0;
+      }
       if (cur.gain != nullptr && D <= 4096) {      // this wave's share of the phase's normed input (sk_stage_norm_slice)
         float ssq = 0.f;
         const bool ok = sk_stage_norm_slice(S.xs, h, D, S.gs, tag_h, P.err, wave, ssq);
