@@ -598,7 +598,7 @@ bool step_kernel_fits(const first_ctx* c) {
   const int ncu = c->num_cu;
   if (d.n_q_heads > ncu || d.d_ffn > 16384 || d.d_model > 64 * ncu || d.d_model > 16384 || c->nq > 16384) return false;   // (one residual row per service-wave lane)
   if ((long long)std::max({d.vocab, 2 * d.d_ffn, c->nq + 2 * c->nkv}) * (ncu + 1) >= (1LL << 31)) return false;
-  // (the output projection's rows may sit on half of the workgroups, at most 64 rows each)
+  // (one residual row per service-wave lane: at most 64 rows of the output / down projection per workgroup)
   auto units = [&](long long rows, int K) { return (int)((rows + ncu - 1) / ncu + 2) * ((K + SK_SEG - 1) / SK_SEG); };
   const int worst = std::max({units(d.vocab, d.d_model), units(c->nq + 2 * c->nkv, d.d_model), 66 * ((c->nq + SK_SEG - 1) / SK_SEG),
                               units(2LL * d.d_ffn, d.d_model), units(d.d_model, d.d_ffn)});

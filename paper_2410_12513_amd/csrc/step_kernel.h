@@ -1541,11 +1541,12 @@ __global__ void __launch_bounds__(WG) k_permute_down_columns(const bf16* __restr
 // stages it into LDS.  It never has weight loads in flight, which matters because a wave's loads return in order: a
 // poll or an input load issued behind a prefetch queue would wait for all of it.
 //
-// Who does what in the attention + output-projection phase.  With Hq x nsplit <= half the grid (short contexts) the
-// first Hq x nsplit workgroups compute attention and own NO rows of the output projection; the others own all of them
-// and have their first rounds in the ring when the attention output arrives.  The attention workgroups have no weight loads in flight meanwhile
-// (their ring registers hold the key and value tiles) and go on to request the gate/up rows as soon as their part of
-// attention is done.  With long contexts every workgroup computes attention and the projection's rows are dealt evenly.
+// Who does what in the attention + output-projection phase.  The first Hq x nsplit workgroups compute attention (their
+// tile waves have no weight loads in flight meanwhile: the ring registers hold the key and value tiles), the others touch
+// gate/up weights ahead (sk_prefetch); the output projection's rows are dealt evenly over all of them, like every other
+// phase's.  (Keeping its rows off the attention workgroups when those are at most half the grid - so that the others
+// could hold them ready - was worth something with a deep ring; with two rounds in flight it measured 0.7 to 2 % slower
+// at contexts below 200 keys, where it applied, and is gone.)
 //
 // The residual rows a workgroup updates in the output and down projections are fetched by its service wave right
 // after it has staged the phase before (QKV or gate/up), when it has seen every word of h current.
@@ -1579,11 +1580,8 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   const int n_attn = p.Hq * nsplit;
   const bool attn_wg = cu < n_attn;
   const SkAttnGeo A = sk_attn_geo(p, attn_wg ? cu : 0, nsplit, tps, pos);
-  // output projection: rows on the workgroups that have no attention work when those are at least half the grid and
-  // enough for one residual row per service-wave lane
-  const int o_first = (2 * n_attn <= ncu && (ncu - n_attn) * 64 >= D) ? n_attn : 0;
   const SkShare share{cu * 1024, (cu + 1) * 1024, ncu};
-  const SkShare share_o{cu >= o_first ? (cu - o_first) * 1024 : 0, cu >= o_first ? (cu - o_first + 1) * 1024 : 0, ncu - o_first};
+  const SkShare share_o = share;                   // (the output projection's rows: dealt like all others)
 
 #define SK_STAMP(slot)                                                                 \
   do {                                                                                 \
