@@ -1,7 +1,6 @@
 // Whole decode step of one sequence as ONE persistent kernel (bf16 models, batch 1): one 512-thread workgroup per
-// compute unit (256 VGPRs per lane for deep prefetch).  Seven waves of a workgroup only stream weights through a ring of
-// in-flight loads that runs on across phase boundaries; the eighth (the service wave) turns partial sums into outputs and
-// stages the next phase's input.  Workgroups hand activations to each other as self-validating ("tagged") words, so no
+// compute unit.  Seven waves of a workgroup stream weights through a short ring of in-flight loads that runs on across
+// phase boundaries; the eighth (the service wave) turns partial sums into outputs; all eight stage the next phase's input.  Workgroups hand activations to each other as self-validating ("tagged") words, so no
 // grid barrier separates the phases.  Kept-layer indices are read from the device-side compaction, so a skipped layer
 // costs neither a launch nor a byte (Section 4.3 item 2).
 #pragma once
@@ -52,7 +51,7 @@ __device__ __forceinline__ uint4 ld_global16(const void* p) {
 __device__ __forceinline__ float ldg(const float* p) { return *as_global(p); }
 
 // Activations exchanged between workgroups inside the kernel are written and read with
-// device-scope (cache-coherent) accesses, so that the grid barrier needs no cache flushes:
+// device-scope (cache-coherent) accesses, so that no cache has to be flushed or invalidated:
 // the L2 of each XCD is not coherent with the others for ordinary loads and stores.
 __device__ __forceinline__ float ld_coh(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
