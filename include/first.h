@@ -63,6 +63,11 @@ extern "C" {
                                       read the caller's row-major matrices */
 #define FIRST_OPT_PREFILL_ATTN  7  /* prompt attention.  1 (default): tiled kernel on the matrix cores when the cache is bf16
                                       and head_dim is 64 or 128, else the plain kernel; 0: always the plain fp32 kernel */
+#define FIRST_OPT_STEP_POLL_LIMIT 10 /* test tap: value >= 0 = the number of unsuccessful polls after which a wait between workgroups of
+                                      the persistent kernel gives up (default, or -1: 2^21, seconds).  With 0 the next decode step
+                                      gives up at its first exchange: every wave leaves at its next wait, nothing hangs, and the next
+                                      call that synchronises (first_sync, first_seq_len, ...) returns FIRST_ERR_HIP, clears the limit
+                                      and resets the exchange state; the live sequences must be prefilled again.  Synchronises. */
 #define FIRST_OPT_BATCH_PATH    6  /* decode with several live sequences.  -1 (default): per layer, the sequences that
                                       keep it share one pass over its weights (bf16 models, widths multiples of 8),
                                       else one pass per sequence; 0: always one pass per sequence; 1: shared pass or error */

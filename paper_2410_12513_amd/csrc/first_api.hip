@@ -255,7 +255,7 @@ void drop_graphs(first_ctx* c) {
 int check_step_error(first_ctx* c, const char* who) {
   int err = 0;
   HIPCHK(c, hipMemcpy(&err, c->d_err, sizeof(int), hipMemcpyDeviceToHost));
-  if (err) {
+  if (err & 1) {                                   // (the bits above bit 0: a poll limit set by FIRST_OPT_STEP_POLL_LIMIT, gone with the error)
     (void)hipMemset(c->d_err, 0, 4 * sizeof(int));
     (void)reset_tagged_exchange(c);
     return fail(c, FIRST_ERR_HIP, std::string(who) + ": a wait between workgroups of the persistent decode kernel gave up; "
@@ -1256,6 +1256,13 @@ int first_set_option(first_ctx* c, int32_t option, int32_t value) {
     case FIRST_OPT_BATCH_PATH:
       if (value < -1 || value > 1) return fail(c, FIRST_ERR_ARG, "first_set_option: unknown batch path");
       c->batch_path = value; return FIRST_OK;
+    case FIRST_OPT_STEP_POLL_LIMIT: {
+      if (value < -1 || value > (1 << 29)) return fail(c, FIRST_ERR_ARG, "first_set_option: poll limit out of range");
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      const int word = value < 0 ? 0 : (value + 1) << 1;
+      HIPCHK(c, hipMemcpy(c->d_err, &word, sizeof(int), hipMemcpyHostToDevice));
+      return FIRST_OK;
+    }
     default: return fail(c, FIRST_ERR_ARG, "first_set_option: unknown option");
   }
 }

@@ -122,11 +122,14 @@ struct SkTags {
   __device__ __forceinline__ void add(const f32x4_t& v) { add(v.x); add(v.y); add(v.z); add(v.w); }
   __device__ __forceinline__ bool good(unsigned bit) const { return bit ? (all & 1u) != 0u : (any & 1u) == 0u; }
 };
-// One more failed poll: gives up (and says so in *err) after SK_SPIN_LIMIT polls or when
-// another wave of the grid has given up; e is *err as read together with the poll.
+// One more failed poll: gives up (and says so in *err) after the limit of polls or when another wave of the grid has
+// given up; e is *err as read together with the poll.  Bit 0 of *err: somebody gave up.  The bits above it, if not zero:
+// the limit + 1 for this launch instead of SK_SPIN_LIMIT - what a test writes to see the kernel give up and every wave
+// leave in an orderly way, without anything having to go wrong first.
 __device__ __forceinline__ bool sk_poll_give_up(unsigned& spins, int e, int* err) {
-  if (++spins <= SK_SPIN_LIMIT && e == 0) { __builtin_amdgcn_s_sleep(2); return false; }
-  __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned limit = ((unsigned)e >> 1) != 0u ? ((unsigned)e >> 1) - 1u : SK_SPIN_LIMIT;
+  if (++spins <= limit && (e & 1) == 0) { __builtin_amdgcn_s_sleep(2); return false; }
+  __hip_atomic_fetch_or(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return true;
 }
 __device__ __forceinline__ void coh_issue4(int& v, const int* p) {

@@ -167,3 +167,42 @@ def test_step_kernel_long_run_is_reproducible_and_never_gives_up():
         streams.append(hist.cpu())
         ctx.close()
     assert torch.equal(streams[0], streams[1])
+
+
+@pytest.mark.parametrize("model,n_prompt", [("step_hd128", 150), ("step_hd64", 700)])
+def test_step_kernel_gives_up_in_an_orderly_way_and_recovers(model, n_prompt):
+    """A wait between workgroups that gives up: forced from the host with a poll limit of 0 (every first unsuccessful poll
+    gives up), so nothing has to go wrong for it.  Every wave leaves, the launch ends, the next synchronising call
+    reports the error once and resets the exchange state; after a new prefill the context decodes exactly what an
+    untouched twin decodes."""
+    import paper_2410_12513_amd as P
+    prompt = make_prompt(CONFIGS[model].vocab, n_prompt, 57)
+    outs = []
+    for provoke in (False, True):
+        desc, w, router, ctx = build(model, 57, max_seq_len=n_prompt + 40)
+        ctx.set_option(OPT_DECODE_PATH, 1)
+        got = _prefill(ctx, desc, [prompt])
+        tok = got["token"].to(torch.int32).cuda()
+        if provoke:
+            for use_graph in (1, 0):
+                ctx.set_option(1, use_graph)
+                ctx.set_option(10, 0)                     # STEP_POLL_LIMIT: give up at the first unsuccessful poll
+                ctx.decode_step(tok, None, tok.clone())
+                with pytest.raises(P.FirstError) as e:
+                    ctx.sync()
+                assert e.value.code == -4 and "gave up" in str(e.value)
+                ctx.sync()                                # reported once; the limit went with the error
+                got = _prefill(ctx, desc, [prompt])
+                tok = got["token"].to(torch.int32).cuda()
+            ctx.set_option(1, 1)
+        lg = torch.zeros(1, desc.vocab, device="cuda")
+        hist = []
+        for s in range(12):
+            ctx.decode_step(tok, lg, tok)
+            ctx.sync()
+            hist.append((int(tok[0]), lg.clone()))
+        outs.append(hist)
+        assert ctx.seq_len(0) == n_prompt + 12
+        ctx.close()
+    for (ta, la), (tb, lb) in zip(*outs):
+        assert ta == tb and torch.equal(la, lb)
