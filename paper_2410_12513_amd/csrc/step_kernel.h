@@ -1621,13 +1621,14 @@ __global__ void __launch_bounds__(SK_THREADS) k_step(StepParams P) {
   // staging registers) with the same sequence of workgroup barriers.
   if (service) {
     if (lane == 0) { S.flag[12] = 1; S.flag[13] = 1; }      // verdicts of the streaming waves' shares of staging, by phase parity
-    lds_barrier();                                 // the rotation table is in LDS
     // RMSNorm gains of the next phase that has a norm: constants, fetched while the phase before streams so that they
-    // are not in the way when the phase's input arrives
+    // are not in the way when the phase's input arrives.  Those of the first phase: before the barrier, because every
+    // wave of the workgroup reads them as soon as it is past it (sk_stage_norm_slice).
     {
       const SegDesc first = seg_desc(P, 0, nk, kept, share, share_o);
       if (first.gain != nullptr && D <= 4096) sk_gains_to_lds(S.gs, first.gain, D);
     }
+    lds_barrier();                                 // the rotation table and the first gains are in LDS
     float h_prev = 0.f;                            // lane r: residual row row0 + r of the coming output / down projection (tagged word)
     int z_staged = 0;                              // K-segments of the coming down projection's input already in LDS
     // (a phase's descriptor is worked out while the phase before streams: nothing but the wait for the input and its
