@@ -184,7 +184,7 @@ constexpr int AS_NT = 2;                                // tiles per iteration
 constexpr int AS_PT = 1024;                             // page ids of a split kept in LDS: the host gives a split at most AS_PT / 4 tiles
 __host__ __device__ inline size_t as_lds_bytes(int G, int hd) {
   return (size_t)2 * AS_NT * 2 * 64 * hd * 2 +          // [2 buffers][AS_NT][K, V][64][hd] bf16
-         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8 + AS_PT + SK_WAVES * 16 * 4) * sizeof(float);
+         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8 + AS_PT + SK_WAVES * (16 * 4 + 4)) * sizeof(float);
 }
 
 // Reductions over the 16 lanes of a DPP row (quads, half rows, rows): every lane ends up with
@@ -237,7 +237,7 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   int* flag = reinterpret_cast<int*>(fb); fb += 8;
   int* pt_lds = reinterpret_cast<int*>(fb); fb += AS_PT;   // page ids of this split's tiles: a lookup in global memory before every
                                                         // tile request would put a second, dependent round trip into each iteration
-  float* wbuf = fb + (size_t)wave * 16 * 4;             // [16 keys][4 heads] softmax weights of this wave's slice
+  float* wbuf = fb + (size_t)wave * (16 * 4 + 4);       // [16 keys][4 heads] softmax weights of this wave's slice, then the 4 heads' rescale factors
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps), T = max(0, t_last - t_first);
   const int n_it = (T + AS_NT - 1) / AS_NT;
@@ -313,11 +313,12 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   }
   lds_barrier();
 
-  // A operand of the score MFMA: row m = lane % 16 holds query head m % G (the heads repeat down the
-  // 16 rows, so that every group of 16 lanes gets all G heads of its key in its own result registers), k = dims
+  // A operand of the score MFMA: row m = lane % 16 holds query head m / 4, k = dims.  A lane's four result registers
+  // are rows 4 (lane / 16) .. + 3, so the 16 lanes of group g = lane / 16 all hold the scores of head g (one key each):
+  // the four heads' softmax steps run side by side in the four lane groups instead of one after the other in every lane.
   bf16x8_t qh[KS], ql[KS];
   {
-    const int hm = (lane & 15) % G;
+    const int hm = (lane & 15) >> 2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       union { unsigned short u[8]; bf16x8_t v; } H, L;
@@ -333,10 +334,10 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
 
   // per wave: running maximum, sum and weighted values of its 16-key slices, for all G heads;
   // lane (sub = lane / 16, dc = lane % 16) accumulates dims dc*DL .. +DL over keys 4 i + sub
-  float m[G], l[G], o[G][DL];
+  float m1 = -INFINITY, l1 = 0.f;                        // head lane / 16: running maximum and sum
+  float o[G][DL];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    m[h] = -INFINITY; l[h] = 0.f;
 #pragma unroll
     for (int e = 0; e < DL; ++e) o[h][e] = 0.f;
   }
@@ -369,26 +370,28 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
       sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[ks], kb, sc, 0, 0, 0);
       sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[ks], kb, sc, 0, 0, 0);
     }
-    // lane (key = lane % 16, head group = lane / 16) holds heads 4 (lane / 16) + j: G <= 4 lives in lanes 0..15
-    float pj[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      // result rows 4 (lane / 16) + j hold head j: register h of every lane is S[head h][key lane % 16]
-      float sv = sc[h];
-      if (k0 + (lane & 15) >= nkeys) sv = -INFINITY;
+    // lane (key = lane % 16, head = lane / 16): every register of sc is S[head][key]
+    {
+      const bool live = k0 + (lane & 15) < nkeys;
+      const float sv = live ? sc[0] : -INFINITY;
       const float mt = row16_max(sv);
-      const float mn = fmaxf(m[h], mt);
-      const float corr = mn == -INFINITY ? 1.f : expf(m[h] - mn);      // (a slice past the last key, nothing seen yet)
-      const float pv = (k0 + (lane & 15) < nkeys) ? expf(sv - mn) : 0.f;
+      const float mn = fmaxf(m1, mt);
+      const float corr = mn == -INFINITY ? 1.f : expf(m1 - mn);        // (a slice past the last key, nothing seen yet)
+      const float pv = live ? expf(sv - mn) : 0.f;
       const float ls = row16_sum(pv);
-      l[h] = l[h] * corr + ls;
-      m[h] = mn;
+      l1 = l1 * corr + ls;
+      m1 = mn;
+      // the weights go through LDS: lane (sub, dc) needs those of keys 4 i + sub, for all heads
+      wbuf[(lane & 15) * 4 + (lane >> 4)] = pv;
+      if (__any(corr != 1.f)) {                          // (after the first tiles the maxima rarely move: 1.0 would change nothing)
+        if ((lane & 15) == 0) wbuf[64 + (lane >> 4)] = corr;
+        const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(wbuf + 64);
 #pragma unroll
-      for (int e = 0; e < DL; ++e) o[h][e] *= corr;
-      pj[h] = pv;                                      // every lane: weight of key lane % 16 for head h
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int e = 0; e < DL; ++e) o[h][e] *= c4[h];
+      }
     }
-    // the weights go through LDS: lane (sub, dc) needs those of keys 4 i + sub
-    if (lane < 16) *reinterpret_cast<f32x4_t*>(wbuf + lane * 4) = f32x4_t{pj[0], pj[1], pj[2], pj[3]};
     // weighted values: 4 rows per lane group, each value row shared by the G heads
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -403,8 +406,10 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
         vf[c8 * 8 + 4] = __uint_as_float(w.z << 16); vf[c8 * 8 + 5] = __uint_as_float(w.z & 0xffff0000u);
         vf[c8 * 8 + 6] = __uint_as_float(w.w << 16); vf[c8 * 8 + 7] = __uint_as_float(w.w & 0xffff0000u);
       }
+      if (k0 + 15 > pos) {                             // (only the slice that holds the last position has them)
 #pragma unroll
-      for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];          // never-written slots: no NaN patterns
+        for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];        // never-written slots: no NaN patterns
+      }
       const f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(wbuf + kr * 4);   // weights of key kr for the G heads
 #pragma unroll
       for (int h = 0; h < G; ++h) {
@@ -434,7 +439,10 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
 #pragma unroll
       for (int e = 0; e < DL; ++e) mb[dc * DL + e] = o[h][e];
     }
-    if (lane == 0) { mb[HD] = m[h]; mb[HD + 1] = l[h]; }
+  }
+  if ((lane & 15) == 0) {
+    float* mb = mbuf + (size_t)(wave * G + (lane >> 4)) * (HD + 2);
+    mb[HD] = m1; mb[HD + 1] = l1;
   }
   __syncthreads();
   // wave h merges head h over the 8 waves (fixed order) and writes the split's partial
