@@ -73,6 +73,11 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) {
   c.u = v;
   return c.b;
 }
+__device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t v) {
+  union { u32x4_t u; bf16x8_t b; } c;
+  c.u = v;
+  return c.b;
+}
 
 // 1/rms of the norm op's input vectors (length K), one value per slot, computed by a whole wave: lane l ends up
 // with the value of slot l / 4.  Either what k_xsplit stored, or formed from the producer's per-tile-group sums of
@@ -171,20 +176,21 @@ __global__ void __launch_bounds__(AT_THREADS, 4) k_attn_tiles_b(BatchParams P) {
 // head (G = 4 instantiated): k_attn_tiles_b lets every head wave fetch its own copy of each
 // 64-key tile and form scores and weighted values with scalar FMAs, which at long context is
 // bound by the vector ALUs and by G-fold traffic through the compute unit's memory pipeline.
-// Here the workgroup fetches every tile ONCE, cooperatively, into LDS (double-buffered: the
-// two tiles of the next iteration are in flight while these are worked on); a wave takes 16
-// keys of a tile for ALL G heads: scores = Q K^T on the matrix cores (16x16x32 bf16, Q split
-// into high + low halves so that the product with the stored bf16 keys is exact to 2^-16),
-// an online softmax per wave, weighted values with the value rows shared across the heads.
-// The 8 waves' partial results meet in LDS; partial / count / merge across splits and the
-// output format are those of sk_attention<.., SPLIT_OUT>.  One workgroup per compute unit
-// (128 KB of tiles): the host sizes the grid to about one workgroup per compute unit.
+// Here a wave takes 16 keys (one cache page) at a time for ALL G heads and fetches them once,
+// straight into the registers that use them (three pages per wave in flight; see Stage): scores
+// = Q K^T on the matrix cores (16x16x32 bf16, Q split into high + low halves so that the product
+// with the stored bf16 keys is exact to 2^-16), the G heads' online softmax side by side in the
+// four 16-lane groups, weighted values with the value rows shared across the heads.  Between
+// the prologue and the merge no wave waits for another.  The 8 waves' partial results meet in
+// LDS; partial / count / merge across splits and the output format are those of
+// sk_attention<.., SPLIT_OUT>.  The host sizes the grid to about one workgroup per compute unit.
+// (An earlier version relayed 64-key tiles through 128 KB of LDS with a workgroup barrier per
+// pair of tiles: 0.4 % slower steps at 16 k keys.)
 constexpr int AS_THREADS = SK_WAVES * 64;
-constexpr int AS_NT = 2;                                // tiles per iteration
+constexpr int AS_NT = 2;                                // fewest tiles the host gives a split
 constexpr int AS_PT = 1024;                             // page ids of a split kept in LDS: the host gives a split at most AS_PT / 4 tiles
 __host__ __device__ inline size_t as_lds_bytes(int G, int hd) {
-  return (size_t)2 * AS_NT * 2 * 64 * hd * 2 +          // [2 buffers][AS_NT][K, V][64][hd] bf16
-         ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8 + AS_PT + SK_WAVES * (16 * 4 + 4)) * sizeof(float);
+  return ((size_t)G * hd + 2 * hd + hd + (size_t)SK_WAVES * G * (hd + 2) + 8 + AS_PT + SK_WAVES * (16 * 4 + 4)) * sizeof(float);
 }
 
 // Reductions over the 16 lanes of a DPP row (quads, half rows, rows): every lane ends up with
@@ -206,7 +212,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 template <int HD, int G>
 __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
-  static_assert(HD == 128 && G == 4, "lane layouts below: 8 value dims per lane, the 4 heads repeat down the 16 score rows");
+  static_assert(HD == 128 && G == 4, "lane layouts below: 8 value dims per lane, one head per group of four score rows");
   extern __shared__ __align__(16) float smem_f[];
   DecParams p = P.d;
   const bool listed = P.attn_nwork > 0;
@@ -215,9 +221,6 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   const int slot = listed ? work_slot : (int)blockIdx.z;
   p.b = P.seqs.id[slot];
   constexpr int HALF = HD / 2;
-  constexpr int TILE_E = 64 * HD;                       // elements of one key (or value) tile
-  constexpr int BPT = HD / 64;                          // 8 KB blocks (512 lanes x 16 B) per tile
-  constexpr int NB = AS_NT * 2 * BPT;                   // blocks per iteration
   constexpr int KS = HD / 32;                           // MFMA k-steps over the head dimension
   constexpr int DL = HD / 16;                           // value dims per lane: lane (sub, dc), dc = lane % 16
   const int b = p.b, Pg = p.P, g = listed ? blockIdx.x : blockIdx.y;
@@ -227,8 +230,7 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   const int s = listed ? work_split : (int)blockIdx.x;
   if (s >= nsplit) return;
   // LDS carve-up
-  bf16* tile_lds = reinterpret_cast<bf16*>(smem_f);
-  float* fb = smem_f + (size_t)2 * AS_NT * 2 * TILE_E / 2;
+  float* fb = smem_f;
   float* qs = fb; fb += G * HD;
   float* knew = fb; fb += HD;
   float* vnew = fb; fb += HD;
@@ -240,7 +242,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   float* wbuf = fb + (size_t)wave * (16 * 4 + 4);       // [16 keys][4 heads] softmax weights of this wave's slice, then the 4 heads' rescale factors
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps), T = max(0, t_last - t_first);
-  const int n_it = (T + AS_NT - 1) / AS_NT;
+  // slices of 16 keys (one cache page each): wave w takes the split's slices w, w + 8, ...
+  const int n_sl = max(0, min(4 * t_last, (nkeys + 15) >> 4) - 4 * t_first);
   const int nq = p.Hq * HD, nkv = p.Hkv * HD;
   const float* qkv = p.qkv + (size_t)b * (nq + 2 * nkv);
   const int* pt = p.page_table + (size_t)b * p.max_pages;
@@ -252,31 +255,22 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   for (int i = tid; i < min(T1 * 4, AS_PT); i += AS_THREADS) pt_lds[i] = pt[min(t_first * 4 + i, last_page)];
   lds_barrier();
 
-  // cooperative fetch of the AS_NT key tiles and value tiles of iteration `it` into registers
-  struct Stage { u32x4_t v[NB]; };
-  Stage stage, stage2;                                  // iterations it and it + 1: a request has two iterations to land
-  auto issue = [&](Stage& st, int it) __attribute__((always_inline)) {
+  // A slice's keys and values straight into the registers that use them: for the scores lane (key = lane % 16, kq = lane / 16)
+  // holds dims 32 ks + 8 kq .. + 8 of its key (the B operand of MFMA k-step ks), for the weighted values lane (sub = lane / 16,
+  // dc = lane % 16) holds dims 8 dc .. + 8 of keys 4 i + sub - sixteen 64-byte pieces per key request, four whole rows per
+  // value request.  No wave needs another wave's keys, so nothing goes through LDS and the waves never wait for each other.
+  struct Stage { u32x4_t k[KS], v[4]; };
+  Stage st0, st1, st2;                                  // three slices of this wave in flight
+  auto issue = [&](Stage& st, int j) __attribute__((always_inline)) {
+    const int jj = max(0, min(j, n_sl - 1));             // (past the split: a harmless reload of a valid page)
+    const int pg = pt_lds[min(jj, AS_PT - 1)];
+    const bf16* base = pool + (size_t)pg * p.page_elems + head_off;
 #pragma unroll
-    for (int jb = 0; jb < NB; ++jb) {
-      const int ti = jb / (2 * BPT), rem = jb % (2 * BPT), is_v = rem / BPT, part = rem % BPT;
-      const int tt = max(0, min(it * AS_NT + ti, T1 - 1));                     // past the split: a harmless reload
-      const int t = t_first + tt;
-      const int e = part * 4096 + tid * 8, row = e / HD, col = e % HD;
-      const int key = (t << 6) + row;
-      const int pg = pt_lds[min(tt * 4 + (row >> 4), AS_PT - 1)];            // (pages past the last one were clamped: weight 0)
-      const bf16* src = pool + (size_t)pg * p.page_elems + head_off + (is_v ? v_off : 0) + (size_t)(key & 15) * HD + col;
-      st.v[jb] = *reinterpret_cast<const u32x4_t*>(src);
-    }
-  };
-  // (blocks are stored in fetch order: block jb = (tile, key or value, part) lands at jb * 4096 elements,
-  //  which is exactly [tile][K, V][64][HD]; constant register indices keep the staging array out of memory)
-  auto stash = [&](const Stage& st, int it) __attribute__((always_inline)) {
-    bf16* buf = tile_lds + (size_t)(it & 1) * AS_NT * 2 * TILE_E + tid * 8;
-    static_assert(NB == 8, "written out for 8 blocks");
-    *reinterpret_cast<u32x4_t*>(buf + 0 * 4096) = st.v[0]; *reinterpret_cast<u32x4_t*>(buf + 1 * 4096) = st.v[1];
-    *reinterpret_cast<u32x4_t*>(buf + 2 * 4096) = st.v[2]; *reinterpret_cast<u32x4_t*>(buf + 3 * 4096) = st.v[3];
-    *reinterpret_cast<u32x4_t*>(buf + 4 * 4096) = st.v[4]; *reinterpret_cast<u32x4_t*>(buf + 5 * 4096) = st.v[5];
-    *reinterpret_cast<u32x4_t*>(buf + 6 * 4096) = st.v[6]; *reinterpret_cast<u32x4_t*>(buf + 7 * 4096) = st.v[7];
+    for (int ks = 0; ks < KS; ++ks)
+      st.k[ks] = *reinterpret_cast<const u32x4_t*>(base + (lane & 15) * HD + ks * 32 + ((lane >> 4) << 3));
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      st.v[i] = *reinterpret_cast<const u32x4_t*>(base + v_off + (4 * i + (lane >> 4)) * HD + (lane & 15) * DL);
   };
 
   // this step's q (G heads), k and v of the KV head (requested before the tiles: loads return in order)
@@ -287,8 +281,9 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
     const float k1 = qkv[nq + g * HD + dk], k2 = qkv[nq + g * HD + dk + HALF];
     const float vv = qkv[nq + nkv + g * HD + dv];
     const float2 c_own = p.rope_cs[(size_t)b * HALF + min(tid, HALF - 1)];               // made by k_embed_b
-    issue(stage, 0);                                    // (a split without tiles reloads a valid one and ignores it)
-    issue(stage2, min(1, max(n_it - 1, 0)));
+    issue(st0, wave);                                   // (a wave without slices reloads a valid page and ignores it)
+    issue(st1, wave + SK_WAVES);
+    issue(st2, wave + 2 * SK_WAVES);
     if (tid < HALF) cs[tid] = c_own;
     lds_barrier();
     if (tid < G * HALF) {                              // rotate and pre-scale the queries
@@ -341,87 +336,97 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
 #pragma unroll
     for (int e = 0; e < DL; ++e) o[h][e] = 0.f;
   }
-  const int ti = wave >> 2, quarter = wave & 3, sub = lane >> 4, dc = lane & 15;
+  const int sub = lane >> 4, dc = lane & 15;
+  const int new_sl = (pos >> 4) - 4 * t_first;          // the slice that holds the new position (if this split owns it)
 
-  auto iteration = [&](Stage& st, int it) __attribute__((always_inline)) {
-    stash(st, it);                                     // (waits for the loads of this iteration)
-    issue(st, min(it + 2, n_it - 1));                  // (the last iterations reload their own tiles: branch-free, ignored)
-    lds_barrier();                                     // tiles of `it` are in LDS; everyone has left the buffer of `it - 1`
-    bf16* tk = tile_lds + (size_t)(it & 1) * AS_NT * 2 * TILE_E + (size_t)(ti * 2) * TILE_E;
-    bf16* tv = tk + TILE_E;
-    const int t = t_first + it * AS_NT + ti;
-    if (owns_new && t == (pos >> 6)) {                 // the new position's row comes from this step, not from the cache
-      const int r = pos & 63;
-      if (quarter == 0) {
-        for (int d = lane; d < HD; d += 64) {
-          tk[r * HD + d].v = (uint16_t)__float_as_uint(knew[d]);
-          tv[r * HD + d].v = (uint16_t)__float_as_uint(vnew[d]);
+  auto slice = [&](Stage& st, int j) __attribute__((always_inline)) {
+    if (j < n_sl) {
+      const int k0 = (4 * t_first + j) << 4;             // first key of the slice
+      if (owns_new && j == new_sl) {                     // the new position's row comes from this step, not from the cache
+        const int r = pos & 15;
+        if ((lane & 15) == r) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            unsigned w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int d = ks * 32 + ((lane >> 4) << 3) + 2 * e;
+              w[e] = (__float_as_uint(knew[d]) & 0xffffu) | (__float_as_uint(knew[d + 1]) << 16);
+            }
+            st.k[ks] = u32x4_t{w[0], w[1], w[2], w[3]};
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (4 * i + sub == r) {
+            unsigned w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              w[e] = (__float_as_uint(vnew[dc * DL + 2 * e]) & 0xffffu) | (__float_as_uint(vnew[dc * DL + 2 * e + 1]) << 16);
+            st.v[i] = u32x4_t{w[0], w[1], w[2], w[3]};
+          }
+      }
+      // scores: C[row = head][col = key]
+      f32x4v_t sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t kb = as_bf16x8(st.k[ks]);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[ks], kb, sc, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[ks], kb, sc, 0, 0, 0);
+      }
+      // lane (key = lane % 16, head = lane / 16): every register of sc is S[head][key]
+      {
+        const bool live = k0 + (lane & 15) < nkeys;
+        const float sv = live ? sc[0] : -INFINITY;
+        const float mt = row16_max(sv);
+        const float mn = fmaxf(m1, mt);
+        const float corr = mn == -INFINITY ? 1.f : expf(m1 - mn);        // (nothing seen yet)
+        const float pv = live ? expf(sv - mn) : 0.f;
+        const float ls = row16_sum(pv);
+        l1 = l1 * corr + ls;
+        m1 = mn;
+        // the weights go through LDS: lane (sub, dc) needs those of keys 4 i + sub, for all heads
+        wbuf[(lane & 15) * 4 + (lane >> 4)] = pv;
+        if (__any(corr != 1.f)) {                          // (after the first slices the maxima rarely move: 1.0 would change nothing)
+          if ((lane & 15) == 0) wbuf[64 + (lane >> 4)] = corr;
+          const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(wbuf + 64);
+#pragma unroll
+          for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int e = 0; e < DL; ++e) o[h][e] *= c4[h];
+        }
+      }
+      // weighted values: 4 rows per lane group, each value row shared by the G heads
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int kr = 4 * i + sub;                      // key of this lane within the slice
+        const int key = k0 + kr;
+        const u32x4_t w = st.v[i];
+        float vf[DL];
+        vf[0] = __uint_as_float(w.x << 16); vf[1] = __uint_as_float(w.x & 0xffff0000u);
+        vf[2] = __uint_as_float(w.y << 16); vf[3] = __uint_as_float(w.y & 0xffff0000u);
+        vf[4] = __uint_as_float(w.z << 16); vf[5] = __uint_as_float(w.z & 0xffff0000u);
+        vf[6] = __uint_as_float(w.w << 16); vf[7] = __uint_as_float(w.w & 0xffff0000u);
+        if (k0 + 15 > pos) {                             // (only the slice that holds the last position has them)
+#pragma unroll
+          for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];        // never-written slots: no NaN patterns
+        }
+        const f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(wbuf + kr * 4);   // weights of key kr for the G heads
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const float wt = w4[h];
+#pragma unroll
+          for (int e = 0; e < DL; ++e) o[h][e] = fmaf(wt, vf[e], o[h][e]);
         }
       }
     }
-    if (owns_new) lds_barrier();                       // (the row is written by one wave of the tile and read by all four)
-    if (t >= t_last) return;
-    const int k0 = (t << 6) + quarter * 16;            // first key of this wave's slice
-    // scores: C[row = head][col = key]
-    f32x4v_t sc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8_t kb = *reinterpret_cast<const bf16x8_t*>(tk + (quarter * 16 + (lane & 15)) * HD + ks * 32 + ((lane >> 4) << 3));
-      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qh[ks], kb, sc, 0, 0, 0);
-      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ql[ks], kb, sc, 0, 0, 0);
-    }
-    // lane (key = lane % 16, head = lane / 16): every register of sc is S[head][key]
-    {
-      const bool live = k0 + (lane & 15) < nkeys;
-      const float sv = live ? sc[0] : -INFINITY;
-      const float mt = row16_max(sv);
-      const float mn = fmaxf(m1, mt);
-      const float corr = mn == -INFINITY ? 1.f : expf(m1 - mn);        // (a slice past the last key, nothing seen yet)
-      const float pv = live ? expf(sv - mn) : 0.f;
-      const float ls = row16_sum(pv);
-      l1 = l1 * corr + ls;
-      m1 = mn;
-      // the weights go through LDS: lane (sub, dc) needs those of keys 4 i + sub, for all heads
-      wbuf[(lane & 15) * 4 + (lane >> 4)] = pv;
-      if (__any(corr != 1.f)) {                          // (after the first tiles the maxima rarely move: 1.0 would change nothing)
-        if ((lane & 15) == 0) wbuf[64 + (lane >> 4)] = corr;
-        const f32x4_t c4 = *reinterpret_cast<const f32x4_t*>(wbuf + 64);
-#pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-          for (int e = 0; e < DL; ++e) o[h][e] *= c4[h];
-      }
-    }
-    // weighted values: 4 rows per lane group, each value row shared by the G heads
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int kr = 4 * i + sub;                      // key of this lane within the slice
-      const int key = k0 + kr;
-      float vf[DL];
-#pragma unroll
-      for (int c8 = 0; c8 < DL / 8; ++c8) {
-        const uint4 w = *reinterpret_cast<const uint4*>(tv + (quarter * 16 + kr) * HD + dc * DL + c8 * 8);
-        vf[c8 * 8 + 0] = __uint_as_float(w.x << 16); vf[c8 * 8 + 1] = __uint_as_float(w.x & 0xffff0000u);
-        vf[c8 * 8 + 2] = __uint_as_float(w.y << 16); vf[c8 * 8 + 3] = __uint_as_float(w.y & 0xffff0000u);
-        vf[c8 * 8 + 4] = __uint_as_float(w.z << 16); vf[c8 * 8 + 5] = __uint_as_float(w.z & 0xffff0000u);
-        vf[c8 * 8 + 6] = __uint_as_float(w.w << 16); vf[c8 * 8 + 7] = __uint_as_float(w.w & 0xffff0000u);
-      }
-      if (k0 + 15 > pos) {                             // (only the slice that holds the last position has them)
-#pragma unroll
-        for (int e = 0; e < DL; ++e) vf[e] = key > pos ? 0.f : vf[e];        // never-written slots: no NaN patterns
-      }
-      const f32x4_t w4 = *reinterpret_cast<const f32x4_t*>(wbuf + kr * 4);   // weights of key kr for the G heads
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float w = w4[h];
-#pragma unroll
-        for (int e = 0; e < DL; ++e) o[h][e] = fmaf(w, vf[e], o[h][e]);
-      }
-    }
+    issue(st, j + 3 * SK_WAVES);
   };
-  for (int it = 0; it < n_it; it += 2) {
-    iteration(stage, it);
-    if (it + 1 < n_it) iteration(stage2, it + 1);
+  static_assert(DL == 8, "one 16-byte value load per lane and key");
+  for (int j = wave; j < n_sl; j += 3 * SK_WAVES) {
+    slice(st0, j);
+    slice(st1, j + SK_WAVES);
+    slice(st2, j + 2 * SK_WAVES);
   }
 
   // fold the key subgroups (lanes sub = 0..3), then every wave leaves its partial per head in LDS

@@ -942,8 +942,6 @@ int first_create(const first_model_desc* desc, const first_weights* w, void* hip
     if (e == hipSuccess) e = hipMemset(c->d_mask, 0, (size_t)B * L);
     if (e == hipSuccess) e = hipMemset(c->d_page_table, 0, (size_t)B * c->max_pages * sizeof(int));
     // the prefill attention kernels stage more than 64 KB of LDS for head_dim 128
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_mfma_b<128, 4>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, bf16>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_prefill<float, float>),
