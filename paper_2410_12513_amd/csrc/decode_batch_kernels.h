@@ -237,8 +237,8 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
   float2* cs = reinterpret_cast<float2*>(fb); fb += HD;
   float* mbuf = fb; fb += SK_WAVES * G * (HD + 2);      // [wave][head][HD dims, max, sum]
   int* flag = reinterpret_cast<int*>(fb); fb += 8;
-  int* pt_lds = reinterpret_cast<int*>(fb); fb += AS_PT;   // page ids of this split's tiles: a lookup in global memory before every
-                                                        // tile request would put a second, dependent round trip into each iteration
+  int* pt_lds = reinterpret_cast<int*>(fb); fb += AS_PT;   // page ids of this split's slices: a lookup in global memory before every
+                                                        // page request would put a second, dependent round trip in front of each
   float* wbuf = fb + (size_t)wave * (16 * 4 + 4);       // [16 keys][4 heads] softmax weights of this wave's slice, then the 4 heads' rescale factors
   const int tps = (tiles + nsplit - 1) / nsplit;
   const int t_first = s * tps, t_last = min(tiles, t_first + tps), T = max(0, t_last - t_first);
@@ -273,7 +273,7 @@ __global__ void __launch_bounds__(AS_THREADS) k_attn_mfma_b(BatchParams P) {
       st.v[i] = *reinterpret_cast<const u32x4_t*>(base + v_off + (4 * i + (lane >> 4)) * HD + (lane & 15) * DL);
   };
 
-  // this step's q (G heads), k and v of the KV head (requested before the tiles: loads return in order)
+  // this step's q (G heads), k and v of the KV head (requested before the pages: loads return in order)
   {
     const int iq = min(tid, G * HALF - 1), hh = iq / HALF, dq = iq - hh * HALF;
     const int dk = min(tid, HALF - 1), dv = min(tid, HD - 1);
